@@ -1,0 +1,202 @@
+/*
+ * mpt -- the hot path of one mixed-precision training step on AMD MI355X (gfx950).
+ *
+ * Method: "Mixed Precision Training", arXiv 1710.03740.  Tensors are stored in
+ * IEEE binary16; dot products accumulate in FP32 and round once to FP16 on
+ * store (Sec. 3.3); the loss is scaled by S so that small gradients survive the
+ * FP16 store, weight gradients are unscaled by 1/S before the update and an
+ * Inf/NaN among them makes the step a no-op (Sec. 3.2); the optimizer updates an
+ * FP32 master copy of the weights, which is rounded to FP16 for the next
+ * iteration (Sec. 3.1); a dynamic policy raises or lowers S (Sec. 5).
+ *
+ * Conventions for EVERY entry point unless stated otherwise
+ *   - Pointers named *_dev or documented "device" are DEVICE pointers owned by
+ *     the caller.  The library never allocates, retains or frees memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls only enqueue work on it and never synchronise.
+ *   - FP16 data is passed as uint16_t (IEEE binary16 bit patterns).
+ *   - Matrices are row-major; `ld*` is the element stride between rows and must
+ *     be >= the row length.
+ *   - Return value: MPT_OK (0) or a negative mpt_status.  Arguments are checked
+ *     before anything is enqueued; on error nothing has been enqueued.
+ *   - Inputs are never modified.  Outputs are fully overwritten unless the
+ *     entry point says "accumulate" or "no-op when flagged".
+ *   - FP16 stores round to nearest even and overflow to Inf (no saturation).
+ */
+#ifndef MPT_H
+#define MPT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum mpt_status {
+  MPT_OK = 0,
+  MPT_ERR_NULL = -1,      /* a required pointer is NULL */
+  MPT_ERR_SHAPE = -2,     /* a size is < 1, a leading dimension is too small, or a size exceeds the supported maximum */
+  MPT_ERR_ALIGN = -3,     /* a pointer is not aligned to its element type */
+  MPT_ERR_WORKSPACE = -4, /* workspace given but smaller than mpt_gemm_workspace_bytes() */
+  MPT_ERR_ARG = -5,       /* a scalar argument is out of range (e.g. non-finite or non-positive scale) */
+  MPT_ERR_HIP = -6        /* the HIP runtime refused the launch */
+} mpt_status;
+
+/* Static string for a status code.  Never NULL. */
+const char* mpt_status_string(int status);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int mpt_version(void);
+
+/* ------------------------------------------------------------------------- *
+ * Dense contractions (Sec. 3.3: FP16 products, FP32 accumulation, one RNE
+ * rounding to FP16 on store; Sec. 3.1 / Fig. 1: forward, backward-activation
+ * and backward-weight of a layer).  X[M,K] activations, W[K,N] weights,
+ * Y[M,N] outputs, dY[M,N] upstream gradient.  Any M,N,K >= 1 (each < 2^31 and
+ * every matrix below 2^31 elements per operand row span).  Fast path: base pointers 16-byte aligned
+ * and leading dimensions multiples of 8; anything else (2-byte alignment is the
+ * minimum) takes a slower element-wise loader with identical results.
+ *
+ * Workspace: split-reduction needs FP32 partials in caller memory.  Pass
+ * ws_dev = NULL, ws_bytes = 0 to forbid splitting (always legal), or a device
+ * buffer of at least mpt_gemm_workspace_bytes(op, M, N, K) bytes, 16-byte
+ * aligned.  Partials are summed in a fixed order (results are run-to-run
+ * deterministic) and rounded once.
+ * ------------------------------------------------------------------------- */
+typedef enum mpt_gemm_op { MPT_OP_FWD = 0, MPT_OP_DGRAD = 1, MPT_OP_WGRAD = 2 } mpt_gemm_op;
+
+size_t mpt_gemm_workspace_bytes(int op, int64_t M, int64_t N, int64_t K);
+
+/* Y[m,n] = rne16( sum_k X[m,k] * W[k,n] ) */
+int mpt_gemm_fwd(void* stream, int64_t M, int64_t N, int64_t K,
+                 const uint16_t* X_dev, int64_t ldx,
+                 const uint16_t* W_dev, int64_t ldw,
+                 uint16_t* Y_dev, int64_t ldy,
+                 void* ws_dev, size_t ws_bytes);
+
+/* dX[m,k] = rne16( sum_n dY[m,n] * W[k,n] ) */
+int mpt_gemm_dgrad(void* stream, int64_t M, int64_t N, int64_t K,
+                   const uint16_t* dY_dev, int64_t ldy,
+                   const uint16_t* W_dev, int64_t ldw,
+                   uint16_t* dX_dev, int64_t ldx,
+                   void* ws_dev, size_t ws_bytes);
+
+/* dW[k,n] = sum_m X[m,k] * dY[m,n].
+ *   out_fp32 = 0: dW_dev is uint16_t*, FP16 store (the paper's stored weight gradient); accumulate must be 0.
+ *   out_fp32 = 1: dW_dev is float*, FP32 store; accumulate = 1 adds this call's sum to the buffer's
+ *                 current contents (per-timestep contributions never pass through FP16).
+ *   flag_dev (nullable, device uint32_t): when given, 1 is OR-ed into it if any stored element is Inf/NaN
+ *                 (Sec. 3.2's overflow test folded into the producer; never cleared here). */
+int mpt_gemm_wgrad(void* stream, int64_t M, int64_t N, int64_t K,
+                   const uint16_t* X_dev, int64_t ldx,
+                   const uint16_t* dY_dev, int64_t ldy,
+                   void* dW_dev, int64_t lddw,
+                   int out_fp32, int accumulate, uint32_t* flag_dev,
+                   void* ws_dev, size_t ws_bytes);
+
+/* ------------------------------------------------------------------------- *
+ * 3x3 convolution, stride 1, zero padding 1, as an implicit GEMM (Sec. 3.3 and
+ * Sec. 4 list convolutions among the FP32-accumulated dot products).
+ * x[Nb,H,W,C] NHWC, w[Kf,3,3,C] KRSC, y/dy[Nb,H,W,Kf]; all dense, 16-byte
+ * aligned, C and Kf multiples of 8.  Cross-correlation (no filter flip):
+ *   y [n,p,q,k] = rne16( sum_{r,s,c} x[n,p+r-1,q+s-1,c] * w[k,r,s,c] )
+ *   dx[n,h,v,c] = rne16( sum_{r,s,k} dy[n,h-r+1,v-s+1,k] * w[k,r,s,c] )
+ *   dw[k,r,s,c] = rne16( sum_{n,p,q} dy[n,p,q,k] * x[n,p+r-1,q+s-1,c] )
+ * Workspace as for the GEMMs, sized by mpt_conv3x3_workspace_bytes().
+ * ------------------------------------------------------------------------- */
+size_t mpt_conv3x3_workspace_bytes(int op, int64_t Nb, int64_t H, int64_t W, int64_t C, int64_t Kf);
+
+int mpt_conv3x3_fwd(void* stream, int64_t Nb, int64_t H, int64_t W, int64_t C, int64_t Kf,
+                    const uint16_t* x_dev, const uint16_t* w_dev, uint16_t* y_dev,
+                    void* ws_dev, size_t ws_bytes);
+int mpt_conv3x3_dgrad(void* stream, int64_t Nb, int64_t H, int64_t W, int64_t C, int64_t Kf,
+                      const uint16_t* dy_dev, const uint16_t* w_dev, uint16_t* dx_dev,
+                      void* ws_dev, size_t ws_bytes);
+int mpt_conv3x3_wgrad(void* stream, int64_t Nb, int64_t H, int64_t W, int64_t C, int64_t Kf,
+                      const uint16_t* x_dev, const uint16_t* dy_dev, uint16_t* dw_dev,
+                      uint32_t* flag_dev, void* ws_dev, size_t ws_bytes);
+
+/* ------------------------------------------------------------------------- *
+ * Loss-scale state (Sec. 5 sketches the dynamic policy and fixes no constants).
+ * Policy: on overflow scale *= backoff, good_steps = 0; otherwise good_steps += 1
+ * and when it reaches growth_interval: scale *= growth, good_steps = 0.  scale is
+ * clamped to [min_scale, max_scale]; inv_scale = 1/scale in FP32.
+ * The struct may live in host memory (mpt_loss_scale_update) or in device memory
+ * (mpt_loss_scale_update_dev); layout is fixed, 32 bytes.
+ * ------------------------------------------------------------------------- */
+typedef struct mpt_scaler {
+  float scale;
+  float inv_scale;
+  int32_t good_steps;
+  int32_t growth_interval;
+  float growth;
+  float backoff;
+  float min_scale;
+  float max_scale;
+} mpt_scaler;
+
+/* Fill *s (host memory): given initial scale and interval, growth 2, backoff 1/2, clamps [1, 2^24]. */
+int mpt_scaler_init(mpt_scaler* s, float scale, int32_t growth_interval);
+
+/* Host-side policy step on a host-resident struct.  overflow != 0 means the step was skipped. */
+int mpt_loss_scale_update(mpt_scaler* s, int overflow);
+
+/* Device-side policy step: one tiny kernel reads *flag_dev, applies the policy to
+ * *s_dev (device memory, 4-byte aligned) and clears *flag_dev, so a training step
+ * needs no host synchronisation. */
+int mpt_loss_scale_update_dev(void* stream, mpt_scaler* s_dev, uint32_t* flag_dev);
+
+/* ------------------------------------------------------------------------- *
+ * Unscale + overflow check (Sec. 3.2: gradients are unscaled before the update;
+ * overflow is detected by inspecting the weight gradients).
+ *   flag |= any_i( grad[i] is Inf or NaN )         (tested on the stored bits)
+ *   g32_out[i] = float(grad[i]) * inv_scale          (only when g32_out_dev != NULL)
+ * grad_dev: n elements, uint16_t (grad_is_fp32 = 0) or float (grad_is_fp32 = 1).
+ * flag_dev: device uint32_t, OR-ed into (the caller, or
+ * mpt_loss_scale_update_dev, clears it).  n = 0 is a legal no-op.
+ * inv_scale must be finite and > 0.
+ * ------------------------------------------------------------------------- */
+int mpt_unscale_check(void* stream, const void* grad_dev, int grad_is_fp32, size_t n,
+                      float inv_scale, float* g32_out_dev, uint32_t* flag_dev);
+
+/* ------------------------------------------------------------------------- *
+ * FP32 master update + FP16 working copy (Sec. 3.1), skipped on overflow
+ * (Sec. 3.2).  Each step is one separately rounded IEEE FP32 operation:
+ *   g  = float(grad) * inv_scale
+ *   m' = momentum * m + g ;  w' = w - lr * m'       (m32_dev != NULL)
+ *        w' = w - lr * g                            (m32_dev == NULL, plain SGD)
+ *   w16' = rne16(w')
+ * In place on w32_dev / m32_dev; w16_dev is overwritten.
+ * flag_dev (nullable): if *flag_dev != 0 when the kernel runs, the call is a
+ * no-op: master, momentum and FP16 copy keep their bits.
+ * scaler_dev (nullable): when given, inv_scale is read from scaler_dev->inv_scale
+ * on the device and the inv_scale argument is ignored.
+ * n = 0 is a legal no-op.  lr and momentum must be finite; inv_scale finite, > 0.
+ * ------------------------------------------------------------------------- */
+int mpt_master_update(void* stream, size_t n, float* w32_dev, float* m32_dev,
+                      const void* grad_dev, int grad_is_fp32, uint16_t* w16_dev,
+                      float inv_scale, const mpt_scaler* scaler_dev,
+                      float lr, float momentum, const uint32_t* flag_dev);
+
+/* ------------------------------------------------------------------------- *
+ * Pointwise / reduction glue for a whole step on the device (Sec. 3.3: softmax
+ * reduces in FP32 with FP16 input and output; non-linearities are pointwise).
+ *   relu_fwd:  h[i]  = max(y[i], 0)
+ *   relu_bwd:  dy[i] = y[i] > 0 ? dh[i] : 0
+ *   softmax_xent_scaled: p = softmax(logits[b,:]);
+ *       loss_dev[0] = mean_b -log p[b,label_b]            (FP32; nullable)
+ *       dlogits[b,c] = rne16( scale * (p[b,c] - [c==label_b]) / B )
+ *     which applies Sec. 3.2's loss scale at the head of back-propagation.
+ *     labels_dev: int32, each in [0, C).  C <= 4096.
+ * ------------------------------------------------------------------------- */
+int mpt_relu_fwd(void* stream, size_t n, const uint16_t* y_dev, uint16_t* h_dev);
+int mpt_relu_bwd(void* stream, size_t n, const uint16_t* dh_dev, const uint16_t* y_dev, uint16_t* dy_dev);
+int mpt_softmax_xent_scaled(void* stream, int64_t B, int64_t C,
+                            const uint16_t* logits_dev, int64_t ldl, const int32_t* labels_dev,
+                            float scale, float* loss_dev, uint16_t* dlogits_dev, int64_t ldd);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MPT_H */

@@ -19,7 +19,7 @@ def _pad(a):
     return np.pad(a, ((0, 0), (1, 1), (1, 1), (0, 0)))
 
 
-def conv3x3_fwd(x16, w16):
+def conv3x3_fwd(x16, w16, full=False):
     x, w = to_f64(x16), to_f64(w16)
     Nb, H, W, C = x.shape
     Kf = w.shape[0]
@@ -31,10 +31,10 @@ def conv3x3_fwd(x16, w16):
         for s in range(3):
             y += xp[:, r:r + H, s:s + W, :] @ w[:, r, s, :].T
             sabs += ap[:, r:r + H, s:s + W, :] @ np.abs(w[:, r, s, :]).T
-    return rne16(y), sabs
+    return (rne16(y), sabs, y) if full else (rne16(y), sabs)
 
 
-def conv3x3_dgrad(dy16, w16):
+def conv3x3_dgrad(dy16, w16, full=False):
     dy, w = to_f64(dy16), to_f64(w16)
     Nb, H, W, Kf = dy.shape
     C = w.shape[3]
@@ -47,10 +47,10 @@ def conv3x3_dgrad(dy16, w16):
             # dy index h-r+1 in padded coordinates is h + (2-r)
             dx += dp[:, 2 - r:2 - r + H, 2 - s:2 - s + W, :] @ w[:, r, s, :]
             sabs += ap[:, 2 - r:2 - r + H, 2 - s:2 - s + W, :] @ np.abs(w[:, r, s, :])
-    return rne16(dx), sabs
+    return (rne16(dx), sabs, dx) if full else (rne16(dx), sabs)
 
 
-def conv3x3_wgrad(x16, dy16):
+def conv3x3_wgrad(x16, dy16, full=False):
     x, dy = to_f64(x16), to_f64(dy16)
     Nb, H, W, C = x.shape
     Kf = dy.shape[3]
@@ -63,7 +63,7 @@ def conv3x3_wgrad(x16, dy16):
         for s in range(3):
             dw[:, r, s, :] = d2.T @ xp[:, r:r + H, s:s + W, :].reshape(-1, C)
             sabs[:, r, s, :] = a2.T @ ap[:, r:r + H, s:s + W, :].reshape(-1, C)
-    return rne16(dw), sabs
+    return (rne16(dw), sabs, dw) if full else (rne16(dw), sabs)
 
 
 # ---- explicit-loop definitions (tiny inputs only) ----

@@ -13,7 +13,8 @@ the weight gradients so that Sec. 3.2's check can see it.
 
 Row-major shapes: X[M,K] activations, W[K,N] weights, Y[M,N], dY[M,N].
 Each routine also returns sabs = sum |a*b| per output, the scale against which
-FP32 accumulation error of a real kernel is judged.
+FP32 accumulation error of a real kernel is judged; with full=True it returns
+the unrounded FP64 sum as a third value.
 """
 import numpy as np
 from .fp16 import rne16, to_f64
@@ -25,19 +26,23 @@ def _contract(A, B):
         return A @ B, np.abs(A) @ np.abs(B)
 
 
-def gemm_fwd(X16, W16):
+def _ret(s, sabs, full):
+    return (rne16(s), sabs, s) if full else (rne16(s), sabs)
+
+
+def gemm_fwd(X16, W16, full=False):
     """Y[m,n] = rne16(sum_k X[m,k] W[k,n])."""
     s, sabs = _contract(to_f64(X16), to_f64(W16))
-    return rne16(s), sabs
+    return _ret(s, sabs, full)
 
 
-def gemm_dgrad(dY16, W16):
+def gemm_dgrad(dY16, W16, full=False):
     """dX[m,k] = rne16(sum_n dY[m,n] W[k,n])."""
     s, sabs = _contract(to_f64(dY16), to_f64(W16).T)
-    return rne16(s), sabs
+    return _ret(s, sabs, full)
 
 
-def gemm_wgrad(X16, dY16, out_fp32=False, acc32=None):
+def gemm_wgrad(X16, dY16, out_fp32=False, acc32=None, full=False):
     """dW[k,n] = sum_m X[m,k] dY[m,n].
 
     out_fp32=False: FP16 store (the paper's stored weight gradient).
@@ -48,10 +53,12 @@ def gemm_wgrad(X16, dY16, out_fp32=False, acc32=None):
     s, sabs = _contract(to_f64(X16).T, to_f64(dY16))
     if not out_fp32:
         assert acc32 is None
-        return rne16(s), sabs
+        return _ret(s, sabs, full)
     if acc32 is not None:
         s = s + np.asarray(acc32, dtype=np.float32).astype(np.float64)
-    return s.astype(np.float32), sabs
+    with np.errstate(over="ignore"):
+        out = s.astype(np.float32)
+    return (out, sabs, s) if full else (out, sabs)
 
 
 # ---- the same three definitions as explicit loops (tiny inputs only) ----

@@ -1,0 +1,217 @@
+"""ctypes binding for libmpt.so: argument marshalling only.
+
+Each function has the name of the C entry point it calls (include/mpt.h) and
+takes torch CUDA tensors purely as carriers of device pointers; torch's current
+stream is passed as the hipStream_t.  Every step of the method runs in the
+library's kernels.  A missing library is an error, never a fallback.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmpt.so")
+
+OP_FWD, OP_DGRAD, OP_WGRAD = 0, 1, 2
+
+c_i64, c_sz, c_f, c_i, c_vp = ctypes.c_int64, ctypes.c_size_t, ctypes.c_float, ctypes.c_int, ctypes.c_void_p
+
+
+class MptError(RuntimeError):
+    def __init__(self, fn, status, text):
+        super().__init__("%s failed: %d (%s)" % (fn, status, text))
+        self.status = status
+
+
+class mpt_scaler(ctypes.Structure):
+    _fields_ = [("scale", c_f), ("inv_scale", c_f), ("good_steps", ctypes.c_int32),
+                ("growth_interval", ctypes.c_int32), ("growth", c_f), ("backoff", c_f),
+                ("min_scale", c_f), ("max_scale", c_f)]
+
+
+_GEMM = [c_vp, c_i64, c_i64, c_i64, c_vp, c_i64, c_vp, c_i64, c_vp, c_i64, c_vp, c_sz]
+_CONV = [c_vp, c_i64, c_i64, c_i64, c_i64, c_i64, c_vp, c_vp, c_vp, c_vp, c_sz]
+SIGNATURES = {
+    "mpt_status_string": (ctypes.c_char_p, [c_i]),
+    "mpt_version": (c_i, []),
+    "mpt_gemm_workspace_bytes": (c_sz, [c_i, c_i64, c_i64, c_i64]),
+    "mpt_gemm_fwd": (c_i, _GEMM),
+    "mpt_gemm_dgrad": (c_i, _GEMM),
+    "mpt_gemm_wgrad": (c_i, [c_vp, c_i64, c_i64, c_i64, c_vp, c_i64, c_vp, c_i64, c_vp, c_i64, c_i, c_i, c_vp, c_vp, c_sz]),
+    "mpt_conv3x3_workspace_bytes": (c_sz, [c_i, c_i64, c_i64, c_i64, c_i64, c_i64]),
+    "mpt_conv3x3_fwd": (c_i, _CONV),
+    "mpt_conv3x3_dgrad": (c_i, _CONV),
+    "mpt_conv3x3_wgrad": (c_i, [c_vp, c_i64, c_i64, c_i64, c_i64, c_i64, c_vp, c_vp, c_vp, c_vp, c_vp, c_sz]),
+    "mpt_scaler_init": (c_i, [ctypes.POINTER(mpt_scaler), c_f, ctypes.c_int32]),
+    "mpt_loss_scale_update": (c_i, [ctypes.POINTER(mpt_scaler), c_i]),
+    "mpt_loss_scale_update_dev": (c_i, [c_vp, c_vp, c_vp]),
+    "mpt_unscale_check": (c_i, [c_vp, c_vp, c_i, c_sz, c_f, c_vp, c_vp]),
+    "mpt_master_update": (c_i, [c_vp, c_sz, c_vp, c_vp, c_vp, c_i, c_vp, c_f, c_vp, c_f, c_f, c_vp]),
+    "mpt_relu_fwd": (c_i, [c_vp, c_sz, c_vp, c_vp]),
+    "mpt_relu_bwd": (c_i, [c_vp, c_sz, c_vp, c_vp, c_vp]),
+    "mpt_softmax_xent_scaled": (c_i, [c_vp, c_i64, c_i64, c_vp, c_i64, c_vp, c_f, c_vp, c_vp, c_i64]),
+}
+
+_lib = None
+
+
+def lib():
+    """Load libmpt.so (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libmpt.so is not built (%s); run `python -m paper_1710_03740_amd.build`. "
+                               "There is no fallback path." % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            f = getattr(L, name)
+            f.restype, f.argtypes = res, args
+        _lib = L
+    return _lib
+
+
+def _check(fn, st):
+    if st != 0:
+        raise MptError(fn, st, lib().mpt_status_string(st).decode())
+
+
+def _stream():
+    return c_vp(torch.cuda.current_stream().cuda_stream)
+
+
+def _p(t):
+    return c_vp(0) if t is None else c_vp(t.data_ptr())
+
+
+def _dev(*ts):
+    for t in ts:
+        if t is not None and not t.is_cuda:
+            raise ValueError("mpt binding takes device tensors only")
+
+
+def mpt_version():
+    return lib().mpt_version()
+
+
+def mpt_status_string(st):
+    return lib().mpt_status_string(st).decode()
+
+
+# ---------------------------------------------------------------- GEMMs
+def mpt_gemm_workspace_bytes(op, M, N, K):
+    return lib().mpt_gemm_workspace_bytes(op, M, N, K)
+
+
+def _ws(ws):
+    return (_p(ws), c_sz(0 if ws is None else ws.numel() * ws.element_size()))
+
+
+def mpt_gemm_fwd(X, W, Y, ws=None):
+    _dev(X, W, Y, ws)
+    M, K = X.shape
+    N = W.shape[1]
+    p, b = _ws(ws)
+    _check("mpt_gemm_fwd", lib().mpt_gemm_fwd(_stream(), M, N, K, _p(X), X.stride(0), _p(W), W.stride(0), _p(Y), Y.stride(0), p, b))
+
+
+def mpt_gemm_dgrad(dY, W, dX, ws=None):
+    _dev(dY, W, dX, ws)
+    M, N = dY.shape
+    K = W.shape[0]
+    p, b = _ws(ws)
+    _check("mpt_gemm_dgrad", lib().mpt_gemm_dgrad(_stream(), M, N, K, _p(dY), dY.stride(0), _p(W), W.stride(0), _p(dX), dX.stride(0), p, b))
+
+
+def mpt_gemm_wgrad(X, dY, dW, accumulate=False, flag=None, ws=None):
+    _dev(X, dY, dW, flag, ws)
+    M, K = X.shape
+    N = dY.shape[1]
+    out_fp32 = 1 if dW.dtype == torch.float32 else 0
+    p, b = _ws(ws)
+    _check("mpt_gemm_wgrad", lib().mpt_gemm_wgrad(_stream(), M, N, K, _p(X), X.stride(0), _p(dY), dY.stride(0), _p(dW), dW.stride(0),
+                                                  out_fp32, 1 if accumulate else 0, _p(flag), p, b))
+
+
+# ---------------------------------------------------------------- conv
+def mpt_conv3x3_workspace_bytes(op, Nb, H, W, C, Kf):
+    return lib().mpt_conv3x3_workspace_bytes(op, Nb, H, W, C, Kf)
+
+
+def mpt_conv3x3_fwd(x, w, y, ws=None):
+    _dev(x, w, y, ws)
+    Nb, H, W, C = x.shape
+    p, b = _ws(ws)
+    _check("mpt_conv3x3_fwd", lib().mpt_conv3x3_fwd(_stream(), Nb, H, W, C, w.shape[0], _p(x), _p(w), _p(y), p, b))
+
+
+def mpt_conv3x3_dgrad(dy, w, dx, ws=None):
+    _dev(dy, w, dx, ws)
+    Nb, H, W, Kf = dy.shape
+    p, b = _ws(ws)
+    _check("mpt_conv3x3_dgrad", lib().mpt_conv3x3_dgrad(_stream(), Nb, H, W, w.shape[3], Kf, _p(dy), _p(w), _p(dx), p, b))
+
+
+def mpt_conv3x3_wgrad(x, dy, dw, flag=None, ws=None):
+    _dev(x, dy, dw, flag, ws)
+    Nb, H, W, C = x.shape
+    p, b = _ws(ws)
+    _check("mpt_conv3x3_wgrad", lib().mpt_conv3x3_wgrad(_stream(), Nb, H, W, C, dy.shape[3], _p(x), _p(dy), _p(dw), _p(flag), p, b))
+
+
+# ---------------------------------------------------------------- loss-scaled update path
+def mpt_unscale_check(grad, inv_scale, flag, g32_out=None):
+    _dev(grad, flag, g32_out)
+    _check("mpt_unscale_check", lib().mpt_unscale_check(_stream(), _p(grad), 1 if grad.dtype == torch.float32 else 0,
+                                                        grad.numel(), inv_scale, _p(g32_out), _p(flag)))
+
+
+def mpt_master_update(w32, m32, grad, w16, inv_scale, lr, momentum, flag=None, scaler_dev=None):
+    _dev(w32, m32, grad, w16, flag, scaler_dev)
+    _check("mpt_master_update", lib().mpt_master_update(_stream(), w32.numel(), _p(w32), _p(m32), _p(grad),
+                                                        1 if grad.dtype == torch.float32 else 0, _p(w16),
+                                                        inv_scale, _p(scaler_dev), lr, momentum, _p(flag)))
+
+
+def mpt_scaler_init(scale, growth_interval):
+    s = mpt_scaler()
+    _check("mpt_scaler_init", lib().mpt_scaler_init(ctypes.byref(s), scale, growth_interval))
+    return s
+
+
+def mpt_loss_scale_update(s, overflow):
+    _check("mpt_loss_scale_update", lib().mpt_loss_scale_update(ctypes.byref(s), 1 if overflow else 0))
+    return s.scale
+
+
+def mpt_loss_scale_update_dev(scaler_dev, flag):
+    _dev(scaler_dev, flag)
+    _check("mpt_loss_scale_update_dev", lib().mpt_loss_scale_update_dev(_stream(), _p(scaler_dev), _p(flag)))
+
+
+def scaler_to_device(s, device="cuda"):
+    """Copy a host mpt_scaler struct into a fresh 32-byte device buffer."""
+    raw = bytes(s)
+    return torch.frombuffer(bytearray(raw), dtype=torch.uint8).to(device)
+
+
+def scaler_from_device(buf):
+    return mpt_scaler.from_buffer_copy(bytes(buf.cpu().numpy().tobytes()))
+
+
+# ---------------------------------------------------------------- glue
+def mpt_relu_fwd(y, h):
+    _dev(y, h)
+    _check("mpt_relu_fwd", lib().mpt_relu_fwd(_stream(), y.numel(), _p(y), _p(h)))
+
+
+def mpt_relu_bwd(dh, y, dy):
+    _dev(dh, y, dy)
+    _check("mpt_relu_bwd", lib().mpt_relu_bwd(_stream(), y.numel(), _p(dh), _p(y), _p(dy)))
+
+
+def mpt_softmax_xent_scaled(logits, labels, scale, dlogits, loss=None):
+    _dev(logits, labels, dlogits, loss)
+    B, C = logits.shape
+    _check("mpt_softmax_xent_scaled", lib().mpt_softmax_xent_scaled(_stream(), B, C, _p(logits), logits.stride(0), _p(labels),
+                                                                    scale, _p(loss), _p(dlogits), dlogits.stride(0)))

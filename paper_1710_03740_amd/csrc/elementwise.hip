@@ -1,0 +1,461 @@
+// HBM-bound passes of the mixed-precision step for gfx950:
+//   unscale + Inf/NaN check            (paper Sec. 3.2)
+//   FP32 master update + FP16 copy     (paper Sec. 3.1, skip rule Sec. 3.2)
+//   device-side loss-scale policy      (paper Sec. 5)
+//   ReLU, scaled softmax cross-entropy (paper Sec. 3.3 glue)
+// Every thread moves 16-byte vectors; a wavefront therefore touches 1 KiB
+// contiguous per stream per instruction.  Arithmetic is written with the
+// non-contracting intrinsics so each FP32 operation rounds on its own.
+#include "mpt_internal.h"
+#include <stdlib.h>
+
+typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+
+int mpt_env_int(const char* name, int dflt) {
+  const char* v = getenv(name);
+  return v && *v ? atoi(v) : dflt;
+}
+
+namespace {
+
+constexpr int kThreads = 256;
+
+template <bool NT, class T>
+__device__ __forceinline__ T ld(const T* p) {
+  if constexpr (NT) return __builtin_nontemporal_load(p);
+  else return *p;
+}
+template <bool NT, class T>
+__device__ __forceinline__ void st(T* p, T v) {
+  if constexpr (NT) __builtin_nontemporal_store(v, p);
+  else *p = v;
+}
+
+__device__ __forceinline__ bool half_special(uint32_t bits16) { return (bits16 & 0x7C00u) == 0x7C00u; }
+__device__ __forceinline__ bool float_special(uint32_t bits32) { return (bits32 & 0x7F800000u) == 0x7F800000u; }
+
+// One optimizer step on a single element; the order and the separate rounding
+// of the four operations is the contract (no fused multiply-add).
+template <bool MOM>
+__device__ __forceinline__ float step1(float w, float& m, float graw, float inv, float lr, float mu) {
+  const float g = __fmul_rn(graw, inv);
+  float d;
+  if constexpr (MOM) {
+    m = __fadd_rn(__fmul_rn(mu, m), g);
+    d = __fmul_rn(lr, m);
+  } else {
+    d = __fmul_rn(lr, g);
+  }
+  return __fsub_rn(w, d);
+}
+
+// 8 elements per thread per trip: one 16 B gradient load (FP16) or two (FP32),
+// two 16 B loads each of master and momentum, and the mirror-image stores.
+template <bool MOM, bool G32, bool NT>
+__global__ __launch_bounds__(kThreads) void k_master_update(
+    size_t n, float* __restrict__ w32, float* __restrict__ m32, const void* __restrict__ grad,
+    uint16_t* __restrict__ w16, float inv_scale, const mpt_scaler* __restrict__ scaler, float lr, float mu,
+    const uint32_t* __restrict__ flag) {
+  if (flag != nullptr && *flag != 0u) return;              // overflow: the whole step is a no-op
+  const float inv = scaler != nullptr ? scaler->inv_scale : inv_scale;
+  const size_t nvec = n >> 3;
+  const size_t stride = (size_t)gridDim.x * kThreads;
+  for (size_t v = (size_t)blockIdx.x * kThreads + threadIdx.x; v < nvec; v += stride) {
+    float g[8];
+    if constexpr (G32) {
+      const f4* gp = reinterpret_cast<const f4*>(grad) + 2 * v;
+      const f4 a = ld<NT>(gp), b = ld<NT>(gp + 1);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { g[i] = a[i]; g[4 + i] = b[i]; }
+    } else {
+      const h8 a = ld<NT>(reinterpret_cast<const h8*>(grad) + v);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) g[i] = (float)a[i];
+    }
+    f4* wp = reinterpret_cast<f4*>(w32) + 2 * v;
+    f4 w0 = ld<NT>(wp), w1 = ld<NT>(wp + 1);
+    f4 m0 = {0, 0, 0, 0}, m1 = {0, 0, 0, 0};
+    f4* mp = nullptr;
+    if constexpr (MOM) {
+      mp = reinterpret_cast<f4*>(m32) + 2 * v;
+      m0 = ld<NT>(mp);
+      m1 = ld<NT>(mp + 1);
+    }
+    h8 h;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      float ma = m0[i], mb = m1[i];
+      w0[i] = step1<MOM>(w0[i], ma, g[i], inv, lr, mu);
+      w1[i] = step1<MOM>(w1[i], mb, g[4 + i], inv, lr, mu);
+      m0[i] = ma; m1[i] = mb;
+      h[i] = (_Float16)w0[i];
+      h[4 + i] = (_Float16)w1[i];
+    }
+    st<NT>(wp, w0);
+    st<NT>(wp + 1, w1);
+    if constexpr (MOM) { st<NT>(mp, m0); st<NT>(mp + 1, m1); }
+    st<NT>(reinterpret_cast<h8*>(w16) + v, h);
+  }
+  // ragged tail (< 8 elements), one element per thread of block 0
+  if (blockIdx.x == 0) {
+    const size_t i = (nvec << 3) + threadIdx.x;
+    if (i < n) {
+      float graw;
+      if constexpr (G32) graw = reinterpret_cast<const float*>(grad)[i];
+      else graw = (float)reinterpret_cast<const _Float16*>(grad)[i];
+      float m = 0.f;
+      if constexpr (MOM) m = m32[i];
+      const float w = step1<MOM>(w32[i], m, graw, inv, lr, mu);
+      w32[i] = w;
+      if constexpr (MOM) m32[i] = m;
+      reinterpret_cast<_Float16*>(w16)[i] = (_Float16)w;
+    }
+  }
+}
+
+// Same step for buffers that are only element-aligned: one element per thread per trip.
+template <bool MOM, bool G32>
+__global__ __launch_bounds__(kThreads) void k_master_update_scalar(
+    size_t n, float* __restrict__ w32, float* __restrict__ m32, const void* __restrict__ grad,
+    uint16_t* __restrict__ w16, float inv_scale, const mpt_scaler* __restrict__ scaler, float lr, float mu,
+    const uint32_t* __restrict__ flag) {
+  if (flag != nullptr && *flag != 0u) return;
+  const float inv = scaler != nullptr ? scaler->inv_scale : inv_scale;
+  const size_t stride = (size_t)gridDim.x * kThreads;
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += stride) {
+    float graw;
+    if constexpr (G32) graw = reinterpret_cast<const float*>(grad)[i];
+    else graw = (float)reinterpret_cast<const _Float16*>(grad)[i];
+    float m = 0.f;
+    if constexpr (MOM) m = m32[i];
+    const float w = step1<MOM>(w32[i], m, graw, inv, lr, mu);
+    w32[i] = w;
+    if constexpr (MOM) m32[i] = m;
+    reinterpret_cast<_Float16*>(w16)[i] = (_Float16)w;
+  }
+}
+
+// Inf/NaN scan (+ optional FP32 unscaled copy).  The exponent-field test runs on
+// the stored bits; each wavefront votes and at most one lane per wavefront
+// touches the flag.
+template <bool G32, bool WRITE, bool VEC>
+__global__ __launch_bounds__(kThreads) void k_unscale_check(
+    const void* __restrict__ grad, size_t n, float inv, float* __restrict__ out, uint32_t* __restrict__ flag) {
+  bool bad = false;
+  const size_t stride = (size_t)gridDim.x * kThreads;
+  const size_t tid = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  size_t done = 0;
+  if constexpr (VEC) {
+    const size_t nvec = n >> 3;
+    done = nvec << 3;
+    for (size_t v = tid; v < nvec; v += stride) {
+      if constexpr (G32) {
+        const u4* gp = reinterpret_cast<const u4*>(grad) + 2 * v;
+        const u4 a = ld<true>(gp), b = ld<true>(gp + 1);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) bad |= float_special(a[i]) | float_special(b[i]);
+        if constexpr (WRITE) {
+          f4 oa, ob;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            oa[i] = __fmul_rn(__uint_as_float(a[i]), inv);
+            ob[i] = __fmul_rn(__uint_as_float(b[i]), inv);
+          }
+          f4* op = reinterpret_cast<f4*>(out) + 2 * v;
+          st<true>(op, oa);
+          st<true>(op + 1, ob);
+        }
+      } else {
+        const u4 a = ld<true>(reinterpret_cast<const u4*>(grad) + v);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) bad |= half_special(a[i]) | half_special(a[i] >> 16);
+        if constexpr (WRITE) {
+          const h8 hv = __builtin_bit_cast(h8, a);
+          f4 oa, ob;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            oa[i] = __fmul_rn((float)hv[i], inv);
+            ob[i] = __fmul_rn((float)hv[4 + i], inv);
+          }
+          f4* op = reinterpret_cast<f4*>(out) + 2 * v;
+          st<true>(op, oa);
+          st<true>(op + 1, ob);
+        }
+      }
+    }
+  }
+  // scalar path: the whole buffer when unaligned, else the < 8 element tail
+  for (size_t i = done + tid; i < n; i += stride) {
+    float x;
+    if constexpr (G32) {
+      const uint32_t u = reinterpret_cast<const uint32_t*>(grad)[i];
+      bad |= float_special(u);
+      x = __uint_as_float(u);
+    } else {
+      const uint16_t u = reinterpret_cast<const uint16_t*>(grad)[i];
+      bad |= half_special(u);
+      x = (float)__builtin_bit_cast(_Float16, u);
+    }
+    if constexpr (WRITE) out[i] = __fmul_rn(x, inv);
+  }
+  const unsigned long long vote = __builtin_amdgcn_ballot_w64(bad);
+  if (vote != 0ull && (threadIdx.x & 63) == 0) atomicOr(flag, 1u);
+}
+
+__global__ void k_scaler_update(mpt_scaler* __restrict__ s, uint32_t* __restrict__ flag) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  float scale = s->scale;
+  int good = s->good_steps;
+  if (*flag != 0u) {
+    scale = fmaxf(__fmul_rn(scale, s->backoff), s->min_scale);
+    good = 0;
+  } else {
+    good += 1;
+    if (good == s->growth_interval) {
+      scale = fminf(__fmul_rn(scale, s->growth), s->max_scale);
+      good = 0;
+    }
+  }
+  s->scale = scale;
+  s->inv_scale = __fdiv_rn(1.0f, scale);
+  s->good_steps = good;
+  *flag = 0u;
+}
+
+__global__ __launch_bounds__(kThreads) void k_relu_fwd(size_t n, const uint16_t* __restrict__ y, uint16_t* __restrict__ h, bool vec) {
+  const size_t stride = (size_t)gridDim.x * kThreads;
+  const size_t tid = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  size_t done = 0;
+  if (vec) {
+    const size_t nvec = n >> 3;
+    done = nvec << 3;
+    for (size_t v = tid; v < nvec; v += stride) {
+      h8 a = reinterpret_cast<const h8*>(y)[v];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) a[i] = a[i] > (_Float16)0 ? a[i] : (_Float16)0;
+      reinterpret_cast<h8*>(h)[v] = a;
+    }
+  }
+  for (size_t i = done + tid; i < n; i += stride) {
+    const _Float16 a = reinterpret_cast<const _Float16*>(y)[i];
+    reinterpret_cast<_Float16*>(h)[i] = a > (_Float16)0 ? a : (_Float16)0;
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void k_relu_bwd(size_t n, const uint16_t* __restrict__ dh, const uint16_t* __restrict__ y,
+                                                        uint16_t* __restrict__ dy, bool vec) {
+  const size_t stride = (size_t)gridDim.x * kThreads;
+  const size_t tid = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  size_t done = 0;
+  if (vec) {
+    const size_t nvec = n >> 3;
+    done = nvec << 3;
+    for (size_t v = tid; v < nvec; v += stride) {
+      const h8 a = reinterpret_cast<const h8*>(y)[v];
+      h8 d = reinterpret_cast<const h8*>(dh)[v];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) d[i] = a[i] > (_Float16)0 ? d[i] : (_Float16)0;
+      reinterpret_cast<h8*>(dy)[v] = d;
+    }
+  }
+  for (size_t i = done + tid; i < n; i += stride) {
+    const _Float16 a = reinterpret_cast<const _Float16*>(y)[i];
+    const _Float16 d = reinterpret_cast<const _Float16*>(dh)[i];
+    reinterpret_cast<_Float16*>(dy)[i] = a > (_Float16)0 ? d : (_Float16)0;
+  }
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = __fadd_rn(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// One wavefront per row: FP16 logits in, FP32 max / sum / probabilities, FP16 scaled gradient out.
+__global__ __launch_bounds__(kThreads) void k_softmax_xent_grad(
+    int64_t B, int64_t C, const uint16_t* __restrict__ logits, int64_t ldl, const int32_t* __restrict__ labels,
+    float factor, uint16_t* __restrict__ dlogits, int64_t ldd) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+  if (row >= B) return;
+  const _Float16* z = reinterpret_cast<const _Float16*>(logits) + row * ldl;
+  float mx = -INFINITY;
+  for (int64_t c = lane; c < C; c += 64) mx = fmaxf(mx, (float)z[c]);
+  mx = wave_max(mx);
+  float sum = 0.f;
+  for (int64_t c = lane; c < C; c += 64) sum = __fadd_rn(sum, expf(__fsub_rn((float)z[c], mx)));
+  sum = wave_sum(sum);
+  const int32_t lab = labels[row];
+  _Float16* d = reinterpret_cast<_Float16*>(dlogits) + row * ldd;
+  for (int64_t c = lane; c < C; c += 64) {
+    const float p = __fdiv_rn(expf(__fsub_rn((float)z[c], mx)), sum);
+    d[c] = (_Float16)__fmul_rn(__fsub_rn(p, c == lab ? 1.0f : 0.0f), factor);
+  }
+}
+
+// Mean loss, one block, rows visited in a fixed order so the sum is reproducible.
+__global__ __launch_bounds__(kThreads) void k_softmax_xent_loss(
+    int64_t B, int64_t C, const uint16_t* __restrict__ logits, int64_t ldl, const int32_t* __restrict__ labels,
+    float* __restrict__ loss) {
+  __shared__ float part[kThreads / 64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  float acc = 0.f;
+  for (int64_t row = wave; row < B; row += kThreads / 64) {
+    const _Float16* z = reinterpret_cast<const _Float16*>(logits) + row * ldl;
+    float mx = -INFINITY;
+    for (int64_t c = lane; c < C; c += 64) mx = fmaxf(mx, (float)z[c]);
+    mx = wave_max(mx);
+    float sum = 0.f;
+    for (int64_t c = lane; c < C; c += 64) sum = __fadd_rn(sum, expf(__fsub_rn((float)z[c], mx)));
+    sum = wave_sum(sum);
+    const float zl = (float)z[labels[row]];
+    acc = __fadd_rn(acc, __fsub_rn(logf(sum), __fsub_rn(zl, mx)));
+  }
+  if (lane == 0) part[wave] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float t = 0.f;
+    for (int i = 0; i < kThreads / 64; ++i) t = __fadd_rn(t, part[i]);
+    loss[0] = __fdiv_rn(t, (float)B);
+  }
+}
+
+// Grid size for a streaming pass over `units` thread-trips.
+unsigned grid_for(size_t units) {
+  static const int per_cu = mpt_env_int("MPT_EW_BLOCKS_PER_CU", 0);   // 0: one trip per thread
+  size_t blocks = (units + kThreads - 1) / kThreads;
+  if (blocks < 1) blocks = 1;
+  if (per_cu > 0) {
+    const size_t cap = (size_t)per_cu * 256;
+    if (blocks > cap) blocks = cap;
+  }
+  const size_t hard = 0x7FFFFFFFu;
+  return (unsigned)(blocks > hard ? hard : blocks);
+}
+
+}  // namespace
+
+extern "C" int mpt_unscale_check(void* stream, const void* grad, int grad_is_fp32, size_t n, float inv_scale,
+                                 float* g32_out, uint32_t* flag) {
+  if (n == 0) return MPT_OK;
+  if (grad == nullptr || flag == nullptr) return MPT_ERR_NULL;
+  if (!mpt_finite(inv_scale) || !(inv_scale > 0.f)) return MPT_ERR_ARG;
+  const size_t esz = grad_is_fp32 ? 4 : 2;
+  if (!mpt_aligned(grad, esz) || !mpt_aligned(flag, 4) || (g32_out && !mpt_aligned(g32_out, 4))) return MPT_ERR_ALIGN;
+  const bool vec = mpt_aligned(grad, 16) && (g32_out == nullptr || mpt_aligned(g32_out, 16));
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const unsigned grid = grid_for(vec ? (n + 7) / 8 : n);
+#define MPT_UC(G, W, V) hipLaunchKernelGGL((k_unscale_check<G, W, V>), dim3(grid), dim3(kThreads), 0, s, grad, n, inv_scale, g32_out, flag)
+  const int sel = (grad_is_fp32 ? 4 : 0) | (g32_out ? 2 : 0) | (vec ? 1 : 0);
+  switch (sel) {
+    case 0: MPT_UC(false, false, false); break;
+    case 1: MPT_UC(false, false, true); break;
+    case 2: MPT_UC(false, true, false); break;
+    case 3: MPT_UC(false, true, true); break;
+    case 4: MPT_UC(true, false, false); break;
+    case 5: MPT_UC(true, false, true); break;
+    case 6: MPT_UC(true, true, false); break;
+    default: MPT_UC(true, true, true); break;
+  }
+#undef MPT_UC
+  MPT_LAUNCH_CHECK();
+  return MPT_OK;
+}
+
+extern "C" int mpt_master_update(void* stream, size_t n, float* w32, float* m32, const void* grad, int grad_is_fp32,
+                                 uint16_t* w16, float inv_scale, const mpt_scaler* scaler, float lr, float momentum,
+                                 const uint32_t* flag) {
+  if (n == 0) return MPT_OK;
+  if (w32 == nullptr || grad == nullptr || w16 == nullptr) return MPT_ERR_NULL;
+  if (!mpt_finite(lr) || !mpt_finite(momentum)) return MPT_ERR_ARG;
+  if (scaler == nullptr && (!mpt_finite(inv_scale) || !(inv_scale > 0.f))) return MPT_ERR_ARG;
+  const size_t gsz = grad_is_fp32 ? 4 : 2;
+  if (!mpt_aligned(w32, 4) || (m32 && !mpt_aligned(m32, 4)) || !mpt_aligned(grad, gsz) || !mpt_aligned(w16, 2) ||
+      (flag && !mpt_aligned(flag, 4)) || (scaler && !mpt_aligned(scaler, 4)))
+    return MPT_ERR_ALIGN;
+  const bool vec = mpt_aligned(w32, 16) && (m32 == nullptr || mpt_aligned(m32, 16)) && mpt_aligned(grad, 16) &&
+                   mpt_aligned(w16, 16);
+  static const bool nt = mpt_env_int("MPT_EW_NONTEMPORAL", 1) != 0;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const bool mom = m32 != nullptr;
+  const bool g32 = grad_is_fp32 != 0;
+  if (vec) {
+    const unsigned grid = grid_for((n + 7) / 8);
+#define MPT_MU(M, G, T) hipLaunchKernelGGL((k_master_update<M, G, T>), dim3(grid), dim3(kThreads), 0, s, n, w32, m32, grad, w16, inv_scale, scaler, lr, momentum, flag)
+    const int sel = (mom ? 4 : 0) | (g32 ? 2 : 0) | (nt ? 1 : 0);
+    switch (sel) {
+      case 0: MPT_MU(false, false, false); break;
+      case 1: MPT_MU(false, false, true); break;
+      case 2: MPT_MU(false, true, false); break;
+      case 3: MPT_MU(false, true, true); break;
+      case 4: MPT_MU(true, false, false); break;
+      case 5: MPT_MU(true, false, true); break;
+      case 6: MPT_MU(true, true, false); break;
+      default: MPT_MU(true, true, true); break;
+    }
+#undef MPT_MU
+  } else {
+    const unsigned grid = grid_for(n);
+#define MPT_MS(M, G) hipLaunchKernelGGL((k_master_update_scalar<M, G>), dim3(grid), dim3(kThreads), 0, s, n, w32, m32, grad, w16, inv_scale, scaler, lr, momentum, flag)
+    if (mom) { if (g32) MPT_MS(true, true); else MPT_MS(true, false); }
+    else     { if (g32) MPT_MS(false, true); else MPT_MS(false, false); }
+#undef MPT_MS
+  }
+  MPT_LAUNCH_CHECK();
+  return MPT_OK;
+}
+
+extern "C" int mpt_loss_scale_update_dev(void* stream, mpt_scaler* s_dev, uint32_t* flag) {
+  if (s_dev == nullptr || flag == nullptr) return MPT_ERR_NULL;
+  if (!mpt_aligned(s_dev, 4) || !mpt_aligned(flag, 4)) return MPT_ERR_ALIGN;
+  hipLaunchKernelGGL(k_scaler_update, dim3(1), dim3(64), 0, static_cast<hipStream_t>(stream), s_dev, flag);
+  MPT_LAUNCH_CHECK();
+  return MPT_OK;
+}
+
+extern "C" int mpt_relu_fwd(void* stream, size_t n, const uint16_t* y, uint16_t* h) {
+  if (n == 0) return MPT_OK;
+  if (y == nullptr || h == nullptr) return MPT_ERR_NULL;
+  if (!mpt_aligned(y, 2) || !mpt_aligned(h, 2)) return MPT_ERR_ALIGN;
+  const bool vec = mpt_aligned(y, 16) && mpt_aligned(h, 16);
+  hipLaunchKernelGGL(k_relu_fwd, dim3(grid_for(vec ? (n + 7) / 8 : n)), dim3(kThreads), 0, static_cast<hipStream_t>(stream), n, y, h, vec);
+  MPT_LAUNCH_CHECK();
+  return MPT_OK;
+}
+
+extern "C" int mpt_relu_bwd(void* stream, size_t n, const uint16_t* dh, const uint16_t* y, uint16_t* dy) {
+  if (n == 0) return MPT_OK;
+  if (dh == nullptr || y == nullptr || dy == nullptr) return MPT_ERR_NULL;
+  if (!mpt_aligned(dh, 2) || !mpt_aligned(y, 2) || !mpt_aligned(dy, 2)) return MPT_ERR_ALIGN;
+  const bool vec = mpt_aligned(dh, 16) && mpt_aligned(y, 16) && mpt_aligned(dy, 16);
+  hipLaunchKernelGGL(k_relu_bwd, dim3(grid_for(vec ? (n + 7) / 8 : n)), dim3(kThreads), 0, static_cast<hipStream_t>(stream), n, dh, y, dy, vec);
+  MPT_LAUNCH_CHECK();
+  return MPT_OK;
+}
+
+extern "C" int mpt_softmax_xent_scaled(void* stream, int64_t B, int64_t C, const uint16_t* logits, int64_t ldl,
+                                       const int32_t* labels, float scale, float* loss, uint16_t* dlogits, int64_t ldd) {
+  if (logits == nullptr || labels == nullptr || dlogits == nullptr) return MPT_ERR_NULL;
+  if (B < 1 || C < 1 || C > 4096 || B > 0x7FFFFFFF || ldl < C || ldd < C) return MPT_ERR_SHAPE;
+  if (!mpt_finite(scale) || !(scale > 0.f)) return MPT_ERR_ARG;
+  if (!mpt_aligned(logits, 2) || !mpt_aligned(dlogits, 2) || !mpt_aligned(labels, 4) || (loss && !mpt_aligned(loss, 4)))
+    return MPT_ERR_ALIGN;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const float factor = scale / (float)B;
+  const unsigned grid = (unsigned)((B + kThreads / 64 - 1) / (kThreads / 64));
+  hipLaunchKernelGGL(k_softmax_xent_grad, dim3(grid), dim3(kThreads), 0, s, B, C, logits, ldl, labels, factor, dlogits, ldd);
+  MPT_LAUNCH_CHECK();
+  if (loss != nullptr) {
+    hipLaunchKernelGGL(k_softmax_xent_loss, dim3(1), dim3(kThreads), 0, s, B, C, logits, ldl, labels, loss);
+    MPT_LAUNCH_CHECK();
+  }
+  return MPT_OK;
+}

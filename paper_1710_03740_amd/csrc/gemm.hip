@@ -1,0 +1,600 @@
+// FP16 contractions with FP32 accumulation and one RNE rounding to FP16 on store
+// (paper Sec. 3.3), for the three passes of a layer (Sec. 3.1 / Fig. 1) and for
+// the 3x3 convolution as an implicit GEMM.  gfx950 only.
+//
+// One kernel template computes C[i,j] = sum_r A(i,r) * B(r,j) on a BM x BN tile
+// per workgroup with v_mfma_f32_32x32x16_f16.  Operands differ only in how a
+// tile is fetched:
+//   * "RC" operands are contiguous along the reduction index r: a thread fetches
+//     16-byte chunks of 8 r-values and stores them to LDS unchanged;
+//   * "OC" operands are contiguous along the outer index (i or j): a thread
+//     fetches a 4(r) x 8(outer) patch and transposes it in registers on the way
+//     to LDS.
+// Either way LDS holds [outer][64 r-values] rows of 128 bytes whose 16-byte
+// chunks are XOR-swizzled, so MFMA fragments are single ds_read_b128's.
+// LDS is double buffered: global loads for tile t+1 are issued before the MFMAs
+// of tile t and written to the other buffer after them; one barrier per tile.
+#include "mpt_internal.h"
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+typedef float float16v __attribute__((ext_vector_type(16)));
+typedef float float4v __attribute__((ext_vector_type(4)));
+typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
+typedef uint32_t uint2v __attribute__((ext_vector_type(2)));
+
+namespace {
+
+constexpr int BK = 64;            // reduction depth of one LDS tile
+constexpr int ROWB = BK * 2;      // bytes per LDS row
+
+// ---------------------------------------------------------------- exact 32-bit division by an invariant
+struct FastDiv {
+  uint32_t d, m, s;               // q = (umulhi(m, n) + n') >> s  (round-up method)
+  FastDiv() : d(1), m(0), s(0) {}
+  explicit FastDiv(uint32_t div) : d(div) {
+    if (div <= 1) { m = 0; s = 0; d = 1; return; }
+    uint32_t l = 0;
+    while ((1ull << l) < div) ++l;                                 // l = ceil(log2 d), 1..32
+    m = (uint32_t)(((1ull << 32) * ((1ull << l) - div)) / div + 1);
+    s = l - 1;
+  }
+  __device__ __forceinline__ uint32_t div(uint32_t n) const {
+    if (d == 1) return n;
+    const uint32_t t = __umulhi(m, n);
+    return (t + ((n - t) >> 1)) >> s;
+  }
+  __device__ __forceinline__ void divmod(uint32_t n, uint32_t& q, uint32_t& r) const {
+    q = div(n);
+    r = n - q * d;
+  }
+};
+
+// ---------------------------------------------------------------- operand views
+// chunk(o, r, nvalid): address of the chunk that starts at outer index o and
+// reduction index r, and how many of its 8 elements exist (0 => do not touch).
+// RC views: the chunk runs along r.  OC views: the chunk runs along o.
+
+struct MatRC {                     // element (o, r) at base[o*ld + r]
+  const uint16_t* base; int64_t ld; int O, R;
+  static constexpr bool kRC = true;
+  __device__ __forceinline__ const uint16_t* chunk(int o, int r, int& nv) const {
+    nv = (o < O) ? min(max(R - r, 0), 8) : 0;
+    return base + (int64_t)o * ld + r;
+  }
+};
+
+struct MatOC {                     // element (o, r) at base[r*ld + o]
+  const uint16_t* base; int64_t ld; int O, R;
+  static constexpr bool kRC = false;
+  __device__ __forceinline__ const uint16_t* chunk(int o, int r, int& nv) const {
+    nv = (r < R) ? min(max(O - o, 0), 8) : 0;
+    return base + (int64_t)r * ld + o;
+  }
+};
+
+// Gathered image rows for the 3x3 convolution, stride 1, pad 1.
+// Outer index o = flat pixel (n, y, x); reduction index r = tap * Cc + c with
+// tap = 3*tr + ts.  Source pixel is (y + sgn*(tr-1), x + sgn*(ts-1)); sgn = +1
+// fetches the forward window, sgn = -1 the mirrored window of the input gradient.
+struct ImgRC {
+  const uint16_t* base; int H, W, Cc, O, R, sgn;
+  FastDiv dHW, dW, dC;
+  static constexpr bool kRC = true;
+  __device__ __forceinline__ const uint16_t* chunk(int o, int r, int& nv) const {
+    nv = 0;
+    if (o >= O || r >= R) return base;
+    uint32_t n, rem, y, x, tap, c;
+    dHW.divmod((uint32_t)o, n, rem);
+    dW.divmod(rem, y, x);
+    dC.divmod((uint32_t)r, tap, c);
+    const int tr = (int)tap / 3, ts = (int)tap - 3 * tr;
+    const int yy = (int)y + sgn * (tr - 1), xx = (int)x + sgn * (ts - 1);
+    if (yy < 0 || yy >= H || xx < 0 || xx >= W) return base;
+    nv = 8;
+    return base + (((int64_t)n * H + yy) * W + xx) * Cc + c;
+  }
+};
+
+// Same gather with the roles swapped: reduction index r = flat pixel (n, y, x),
+// outer index o = tap * Cc + c (weight-gradient pass reads the forward window).
+struct ImgOC {
+  const uint16_t* base; int H, W, Cc, O, R;
+  FastDiv dHW, dW, dC;
+  static constexpr bool kRC = false;
+  __device__ __forceinline__ const uint16_t* chunk(int o, int r, int& nv) const {
+    nv = 0;
+    if (o >= O || r >= R) return base;
+    uint32_t n, rem, y, x, tap, c;
+    dHW.divmod((uint32_t)r, n, rem);
+    dW.divmod(rem, y, x);
+    dC.divmod((uint32_t)o, tap, c);
+    const int tr = (int)tap / 3, ts = (int)tap - 3 * tr;
+    const int yy = (int)y + tr - 1, xx = (int)x + ts - 1;
+    if (yy < 0 || yy >= H || xx < 0 || xx >= W) return base;
+    nv = 8;
+    return base + (((int64_t)n * H + yy) * W + xx) * Cc + c;
+  }
+};
+
+// Filter w[k][tap][c] read as B(r = tap*Kf + k, o = c) for the input-gradient pass.
+struct FilterOC {
+  const uint16_t* base; int Cc, Kf, O, R;
+  FastDiv dK;
+  static constexpr bool kRC = false;
+  __device__ __forceinline__ const uint16_t* chunk(int o, int r, int& nv) const {
+    nv = 0;
+    if (o >= O || r >= R) return base;
+    uint32_t tap, k;
+    dK.divmod((uint32_t)r, tap, k);
+    nv = min(O - o, 8);
+    return base + ((int64_t)k * 9 + tap) * Cc + o;
+  }
+};
+
+// ---------------------------------------------------------------- chunk fetch
+template <bool ALIGNED>
+__device__ __forceinline__ uint4v fetch(const uint16_t* p, int nv) {
+  uint4v v = {0u, 0u, 0u, 0u};
+  if constexpr (ALIGNED) {
+    if (nv == 8) v = *reinterpret_cast<const uint4v*>(p);
+  } else {
+    if (nv > 0) {
+      uint16_t e[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) e[i] = (i < nv) ? p[i] : (uint16_t)0;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) v[i] = (uint32_t)e[2 * i] | ((uint32_t)e[2 * i + 1] << 16);
+    }
+  }
+  return v;
+}
+
+// LDS byte offset of 16-byte chunk kc (0..7) of row `row`.
+__device__ __forceinline__ int lds_off(int row, int kc) {
+  return row * ROWB + (((kc ^ row ^ (row >> 3)) & 7) << 4);
+}
+
+// One operand tile in flight: 4 chunks per thread, whatever the flavour.
+template <class View, bool ALIGNED, int BO, int NT>
+struct TileLoader {
+  static_assert(BO * 8 == NT * 4, "4 chunks per thread");
+  uint4v reg[4];
+
+  __device__ __forceinline__ void load(const View& v, int o_base, int r_base, int t) {
+    if constexpr (View::kRC) {
+      const int kc = t & 7, row0 = t >> 3;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int row = row0 + i * (NT / 8);
+        int nv;
+        const uint16_t* p = v.chunk(o_base + row, r_base + kc * 8, nv);
+        reg[i] = fetch<ALIGNED>(p, nv);
+      }
+    } else {
+      const int oc = t % (BO / 8), rg = t / (BO / 8);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        int nv;
+        const uint16_t* p = v.chunk(o_base + oc * 8, r_base + rg * 4 + i, nv);
+        reg[i] = fetch<ALIGNED>(p, nv);
+      }
+    }
+  }
+
+  __device__ __forceinline__ void store(char* lds, int t) const {
+    if constexpr (View::kRC) {
+      const int kc = t & 7, row0 = t >> 3;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int row = row0 + i * (NT / 8);
+        *reinterpret_cast<uint4v*>(lds + lds_off(row, kc)) = reg[i];
+      }
+    } else {
+      // 4(r) x 8(o) patch -> eight rows of 4 r-values (8 bytes each)
+      const int oc = t % (BO / 8), rg = t / (BO / 8);
+      const int kc = rg >> 1, half = (rg & 1) << 3;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const uint32_t sel = (j & 1) ? 0x07060302u : 0x05040100u;
+        uint2v o2;
+        o2[0] = __builtin_amdgcn_perm(reg[1][j >> 1], reg[0][j >> 1], sel);
+        o2[1] = __builtin_amdgcn_perm(reg[3][j >> 1], reg[2][j >> 1], sel);
+        const int row = oc * 8 + j;
+        *reinterpret_cast<uint2v*>(lds + lds_off(row, kc) + half) = o2;
+      }
+    }
+  }
+};
+
+// ---------------------------------------------------------------- epilogue description
+struct Epilogue {
+  void* out;            // uint16_t* (FP16) or float* (FP32 / split partials)
+  int64_t ld;
+  int mode;             // 0: FP16 store, 1: FP32 store, 2: FP32 accumulate, 3: FP32 partial [split][I][J]
+  uint32_t* flag;       // nullable; OR 1 when an FP16/FP32 stored value is Inf/NaN (modes 0..2)
+};
+
+struct Problem {
+  int I, J, R;          // output rows, output cols, reduction length
+  int tiles_i, tiles_j, splits, ktiles_per_split;
+};
+
+// Workgroup id -> (tile_i, tile_j, split).  Consecutive ids land on different XCDs
+// (8 of them, round-robin), so ids are first regrouped per XCD and then walked in
+// panels of 4 tile-rows so that one XCD's L2 sees a compact block of tiles.
+__device__ __forceinline__ void tile_of(const Problem& pb, int wg, int& ti, int& tj, int& sp) {
+  const int per_split = pb.tiles_i * pb.tiles_j;
+  const int total = per_split * pb.splits;
+  const int xcd = wg & 7, local = wg >> 3;
+  const int n_per = total >> 3, rem = total & 7;
+  int id = xcd * n_per + min(xcd, rem) + local;
+  sp = id / per_split;
+  id -= sp * per_split;
+  constexpr int GM = 4;
+  const int panel = id / (GM * pb.tiles_j);
+  const int first_i = panel * GM;
+  const int rows = min(GM, pb.tiles_i - first_i);
+  const int in_panel = id - panel * GM * pb.tiles_j;
+  ti = first_i + in_panel % rows;
+  tj = in_panel / rows;
+}
+
+__device__ __forceinline__ bool half_bits_special(uint32_t b) { return (b & 0x7C00u) == 0x7C00u; }
+
+template <class AView, class BView, bool ALIGNED, int BM, int BN, int WM, int WN>
+__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void k_gemm(AView A, BView B, Problem pb, Epilogue ep) {
+  constexpr int NT = (BM / WM) * (BN / WN) * 64;
+  constexpr int FM = WM / 32, FN = WN / 32;
+  constexpr int A_BYTES = BM * ROWB, B_BYTES = BN * ROWB, STAGE = A_BYTES + B_BYTES;
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+
+  const int t = threadIdx.x;
+  const int lane = t & 63, wave = t >> 6;
+  const int wm = wave / (BN / WN), wn = wave % (BN / WN);
+  int ti, tj, sp;
+  tile_of(pb, blockIdx.x, ti, tj, sp);
+  const int i0 = ti * BM, j0 = tj * BN;
+  const int kt_total = (pb.R + BK - 1) / BK;
+  const int kt_begin = sp * pb.ktiles_per_split;
+  const int kt_end = min(kt_begin + pb.ktiles_per_split, kt_total);
+
+  float16v acc[FM][FN];
+#pragma unroll
+  for (int a = 0; a < FM; ++a)
+#pragma unroll
+    for (int b = 0; b < FN; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+  TileLoader<AView, ALIGNED, BM, NT> la;
+  TileLoader<BView, ALIGNED, BN, NT> lb;
+
+  if (kt_begin < kt_end) {
+    la.load(A, i0, kt_begin * BK, t);
+    lb.load(B, j0, kt_begin * BK, t);
+    la.store(lds, t);
+    lb.store(lds + A_BYTES, t);
+  }
+  __syncthreads();
+
+  const int frag_row = lane & 31, frag_kc = lane >> 5;
+  int stage = 0;
+  for (int kt = kt_begin; kt < kt_end; ++kt) {
+    const bool more = kt + 1 < kt_end;
+    if (more) {
+      la.load(A, i0, (kt + 1) * BK, t);
+      lb.load(B, j0, (kt + 1) * BK, t);
+    }
+    const char* sa = lds + stage * STAGE;
+    const char* sb = sa + A_BYTES;
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      half8 fa[FM], fb[FN];
+#pragma unroll
+      for (int a = 0; a < FM; ++a)
+        fa[a] = *reinterpret_cast<const half8*>(sa + lds_off(wm * WM + a * 32 + frag_row, ks * 2 + frag_kc));
+#pragma unroll
+      for (int b = 0; b < FN; ++b)
+        fb[b] = *reinterpret_cast<const half8*>(sb + lds_off(wn * WN + b * 32 + frag_row, ks * 2 + frag_kc));
+      // operands swapped: the MFMA sees (B-fragment) x (A-fragment), so each lane ends
+      // up owning 4 consecutive output columns j for one output row i.
+#pragma unroll
+      for (int a = 0; a < FM; ++a)
+#pragma unroll
+        for (int b = 0; b < FN; ++b)
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[b], fa[a], acc[a][b], 0, 0, 0);
+    }
+    if (more) {
+      char* dst = lds + (stage ^ 1) * STAGE;
+      la.store(dst, t);
+      lb.store(dst + A_BYTES, t);
+    }
+    __syncthreads();
+    stage ^= 1;
+  }
+
+  // ---- epilogue.  acc[a][b][v]: row i = lane%32, col j = 8*(v/4) + 4*(lane/32) + v%4 of the 32x32 block.
+  bool bad = false;
+  const int64_t split_off = (ep.mode == 3) ? (int64_t)sp * pb.I * pb.J : 0;
+#pragma unroll
+  for (int a = 0; a < FM; ++a) {
+    const int i = i0 + wm * WM + a * 32 + (lane & 31);
+#pragma unroll
+    for (int b = 0; b < FN; ++b) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int j = j0 + wn * WN + b * 32 + g * 8 + ((lane >> 5) << 2);
+        if (i >= pb.I || j >= pb.J) continue;
+        const int nj = min(4, pb.J - j);
+        float x[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) x[e] = acc[a][b][g * 4 + e];
+        if (ep.mode == 0) {
+          uint16_t* o = reinterpret_cast<uint16_t*>(ep.out) + (int64_t)i * ep.ld + j;
+          half4 h;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) h[e] = (_Float16)x[e];
+          const uint2v hb = __builtin_bit_cast(uint2v, h);
+          if (ep.flag) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) bad |= (e < nj) & half_bits_special(hb[e >> 1] >> ((e & 1) * 16));
+          }
+          if (nj == 4 && ((reinterpret_cast<uintptr_t>(o) & 7) == 0)) {
+            *reinterpret_cast<uint2v*>(o) = hb;
+          } else {
+            for (int e = 0; e < nj; ++e) o[e] = (uint16_t)(hb[e >> 1] >> ((e & 1) * 16));
+          }
+        } else {
+          float* o = reinterpret_cast<float*>(ep.out) + split_off + (int64_t)i * ep.ld + j;
+          for (int e = 0; e < nj; ++e) {
+            float v = x[e];
+            if (ep.mode == 2) v = __fadd_rn(o[e], v);
+            if (ep.flag && ep.mode != 3) bad |= (__float_as_uint(v) & 0x7F800000u) == 0x7F800000u;
+            o[e] = v;
+          }
+        }
+      }
+    }
+  }
+  if (ep.flag != nullptr && ep.mode != 3) {
+    const unsigned long long vote = __builtin_amdgcn_ballot_w64(bad);
+    if (vote != 0ull && lane == 0) atomicOr(ep.flag, 1u);
+  }
+}
+
+// Sum split partials in split order (fixed, so results are reproducible), then store once.
+__global__ __launch_bounds__(256) void k_split_reduce(const float* __restrict__ part, int splits, int I, int J, Epilogue ep) {
+  const int64_t total = (int64_t)I * J;
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  bool bad = false;
+  if (idx < total) {
+    float s = part[idx];
+    for (int k = 1; k < splits; ++k) s = __fadd_rn(s, part[(int64_t)k * total + idx]);
+    const int64_t i = idx / J, j = idx - i * J;
+    if (ep.mode == 0) {
+      const _Float16 h = (_Float16)s;
+      const uint16_t hb = __builtin_bit_cast(uint16_t, h);
+      bad = half_bits_special(hb);
+      reinterpret_cast<uint16_t*>(ep.out)[i * ep.ld + j] = hb;
+    } else {
+      float* o = reinterpret_cast<float*>(ep.out) + i * ep.ld + j;
+      if (ep.mode == 2) s = __fadd_rn(*o, s);
+      bad = (__float_as_uint(s) & 0x7F800000u) == 0x7F800000u;
+      *o = s;
+    }
+  }
+  if (ep.flag != nullptr) {
+    const unsigned long long vote = __builtin_amdgcn_ballot_w64(bad);
+    if (vote != 0ull && (threadIdx.x & 63) == 0) atomicOr(ep.flag, 1u);
+  }
+}
+
+// ---------------------------------------------------------------- host-side planning
+struct Plan {
+  bool big;             // 256x256 tiles (8 wavefronts) or 128x128 (4 wavefronts)
+  int splits, ktiles_per_split, tiles_i, tiles_j;
+};
+
+constexpr int kCUs = 256;
+
+Plan make_plan(int64_t I, int64_t J, int64_t R, bool allow_split) {
+  static const int force_tile = mpt_env_int("MPT_GEMM_TILE", 0);      // 128 / 256 force a tile size (tuning only)
+  static const int force_split = mpt_env_int("MPT_GEMM_SPLITS", 0);   // >0 forces a split count (tuning only)
+  Plan p;
+  const int64_t t256 = ((I + 255) / 256) * ((J + 255) / 256);
+  p.big = t256 >= kCUs / 2;
+  if (force_tile == 128) p.big = false;
+  if (force_tile == 256) p.big = true;
+  const int tile = p.big ? 256 : 128;
+  p.tiles_i = (int)((I + tile - 1) / tile);
+  p.tiles_j = (int)((J + tile - 1) / tile);
+  const int64_t tiles = (int64_t)p.tiles_i * p.tiles_j;
+  const int kt = (int)((R + BK - 1) / BK);
+  int splits = 1;
+  if (allow_split && tiles < kCUs) {
+    splits = (int)(kCUs / tiles);
+    const int max_by_depth = kt / 8 > 0 ? kt / 8 : 1;                // keep >= 8 k-tiles per split
+    if (splits > max_by_depth) splits = max_by_depth;
+    if (splits > 64) splits = 64;
+  }
+  if (allow_split && force_split > 0) splits = force_split < kt ? force_split : kt;
+  if (splits < 1) splits = 1;
+  p.ktiles_per_split = (kt + splits - 1) / splits;
+  p.splits = (kt + p.ktiles_per_split - 1) / p.ktiles_per_split;   // no empty split
+  return p;
+}
+
+size_t plan_ws_bytes(const Plan& p, int64_t I, int64_t J) {
+  return p.splits > 1 ? (size_t)p.splits * (size_t)I * (size_t)J * sizeof(float) : 0;
+}
+
+template <class AView, class BView, bool ALIGNED>
+int launch_tiles(hipStream_t s, const AView& A, const BView& B, const Plan& pl, int I, int J, int R, const Epilogue& ep) {
+  Problem pb{I, J, R, pl.tiles_i, pl.tiles_j, pl.splits, pl.ktiles_per_split};
+  const unsigned grid = (unsigned)((int64_t)pl.tiles_i * pl.tiles_j * pl.splits);
+  if (pl.big) {
+    auto k = k_gemm<AView, BView, ALIGNED, 256, 256, 128, 64>;
+    constexpr int lds = 2 * (256 + 256) * ROWB;
+    static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, lds), true);
+    (void)once;
+    hipLaunchKernelGGL(k, dim3(grid), dim3(512), lds, s, A, B, pb, ep);
+  } else {
+    auto k = k_gemm<AView, BView, ALIGNED, 128, 128, 64, 64>;
+    constexpr int lds = 2 * (128 + 128) * ROWB;
+    static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, lds), true);
+    (void)once;
+    hipLaunchKernelGGL(k, dim3(grid), dim3(256), lds, s, A, B, pb, ep);
+  }
+  MPT_LAUNCH_CHECK();
+  return MPT_OK;
+}
+
+// Run one contraction: single pass, or split partials + ordered reduction.
+template <class AView, class BView>
+int run(hipStream_t s, const AView& A, const BView& B, bool aligned, int I, int J, int R, Epilogue ep, void* ws, size_t ws_bytes) {
+  const Plan pl = make_plan(I, J, R, ws != nullptr);
+  if (ws != nullptr && ws_bytes < plan_ws_bytes(pl, I, J)) return MPT_ERR_WORKSPACE;
+  Epilogue first = ep;
+  if (pl.splits > 1) {
+    first.out = ws; first.ld = J; first.mode = 3; first.flag = nullptr;
+  }
+  const int st = aligned ? launch_tiles<AView, BView, true>(s, A, B, pl, I, J, R, first)
+                         : launch_tiles<AView, BView, false>(s, A, B, pl, I, J, R, first);
+  if (st != MPT_OK) return st;
+  if (pl.splits > 1) {
+    const int64_t total = (int64_t)I * J;
+    hipLaunchKernelGGL(k_split_reduce, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
+                       reinterpret_cast<const float*>(ws), pl.splits, I, J, ep);
+    MPT_LAUNCH_CHECK();
+  }
+  return MPT_OK;
+}
+
+bool dims_ok(int64_t a, int64_t b, int64_t c) {
+  const int64_t lim = 0x7FFFFFFF - 512;
+  return a >= 1 && b >= 1 && c >= 1 && a <= lim && b <= lim && c <= lim;
+}
+// A plain matrix can use 16-byte chunk loads when its base and row stride keep every chunk aligned
+// and its contiguous extent is a whole number of chunks.
+bool mat_fast(const void* p, int64_t ld, int64_t contiguous_extent) {
+  return mpt_aligned(p, 16) && (ld % 8) == 0 && (contiguous_extent % 8) == 0;
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------- C ABI: GEMMs
+extern "C" size_t mpt_gemm_workspace_bytes(int op, int64_t M, int64_t N, int64_t K) {
+  if (!dims_ok(M, N, K)) return 0;
+  int64_t I, J, R;
+  switch (op) {
+    case MPT_OP_FWD: I = M; J = N; R = K; break;
+    case MPT_OP_DGRAD: I = M; J = K; R = N; break;
+    case MPT_OP_WGRAD: I = K; J = N; R = M; break;
+    default: return 0;
+  }
+  return plan_ws_bytes(make_plan(I, J, R, true), I, J);
+}
+
+extern "C" int mpt_gemm_fwd(void* stream, int64_t M, int64_t N, int64_t K, const uint16_t* X, int64_t ldx,
+                            const uint16_t* W, int64_t ldw, uint16_t* Y, int64_t ldy, void* ws, size_t ws_bytes) {
+  if (X == nullptr || W == nullptr || Y == nullptr) return MPT_ERR_NULL;
+  if (!dims_ok(M, N, K) || ldx < K || ldw < N || ldy < N) return MPT_ERR_SHAPE;
+  if (!mpt_aligned(X, 2) || !mpt_aligned(W, 2) || !mpt_aligned(Y, 2) || (ws && !mpt_aligned(ws, 16))) return MPT_ERR_ALIGN;
+  MatRC A{X, ldx, (int)M, (int)K};
+  MatOC B{W, ldw, (int)N, (int)K};
+  Epilogue ep{Y, ldy, 0, nullptr};
+  const bool fast = mat_fast(X, ldx, K) && mat_fast(W, ldw, N);
+  return run(static_cast<hipStream_t>(stream), A, B, fast, (int)M, (int)N, (int)K, ep, ws, ws_bytes);
+}
+
+extern "C" int mpt_gemm_dgrad(void* stream, int64_t M, int64_t N, int64_t K, const uint16_t* dY, int64_t ldy,
+                              const uint16_t* W, int64_t ldw, uint16_t* dX, int64_t ldx, void* ws, size_t ws_bytes) {
+  if (dY == nullptr || W == nullptr || dX == nullptr) return MPT_ERR_NULL;
+  if (!dims_ok(M, N, K) || ldy < N || ldw < N || ldx < K) return MPT_ERR_SHAPE;
+  if (!mpt_aligned(dY, 2) || !mpt_aligned(W, 2) || !mpt_aligned(dX, 2) || (ws && !mpt_aligned(ws, 16))) return MPT_ERR_ALIGN;
+  MatRC A{dY, ldy, (int)M, (int)N};
+  MatRC B{W, ldw, (int)K, (int)N};
+  Epilogue ep{dX, ldx, 0, nullptr};
+  const bool fast = mat_fast(dY, ldy, N) && mat_fast(W, ldw, N);
+  return run(static_cast<hipStream_t>(stream), A, B, fast, (int)M, (int)K, (int)N, ep, ws, ws_bytes);
+}
+
+extern "C" int mpt_gemm_wgrad(void* stream, int64_t M, int64_t N, int64_t K, const uint16_t* X, int64_t ldx,
+                              const uint16_t* dY, int64_t ldy, void* dW, int64_t lddw, int out_fp32, int accumulate,
+                              uint32_t* flag, void* ws, size_t ws_bytes) {
+  if (X == nullptr || dY == nullptr || dW == nullptr) return MPT_ERR_NULL;
+  if (!dims_ok(M, N, K) || ldx < K || ldy < N || lddw < N) return MPT_ERR_SHAPE;
+  if (accumulate && !out_fp32) return MPT_ERR_ARG;
+  if (!mpt_aligned(X, 2) || !mpt_aligned(dY, 2) || !mpt_aligned(dW, out_fp32 ? 4 : 2) || (flag && !mpt_aligned(flag, 4)) ||
+      (ws && !mpt_aligned(ws, 16)))
+    return MPT_ERR_ALIGN;
+  MatOC A{X, ldx, (int)K, (int)M};
+  MatOC B{dY, ldy, (int)N, (int)M};
+  Epilogue ep{dW, lddw, out_fp32 ? (accumulate ? 2 : 1) : 0, flag};
+  const bool fast = mat_fast(X, ldx, K) && mat_fast(dY, ldy, N);
+  return run(static_cast<hipStream_t>(stream), A, B, fast, (int)K, (int)N, (int)M, ep, ws, ws_bytes);
+}
+
+// ---------------------------------------------------------------- C ABI: 3x3 convolution
+namespace {
+bool conv_ok(int64_t Nb, int64_t H, int64_t W, int64_t C, int64_t Kf) {
+  const int64_t lim = 0x7FFFFFFF - 512;
+  if (Nb < 1 || H < 1 || W < 1 || C < 1 || Kf < 1) return false;
+  if ((C % 8) != 0 || (Kf % 8) != 0) return false;
+  if (Nb * H * W > lim || 9 * C > lim || 9 * Kf > lim) return false;
+  if (Nb * H * W * C > (int64_t)1 << 40 || Nb * H * W * Kf > (int64_t)1 << 40) return false;
+  return true;
+}
+}  // namespace
+
+extern "C" size_t mpt_conv3x3_workspace_bytes(int op, int64_t Nb, int64_t H, int64_t W, int64_t C, int64_t Kf) {
+  if (!conv_ok(Nb, H, W, C, Kf)) return 0;
+  const int64_t P = Nb * H * W;
+  int64_t I, J, R;
+  switch (op) {
+    case MPT_OP_FWD: I = P; J = Kf; R = 9 * C; break;
+    case MPT_OP_DGRAD: I = P; J = C; R = 9 * Kf; break;
+    case MPT_OP_WGRAD: I = Kf; J = 9 * C; R = P; break;
+    default: return 0;
+  }
+  return plan_ws_bytes(make_plan(I, J, R, true), I, J);
+}
+
+extern "C" int mpt_conv3x3_fwd(void* stream, int64_t Nb, int64_t H, int64_t W, int64_t C, int64_t Kf, const uint16_t* x,
+                               const uint16_t* w, uint16_t* y, void* ws, size_t ws_bytes) {
+  if (x == nullptr || w == nullptr || y == nullptr) return MPT_ERR_NULL;
+  if (!conv_ok(Nb, H, W, C, Kf)) return MPT_ERR_SHAPE;
+  if (!mpt_aligned(x, 16) || !mpt_aligned(w, 16) || !mpt_aligned(y, 16) || (ws && !mpt_aligned(ws, 16))) return MPT_ERR_ALIGN;
+  const int P = (int)(Nb * H * W), R = (int)(9 * C);
+  ImgRC A{x, (int)H, (int)W, (int)C, P, R, +1, FastDiv((uint32_t)(H * W)), FastDiv((uint32_t)W), FastDiv((uint32_t)C)};
+  MatRC B{w, 9 * C, (int)Kf, R};
+  Epilogue ep{y, Kf, 0, nullptr};
+  return run(static_cast<hipStream_t>(stream), A, B, true, P, (int)Kf, R, ep, ws, ws_bytes);
+}
+
+extern "C" int mpt_conv3x3_dgrad(void* stream, int64_t Nb, int64_t H, int64_t W, int64_t C, int64_t Kf, const uint16_t* dy,
+                                 const uint16_t* w, uint16_t* dx, void* ws, size_t ws_bytes) {
+  if (dy == nullptr || w == nullptr || dx == nullptr) return MPT_ERR_NULL;
+  if (!conv_ok(Nb, H, W, C, Kf)) return MPT_ERR_SHAPE;
+  if (!mpt_aligned(dy, 16) || !mpt_aligned(w, 16) || !mpt_aligned(dx, 16) || (ws && !mpt_aligned(ws, 16))) return MPT_ERR_ALIGN;
+  const int P = (int)(Nb * H * W), R = (int)(9 * Kf);
+  ImgRC A{dy, (int)H, (int)W, (int)Kf, P, R, -1, FastDiv((uint32_t)(H * W)), FastDiv((uint32_t)W), FastDiv((uint32_t)Kf)};
+  FilterOC B{w, (int)C, (int)Kf, (int)C, R, FastDiv((uint32_t)Kf)};
+  Epilogue ep{dx, C, 0, nullptr};
+  return run(static_cast<hipStream_t>(stream), A, B, true, P, (int)C, R, ep, ws, ws_bytes);
+}
+
+extern "C" int mpt_conv3x3_wgrad(void* stream, int64_t Nb, int64_t H, int64_t W, int64_t C, int64_t Kf, const uint16_t* x,
+                                 const uint16_t* dy, uint16_t* dw, uint32_t* flag, void* ws, size_t ws_bytes) {
+  if (x == nullptr || dy == nullptr || dw == nullptr) return MPT_ERR_NULL;
+  if (!conv_ok(Nb, H, W, C, Kf)) return MPT_ERR_SHAPE;
+  if (!mpt_aligned(x, 16) || !mpt_aligned(dy, 16) || !mpt_aligned(dw, 16) || (flag && !mpt_aligned(flag, 4)) ||
+      (ws && !mpt_aligned(ws, 16)))
+    return MPT_ERR_ALIGN;
+  const int P = (int)(Nb * H * W), J = (int)(9 * C);
+  MatOC A{dy, Kf, (int)Kf, P};
+  ImgOC B{x, (int)H, (int)W, (int)C, J, P, FastDiv((uint32_t)(H * W)), FastDiv((uint32_t)W), FastDiv((uint32_t)C)};
+  Epilogue ep{dw, J, 0, flag};
+  return run(static_cast<hipStream_t>(stream), A, B, true, (int)Kf, J, P, ep, ws, ws_bytes);
+}

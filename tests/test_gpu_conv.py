@@ -1,0 +1,69 @@
+"""GPU parity of the 3x3 implicit-GEMM convolution against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from oracle import conv, fp16
+from paper_1710_03740_amd import binding as mpt
+from gpu_util import dev16, host16, gemm_check
+
+pytestmark = pytest.mark.gpu
+
+
+def _ws(op, Nb, H, W, C, Kf):
+    b = mpt.mpt_conv3x3_workspace_bytes(op, Nb, H, W, C, Kf)
+    return torch.empty(max(b, 16) // 4, dtype=torch.float32, device="cuda") if b else None
+
+
+def run_all(x, w, dy, split):
+    Nb, H, W, C = x.shape
+    Kf = w.shape[0]
+    d_x, d_w, d_dy = dev16(x), dev16(w), dev16(dy)
+    y = torch.full((Nb, H, W, Kf), float("nan"), dtype=torch.float16, device="cuda")
+    dx = torch.full((Nb, H, W, C), float("nan"), dtype=torch.float16, device="cuda")
+    dw = torch.full((Kf, 3, 3, C), float("nan"), dtype=torch.float16, device="cuda")
+    mpt.mpt_conv3x3_fwd(d_x, d_w, y, _ws(0, Nb, H, W, C, Kf) if split else None)
+    mpt.mpt_conv3x3_dgrad(d_dy, d_w, dx, _ws(1, Nb, H, W, C, Kf) if split else None)
+    mpt.mpt_conv3x3_wgrad(d_x, d_dy, dw, None, _ws(2, Nb, H, W, C, Kf) if split else None)
+    return host16(y), host16(dx), host16(dw)
+
+
+@pytest.mark.parametrize("Nb,H,W,C,Kf", [(1, 1, 1, 8, 8), (2, 3, 4, 8, 16), (3, 5, 7, 24, 40), (2, 14, 14, 64, 72), (5, 9, 6, 136, 264)])
+@pytest.mark.parametrize("split", [False, True])
+def test_small_shapes(Nb, H, W, C, Kf, split):
+    c = workloads.conv_block(batch=Nb, hw=H, c=C, kf=Kf)
+    rng = np.random.default_rng(Nb + H + W)
+    x = np.maximum(rng.standard_normal((Nb, H, W, C)), 0).astype(np.float16)
+    dy = (np.abs(rng.standard_normal((Nb, H, W, Kf))) * 2.0 ** -6 * rng.integers(0, 2, (Nb, H, W, Kf))).astype(np.float16)
+    w = c["w"]
+    y, dx, dw = run_all(x, w, dy, split)
+    o, sa, s = conv.conv3x3_fwd(x, w, full=True)
+    gemm_check(y, o, sa, s, "conv fwd")
+    o, sa, s = conv.conv3x3_dgrad(dy, w, full=True)
+    gemm_check(dx, o, sa, s, "conv dgrad")
+    o, sa, s = conv.conv3x3_wgrad(x, dy, full=True)
+    gemm_check(dw, o, sa, s, "conv wgrad")
+
+
+def test_integer_inputs_bit_exact():
+    rng = np.random.default_rng(0)
+    x = rng.integers(-2, 3, (2, 6, 5, 16)).astype(np.float16)
+    w = rng.integers(-2, 3, (8, 3, 3, 16)).astype(np.float16)
+    dy = rng.integers(-2, 3, (2, 6, 5, 8)).astype(np.float16)
+    y, dx, dw = run_all(x, w, dy, False)
+    assert np.array_equal(fp16.bits(y), fp16.bits(conv.conv3x3_fwd(x, w)[0]))
+    assert np.array_equal(fp16.bits(dx), fp16.bits(conv.conv3x3_dgrad(dy, w)[0]))
+    assert np.array_equal(fp16.bits(dw), fp16.bits(conv.conv3x3_wgrad(x, dy)[0]))
+
+
+def test_cfg4_resnet_block_full_size():
+    c = workloads.conv_block()
+    x, w, dy = c["x"], c["w"], c["dy"]
+    y, dx, dw = run_all(x, w, dy, True)
+    o, sa, s = conv.conv3x3_fwd(x, w, full=True)
+    gemm_check(y, o, sa, s, "cfg4 fwd")
+    o, sa, s = conv.conv3x3_dgrad(dy, w, full=True)
+    gemm_check(dx, o, sa, s, "cfg4 dgrad")
+    o, sa, s = conv.conv3x3_wgrad(x, dy, full=True)
+    gemm_check(dw, o, sa, s, "cfg4 wgrad")

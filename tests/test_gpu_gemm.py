@@ -1,0 +1,169 @@
+"""GPU parity of the three FP16 contractions against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from oracle import fp16, gemm
+from paper_1710_03740_amd import binding as mpt
+from gpu_util import dev, dev16, host, host16, gemm_check
+
+pytestmark = pytest.mark.gpu
+
+
+def _ws(op, M, N, K):
+    b = mpt.mpt_gemm_workspace_bytes(op, M, N, K)
+    return torch.empty(max(b, 16) // 4, dtype=torch.float32, device="cuda") if b else None
+
+
+def run_fwd(X, W, split=False):
+    M, K = X.shape; N = W.shape[1]
+    Y = torch.full((M, N), float("nan"), dtype=torch.float16, device="cuda")
+    mpt.mpt_gemm_fwd(dev16(X), dev16(W), Y, _ws(0, M, N, K) if split else None)
+    return host16(Y)
+
+
+def run_dgrad(dY, W, split=False):
+    M, N = dY.shape; K = W.shape[0]
+    dX = torch.full((M, K), float("nan"), dtype=torch.float16, device="cuda")
+    mpt.mpt_gemm_dgrad(dev16(dY), dev16(W), dX, _ws(1, M, N, K) if split else None)
+    return host16(dX)
+
+
+def run_wgrad(X, dY, split=False, flag=None):
+    M, K = X.shape; N = dY.shape[1]
+    dW = torch.full((K, N), float("nan"), dtype=torch.float16, device="cuda")
+    mpt.mpt_gemm_wgrad(dev16(X), dev16(dY), dW, flag=flag, ws=_ws(2, M, N, K) if split else None)
+    return host16(dW)
+
+
+SHAPES = [(1, 1, 1), (3, 5, 7), (33, 10, 65), (8, 16, 64), (130, 70, 200), (257, 129, 65), (300, 264, 136)]
+
+
+@pytest.mark.parametrize("M,N,K", SHAPES)
+def test_integer_inputs_bit_exact(M, N, K):
+    """Small-integer operands with short reductions: every partial sum is exact in
+    FP32, so all three passes must equal integer arithmetic bit-for-bit."""
+    rng = np.random.default_rng(M + N + K)
+    lim = 4 if max(M, N, K) <= 65 else 2
+    X = rng.integers(-lim, lim + 1, (M, K)).astype(np.float16)
+    W = rng.integers(-lim, lim + 1, (K, N)).astype(np.float16)
+    dY = rng.integers(-lim, lim + 1, (M, N)).astype(np.float16)
+    Xi, Wi, dYi = X.astype(np.int64), W.astype(np.int64), dY.astype(np.int64)
+    for split in (False, True):
+        assert np.array_equal(run_fwd(X, W, split).astype(np.int64), Xi @ Wi)
+        assert np.array_equal(run_dgrad(dY, W, split).astype(np.int64), dYi @ Wi.T)
+        assert np.array_equal(run_wgrad(X, dY, split).astype(np.int64), Xi.T @ dYi)
+
+
+@pytest.mark.parametrize("M,N,K", [(130, 72, 200), (257, 129, 65), (300, 264, 136), (256, 10, 1024), (512, 384, 1024),
+                                   (1000, 520, 776)])
+@pytest.mark.parametrize("split", [False, True])
+def test_random_inputs_against_oracle(M, N, K, split):
+    rng = np.random.default_rng(M * 7 + N * 3 + K)
+    X = rng.standard_normal((M, K)).astype(np.float16)
+    W = (rng.standard_normal((K, N)) * 0.05).astype(np.float16)
+    dY = (np.exp2(rng.uniform(-20, -3, (M, N))) * rng.choice([-1, 1], (M, N))).astype(np.float16)
+    y, sa, s = gemm.gemm_fwd(X, W, full=True)
+    gemm_check(run_fwd(X, W, split), y, sa, s, "fwd %s" % ((M, N, K),))
+    dx, sa, s = gemm.gemm_dgrad(dY, W, full=True)
+    gemm_check(run_dgrad(dY, W, split), dx, sa, s, "dgrad")
+    dw, sa, s = gemm.gemm_wgrad(X, dY, full=True)
+    gemm_check(run_wgrad(X, dY, split), dw, sa, s, "wgrad")
+
+
+def test_leading_dimensions_and_unaligned_bases():
+    rng = np.random.default_rng(5)
+    M, N, K = 70, 52, 90
+    Xb = rng.standard_normal((M, K + 5)).astype(np.float16)
+    Wb = rng.standard_normal((K, N + 3)).astype(np.float16)
+    d_X, d_W = dev16(Xb), dev16(Wb)
+    Yb = torch.zeros((M, N + 7), dtype=torch.float16, device="cuda")
+    mpt.mpt_gemm_fwd(d_X[:, 1:K + 1], d_W[:, 2:N + 2], Yb[:, 3:N + 3])
+    X, W = np.ascontiguousarray(Xb[:, 1:K + 1]), np.ascontiguousarray(Wb[:, 2:N + 2])
+    y, sa, s = gemm.gemm_fwd(X, W, full=True)
+    out = host16(Yb)
+    gemm_check(np.ascontiguousarray(out[:, 3:N + 3]), y, sa, s, "fwd strided")
+    assert not out[:, :3].any() and not out[:, N + 3:].any()       # nothing written outside the view
+
+
+def test_overflow_stores_inf_and_raises_wgrad_flag():
+    X = np.full((64, 8), 200.0, dtype=np.float16)
+    dY = np.full((64, 8), 100.0, dtype=np.float16)
+    dY[:, 1] = 2.0 ** -10
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    dW = run_wgrad(X, dY, flag=flag)
+    want, _ = gemm.gemm_wgrad(X, dY)
+    assert np.array_equal(fp16.bits(dW), fp16.bits(want))
+    assert fp16.bits(dW)[0, 0] == 0x7C00 and int(flag.item()) == 1
+    flag.zero_()
+    dY[:, 0] = 2.0 ** -10
+    run_wgrad(X, dY, flag=flag)
+    assert int(flag.item()) == 0
+
+
+def test_subnormal_operands_and_results_are_kept():
+    """Without loss scaling the upstream gradient is largely subnormal in FP16;
+    neither operands nor results may be flushed."""
+    rng = np.random.default_rng(8)
+    M, N, K = 128, 64, 96
+    X = rng.standard_normal((M, K)).astype(np.float16)
+    dY = (np.exp2(rng.uniform(-24, -15, (M, N))) * rng.choice([-1, 1], (M, N))).astype(np.float16)
+    assert ((fp16.bits(dY) & 0x7C00) == 0).mean() > 0.8
+    W = (np.exp2(rng.uniform(-8, -1, (K, N)))).astype(np.float16)
+    dw, sa, s = gemm.gemm_wgrad(X, dY, full=True)
+    gemm_check(run_wgrad(X, dY), dw, sa, s, "wgrad subnormal operand")
+    dx, sa, s = gemm.gemm_dgrad(dY, W, full=True)
+    got = run_dgrad(dY, W)
+    gemm_check(got, dx, sa, s, "dgrad subnormal result")
+    assert (((fp16.bits(got) & 0x7C00) == 0) & ((fp16.bits(got) & 0x3FF) != 0)).any()
+
+
+def test_power_of_two_invariance_and_determinism():
+    rng = np.random.default_rng(10)
+    X = rng.standard_normal((200, 300)).astype(np.float16)
+    dY = (rng.uniform(0.5, 1.0, (200, 100)) * 2.0 ** -9).astype(np.float16)
+    a = run_wgrad(X, dY, split=True)
+    b = run_wgrad(X, dY, split=True)
+    assert np.array_equal(fp16.bits(a), fp16.bits(b))
+    c = run_wgrad(X, (dY.astype(np.float32) * 64).astype(np.float16), split=True)
+    av, cv = fp16.to_f64(a), fp16.to_f64(c)
+    normal = np.abs(av) >= 2.0 ** -14
+    assert np.array_equal(cv[normal], av[normal] * 64)
+
+
+def test_wgrad_fp32_store_and_accumulate():
+    rng = np.random.default_rng(12)
+    T, B, K, N = 5, 64, 72, 40
+    X = rng.standard_normal((T, B, K)).astype(np.float16)
+    dY = (rng.standard_normal((T, B, N)) * 2.0 ** -12).astype(np.float16)
+    d_acc = torch.zeros((K, N), dtype=torch.float32, device="cuda")
+    acc = None
+    for t in range(T):
+        mpt.mpt_gemm_wgrad(dev16(X[t]), dev16(dY[t]), d_acc, accumulate=(t > 0))
+        acc, _ = gemm.gemm_wgrad(X[t], dY[t], out_fp32=True, acc32=acc)
+    got = host(d_acc)
+    assert fp16.ulpdist32(got, acc).max() <= 16          # FP32 accumulation order differs from FP64
+    rel = np.abs(got - acc).max() / np.abs(acc).max()
+    assert rel < 1e-6
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    d_acc[3, 3] = float("inf")
+    mpt.mpt_gemm_wgrad(dev16(X[0]), dev16(dY[0]), d_acc, accumulate=True, flag=flag)
+    assert int(flag.item()) == 1
+
+
+@pytest.mark.parametrize("scale", [1.0, 8192.0])
+def test_cfg2_square_4096(scale):
+    """The benchmark shape, in the benchmarked launch configuration, whole output compared."""
+    c = workloads.square_gemm(4096, scale=scale)
+    A, B, G = c["A"], c["B"], c["G"]
+    y, sa, s = gemm.gemm_fwd(A, B, full=True)
+    gemm_check(run_fwd(A, B), y, sa, s, "cfg2 fwd")
+    dx, sa, s = gemm.gemm_dgrad(G, B, full=True)
+    gemm_check(run_dgrad(G, B), dx, sa, s, "cfg2 dgrad S=%g" % scale)
+    dw, sa, s = gemm.gemm_wgrad(A, G, full=True)
+    gemm_check(run_wgrad(A, G), dw, sa, s, "cfg2 wgrad S=%g" % scale)
+    gb = fp16.bits(G)
+    flushed = float((c["g_true"] != 0)[(gb & 0x7FFF) == 0].mean()) if ((gb & 0x7FFF) == 0).any() else 0.0
+    print("[cfg2] S=%g: upstream gradient flushed to zero %.3f, subnormal %.3f" %
+          (scale, float(((gb & 0x7FFF) == 0).mean()), float((((gb & 0x7C00) == 0) & ((gb & 0x3FF) != 0)).mean())), flush=True)
