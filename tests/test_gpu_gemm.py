@@ -97,7 +97,7 @@ def test_overflow_stores_inf_and_raises_wgrad_flag():
     assert np.array_equal(fp16.bits(dW), fp16.bits(want))
     assert fp16.bits(dW)[0, 0] == 0x7C00 and int(flag.item()) == 1
     flag.zero_()
-    dY[:, 0] = 2.0 ** -10
+    dY[:, :] = 2.0 ** -10
     run_wgrad(X, dY, flag=flag)
     assert int(flag.item()) == 0
 
@@ -138,14 +138,17 @@ def test_wgrad_fp32_store_and_accumulate():
     X = rng.standard_normal((T, B, K)).astype(np.float16)
     dY = (rng.standard_normal((T, B, N)) * 2.0 ** -12).astype(np.float16)
     d_acc = torch.zeros((K, N), dtype=torch.float32, device="cuda")
-    acc = None
+    acc, sabs = None, 0.0
     for t in range(T):
         mpt.mpt_gemm_wgrad(dev16(X[t]), dev16(dY[t]), d_acc, accumulate=(t > 0))
-        acc, _ = gemm.gemm_wgrad(X[t], dY[t], out_fp32=True, acc32=acc)
+        acc, sa = gemm.gemm_wgrad(X[t], dY[t], out_fp32=True, acc32=acc)
+        sabs = sabs + sa
     got = host(d_acc)
-    assert fp16.ulpdist32(got, acc).max() <= 16          # FP32 accumulation order differs from FP64
-    rel = np.abs(got - acc).max() / np.abs(acc).max()
-    assert rel < 1e-6
+    # FP32 accumulation allowance against the sum of magnitudes (cancellation makes ulp counts meaningless)
+    from gpu_util import C_ACC, U32
+    assert (np.abs(got.astype(np.float64) - acc.astype(np.float64)) <= C_ACC * U32 * sabs).all()
+    well = np.abs(acc) >= sabs * 2.0 ** -4
+    assert fp16.ulpdist32(got[well], acc[well]).max() <= 64
     flag = torch.zeros(1, dtype=torch.int32, device="cuda")
     d_acc[3, 3] = float("inf")
     mpt.mpt_gemm_wgrad(dev16(X[0]), dev16(dY[0]), d_acc, accumulate=True, flag=flag)
