@@ -1,0 +1,173 @@
+#!/usr/bin/env python3
+"""Benchmark of the mixed-precision hot path on one MI355X.
+
+A "step" is one pass over the whole hot path on the square-GEMM workload
+(M = N = K = 4096): forward, backward-activation and backward-weight GEMMs
+(FP16 in, FP32 accumulate, FP16 store), then on the 16.8M-element weight
+gradient: unscale + Inf/NaN check, FP32 master update with momentum and FP16
+copy, and the device-side loss-scale policy.  Inputs are resident in HBM before
+the timed region.  Prints ONE JSON line.
+
+`value` = FLOPs of the three GEMMs / whole-step time (the update path's time is
+inside the step).  `roofline` describes the dominant kernel (the GEMM);
+`roofline_update` describes the fused master update measured on the
+116M-parameter flat buffer.  `cpu_baseline` times the CPU oracle on the host.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_F16_PEAK_TFLOPS = 2500.0     # MI355X dense FP16 matrix peak
+HBM_PEAK_GBS = 8000.0             # MI355X HBM3E peak
+N_SQUARE = 4096
+N_FLAT = 116_000_000
+# HBM traffic per GEMM launch (bytes) from rocprofv3 FETCH_SIZE/WRITE_SIZE counter runs, scaled by the
+# same counters on a copy kernel of known size; see profiles/.  None until measured.
+GEMM_TRAFFIC_BYTES = None
+UPDATE_TRAFFIC_BYTES = None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives are part of it); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import workloads
+    from paper_1710_03740_amd import binding as mpt
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    mpt.lib()                                    # fail loudly if the HIP library is missing
+    dev = "cuda"
+    n = N_SQUARE
+    c = workloads.square_gemm(n, scale=8192.0)
+
+    def d16(a):
+        return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).to(dev).view(torch.float16)
+
+    X, W16, G = d16(c["A"]), d16(c["B"]), d16(c["G"])
+    Y = torch.empty((n, n), dtype=torch.float16, device=dev)
+    dX = torch.empty((n, n), dtype=torch.float16, device=dev)
+    dW = torch.empty((n, n), dtype=torch.float16, device=dev)
+    W32 = W16.float()
+    M32 = torch.zeros_like(W32)
+    flag = torch.zeros(1, dtype=torch.int32, device=dev)
+    scaler = mpt.scaler_to_device(mpt.mpt_scaler_init(8192.0, 1000))
+    lr, mu = 1e-3, 0.9
+
+    gemm_events = []
+
+    def step(record):
+        if record:
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+            ev[0].record()
+        mpt.mpt_gemm_fwd(X, W16, Y)
+        if record:
+            ev[1].record()
+        mpt.mpt_gemm_dgrad(G, W16, dX)
+        if record:
+            ev[2].record()
+        mpt.mpt_gemm_wgrad(X, G, dW)
+        if record:
+            ev[3].record()
+            gemm_events.append(ev)
+        mpt.mpt_unscale_check(dW, 1.0 / 8192.0, flag)
+        mpt.mpt_master_update(W32, M32, dW, W16, 1.0, lr, mu, flag, scaler_dev=scaler)
+        mpt.mpt_loss_scale_update_dev(scaler, flag)
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(True)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    flops_step = 3 * 2.0 * n ** 3
+    value = flops_step / (ms_per_step * 1e-3) / 1e12
+
+    # dominant kernel: average GEMM launch duration from the HIP events recorded inside the timed region
+    durs = [ev[i].elapsed_time(ev[i + 1]) for ev in gemm_events for i in range(3)]
+    gemm_ms = sum(durs) / len(durs)
+    achieved = 2.0 * n ** 3 / (gemm_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "achieved": round(achieved, 1), "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(achieved / MFMA_F16_PEAK_TFLOPS, 4), "traffic": GEMM_TRAFFIC_BYTES,
+                "kernel": "k_gemm 256x256x64 (avg of fwd, dgrad, wgrad)", "avg_launch_us": round(gemm_ms * 1e3, 2),
+                "per_pass_us": {k: round(1e3 * sum(ev[i].elapsed_time(ev[i + 1]) for ev in gemm_events) / len(gemm_events), 2)
+                                for i, k in enumerate(("fwd", "dgrad", "wgrad"))}}
+
+    # the other half of the metric: fused master update on the 116M-parameter flat buffer
+    del X, G, Y, dX, dW, W32, M32
+    w = torch.empty(N_FLAT, dtype=torch.float32, device=dev).uniform_(-0.05, 0.05)
+    m = torch.zeros(N_FLAT, dtype=torch.float32, device=dev)
+    g = (torch.randn(N_FLAT, device=dev) * 64).to(torch.float16)
+    h = w.to(torch.float16)
+    flag.zero_()
+    for _ in range(3):
+        mpt.mpt_master_update(w, m, g, h, 2.0 ** -16, lr, mu, flag)
+    reps = max(args.steps, 10)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        mpt.mpt_master_update(w, m, g, h, 2.0 ** -16, lr, mu, flag)
+    e1.record()
+    torch.cuda.synchronize()
+    upd_ms = e0.elapsed_time(e1) / reps
+    upd_gbs = 20.0 * N_FLAT / (upd_ms * 1e-3) / 1e9
+    e0.record()
+    for _ in range(reps):
+        mpt.mpt_unscale_check(g, 2.0 ** -16, flag)
+    e1.record()
+    torch.cuda.synchronize()
+    chk_ms = e0.elapsed_time(e1) / reps
+    roofline_update = {"bound": "hbm", "achieved": round(upd_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                       "frac": round(upd_gbs / HBM_PEAK_GBS, 4), "traffic": UPDATE_TRAFFIC_BYTES,
+                       "kernel": "k_master_update (momentum, FP16 grad), 116M elements, 20 B/element",
+                       "avg_launch_us": round(upd_ms * 1e3, 2),
+                       "unscale_check_GBs": round(2.0 * N_FLAT / (chk_ms * 1e-3) / 1e9, 1)}
+    del w, m, g, h
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import gemm as ogemm
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count() or 1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        rows = 2048                                   # bounded sample: half the rows of the forward GEMM
+        t0 = time.perf_counter()
+        ogemm.gemm_fwd(c["A"][:rows], c["B"])
+        dt = time.perf_counter() - t0
+        cpu = {"value": round(2.0 * rows * n * n / dt / 1e12, 5), "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+               "sample": "oracle.gemm.gemm_fwd on %d of the %d rows of the 4096^3 forward GEMM (FP64 sum + sum of magnitudes), %.1f s" % (rows, n, dt)}
+
+    out = {"metric": "GEMM TFLOP/s (fwd+dgrad+wgrad) % FP16 peak; master-update GB/s % HBM peak",
+           "value": round(value, 1), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "fp16", "data": "synthetic",
+           "config": {"workload": "cfg2: square GEMM M=N=K=4096 fwd+dgrad+wgrad, then unscale/check + momentum master update + scaler on the 16.8M-element weight",
+                      "loss_scale": 8192, "master_update_elements": n * n},
+           "pct_of_fp16_peak": round(100 * value / MFMA_F16_PEAK_TFLOPS, 2),
+           "master_update_pct_of_hbm_peak": round(100 * upd_gbs / HBM_PEAK_GBS, 2),
+           "roofline": roofline, "roofline_update": roofline_update, "cpu_baseline": cpu}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -52,8 +52,10 @@ __device__ __forceinline__ float step1(float w, float& m, float graw, float inv,
   return __fsub_rn(w, d);
 }
 
-// 8 elements per thread per trip: one 16 B gradient load (FP16) or two (FP32),
-// two 16 B loads each of master and momentum, and the mirror-image stores.
+// 4 consecutive elements per thread per trip, and consecutive threads own consecutive
+// quads, so every load and store instruction of a wavefront covers one contiguous span
+// (1 KiB of an FP32 stream, 512 B of an FP16 stream).  Six streams move per element:
+// gradient, master and momentum in; master, momentum and FP16 copy out.
 template <bool MOM, bool G32, bool NT>
 __global__ __launch_bounds__(kThreads) void k_master_update(
     size_t n, float* __restrict__ w32, float* __restrict__ m32, const void* __restrict__ grad,
@@ -61,47 +63,42 @@ __global__ __launch_bounds__(kThreads) void k_master_update(
     const uint32_t* __restrict__ flag) {
   if (flag != nullptr && *flag != 0u) return;              // overflow: the whole step is a no-op
   const float inv = scaler != nullptr ? scaler->inv_scale : inv_scale;
-  const size_t nvec = n >> 3;
+  const size_t nquad = n >> 2;
   const size_t stride = (size_t)gridDim.x * kThreads;
-  for (size_t v = (size_t)blockIdx.x * kThreads + threadIdx.x; v < nvec; v += stride) {
-    float g[8];
+  for (size_t q = (size_t)blockIdx.x * kThreads + threadIdx.x; q < nquad; q += stride) {
+    float g[4];
     if constexpr (G32) {
-      const f4* gp = reinterpret_cast<const f4*>(grad) + 2 * v;
-      const f4 a = ld<NT>(gp), b = ld<NT>(gp + 1);
+      const f4 a = ld<NT>(reinterpret_cast<const f4*>(grad) + q);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) { g[i] = a[i]; g[4 + i] = b[i]; }
+      for (int i = 0; i < 4; ++i) g[i] = a[i];
     } else {
-      const h8 a = ld<NT>(reinterpret_cast<const h8*>(grad) + v);
+      const h4 a = ld<NT>(reinterpret_cast<const h4*>(grad) + q);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) g[i] = (float)a[i];
+      for (int i = 0; i < 4; ++i) g[i] = (float)a[i];
     }
-    f4* wp = reinterpret_cast<f4*>(w32) + 2 * v;
-    f4 w0 = ld<NT>(wp), w1 = ld<NT>(wp + 1);
-    f4 m0 = {0, 0, 0, 0}, m1 = {0, 0, 0, 0};
+    f4* wp = reinterpret_cast<f4*>(w32) + q;
+    f4 w = ld<NT>(wp);
+    f4 m = {0, 0, 0, 0};
     f4* mp = nullptr;
     if constexpr (MOM) {
-      mp = reinterpret_cast<f4*>(m32) + 2 * v;
-      m0 = ld<NT>(mp);
-      m1 = ld<NT>(mp + 1);
+      mp = reinterpret_cast<f4*>(m32) + q;
+      m = ld<NT>(mp);
     }
-    h8 h;
+    h4 h;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      float ma = m0[i], mb = m1[i];
-      w0[i] = step1<MOM>(w0[i], ma, g[i], inv, lr, mu);
-      w1[i] = step1<MOM>(w1[i], mb, g[4 + i], inv, lr, mu);
-      m0[i] = ma; m1[i] = mb;
-      h[i] = (_Float16)w0[i];
-      h[4 + i] = (_Float16)w1[i];
+      float mi = m[i];
+      w[i] = step1<MOM>(w[i], mi, g[i], inv, lr, mu);
+      m[i] = mi;
+      h[i] = (_Float16)w[i];
     }
-    st<NT>(wp, w0);
-    st<NT>(wp + 1, w1);
-    if constexpr (MOM) { st<NT>(mp, m0); st<NT>(mp + 1, m1); }
-    st<NT>(reinterpret_cast<h8*>(w16) + v, h);
+    st<NT>(wp, w);
+    if constexpr (MOM) st<NT>(mp, m);
+    st<NT>(reinterpret_cast<h4*>(w16) + q, h);
   }
-  // ragged tail (< 8 elements), one element per thread of block 0
+  // ragged tail (< 4 elements), one element per thread of block 0
   if (blockIdx.x == 0) {
-    const size_t i = (nvec << 3) + threadIdx.x;
+    const size_t i = (nquad << 2) + threadIdx.x;
     if (i < n) {
       float graw;
       if constexpr (G32) graw = reinterpret_cast<const float*>(grad)[i];
@@ -388,7 +385,7 @@ extern "C" int mpt_master_update(void* stream, size_t n, float* w32, float* m32,
   const bool mom = m32 != nullptr;
   const bool g32 = grad_is_fp32 != 0;
   if (vec) {
-    const unsigned grid = grid_for((n + 7) / 8);
+    const unsigned grid = grid_for((n + 3) / 4);
 #define MPT_MU(M, G, T) hipLaunchKernelGGL((k_master_update<M, G, T>), dim3(grid), dim3(kThreads), 0, s, n, w32, m32, grad, w16, inv_scale, scaler, lr, momentum, flag)
     const int sel = (mom ? 4 : 0) | (g32 ? 2 : 0) | (nt ? 1 : 0);
     switch (sel) {
