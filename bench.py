@@ -27,9 +27,9 @@ HBM_PEAK_GBS = 8000.0             # MI355X HBM3E peak
 N_SQUARE = 4096
 N_FLAT = 116_000_000
 # HBM traffic per GEMM launch (bytes) from rocprofv3 FETCH_SIZE/WRITE_SIZE counter runs, scaled by the
-# same counters on a copy kernel of known size; see profiles/.  None until measured.
-GEMM_TRAFFIC_BYTES = None
-UPDATE_TRAFFIC_BYTES = None
+# same counters on a copy kernel of known size; see profiles/k_gemm_and_update_hbm_traffic.md.
+GEMM_TRAFFIC_BYTES = 235.4e6      # 201.8 MB read + 33.6 MB written per 4096^3 launch
+UPDATE_TRAFFIC_BYTES = 2320.0e6   # 1160 MB read + 1160 MB written per 116M-element launch
 
 
 def main():
@@ -38,6 +38,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy, so a counter run of this command holds a kernel of known traffic")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives are part of it); use --gpus 1", file=sys.stderr)
@@ -88,6 +90,14 @@ def main():
         mpt.mpt_unscale_check(dW, 1.0 / 8192.0, flag)
         mpt.mpt_master_update(W32, M32, dW, W16, 1.0, lr, mu, flag, scaler_dev=scaler)
         mpt.mpt_loss_scale_update_dev(scaler, flag)
+
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB read + 1 GiB written per copy
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step(False)
@@ -150,12 +160,14 @@ def main():
             cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count() or 1])
         except Exception:
             cores = os.cpu_count() or 1
-        rows = 2048                                   # bounded sample: half the rows of the forward GEMM
-        t0 = time.perf_counter()
-        ogemm.gemm_fwd(c["A"][:rows], c["B"])
+        t0 = time.perf_counter()                      # bounded sample: one pass of each of the three GEMMs
+        ogemm.gemm_fwd(c["A"], c["B"])
+        ogemm.gemm_dgrad(c["G"], c["B"])
+        ogemm.gemm_wgrad(c["A"], c["G"])
         dt = time.perf_counter() - t0
-        cpu = {"value": round(2.0 * rows * n * n / dt / 1e12, 5), "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
-               "sample": "oracle.gemm.gemm_fwd on %d of the %d rows of the 4096^3 forward GEMM (FP64 sum + sum of magnitudes), %.1f s" % (rows, n, dt)}
+        cpu = {"value": round(flops_step / dt / 1e12, 5), "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+               "sample": "oracle gemm_fwd + gemm_dgrad + gemm_wgrad once each at 4096^3 (each: FP64 matmul, FP64 matmul of magnitudes, "
+                         "one FP16 rounding); %.1f s wall" % dt}
 
     out = {"metric": "GEMM TFLOP/s (fwd+dgrad+wgrad) % FP16 peak; master-update GB/s % HBM peak",
            "value": round(value, 1), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
