@@ -1,0 +1,168 @@
+"""GPU parity for the composed workloads: the two-layer perceptron step (glue
+kernels + GEMMs + update) and the projected-LSTM layer's GEMMs, against the
+oracle.  Stages are teacher-forced: each GPU stage receives the oracle's FP16
+inputs for that stage, so every comparison is per operation."""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from oracle import fp16, gemm, loss, mlp, update
+from paper_1710_03740_amd import binding as mpt
+from gpu_util import dev, dev16, host, host16, gemm_check, C_ACC, U32
+
+pytestmark = pytest.mark.gpu
+
+
+def _empty16(*shape):
+    return torch.full(shape, float("nan"), dtype=torch.float16, device="cuda")
+
+
+def test_relu_and_softmax_glue():
+    rng = np.random.default_rng(0)
+    y = (rng.standard_normal(10007) * 2).astype(np.float16)
+    y[:4] = [0.0, -0.0, np.inf, -np.inf]
+    dh = rng.standard_normal(10007).astype(np.float16)
+    h, dy = _empty16(10007), _empty16(10007)
+    mpt.mpt_relu_fwd(dev16(y), h)
+    mpt.mpt_relu_bwd(dev16(dh), dev16(y), dy)
+    assert np.array_equal(fp16.bits(host16(h)), fp16.bits(loss.relu_fwd(y)))
+    assert np.array_equal(fp16.bits(host16(dy)), fp16.bits(loss.relu_bwd(dh, y)))
+    # unaligned views take the scalar path
+    h2 = _empty16(10008)
+    mpt.mpt_relu_fwd(dev16(y)[1:], h2[2:10008])
+    assert np.array_equal(fp16.bits(host16(h2)[2:]), fp16.bits(loss.relu_fwd(y[1:])))
+    for B, C, S in ((256, 10, 1024.0), (33, 1000, 128.0), (5, 4096, 1.0)):
+        z = (rng.standard_normal((B, C)) * 3).astype(np.float16)
+        lab = rng.integers(0, C, B).astype(np.int32)
+        L, d = loss.softmax_xent_scaled(z, lab, S)
+        d_d, d_L = _empty16(B, C), torch.zeros(1, dtype=torch.float32, device="cuda")
+        mpt.mpt_softmax_xent_scaled(dev16(z), dev(lab), S, d_d, d_L)
+        dist = fp16.ulpdist16(fp16.bits(host16(d_d)), fp16.bits(d))
+        assert dist.max() <= 1 and (dist > 0).mean() < 0.02, (B, C, dist.max(), (dist > 0).mean())
+        assert abs(float(d_L.item()) - L) < 2e-6 * max(1.0, abs(L))
+
+
+def test_cfg1_mlp_step_teacher_forced():
+    c = workloads.mlp()
+    o = mlp.mlp_step(c["x"], c["labels"], c["w1_32"], c["w2_32"], c["w1_16"], c["w2_16"], c["scale"], c["lr"])
+    x, w1, w2 = dev16(c["x"]), dev16(c["w1_16"]), dev16(c["w2_16"])
+    S, inv = c["scale"], 1.0 / c["scale"]
+
+    def chk(got, want16, a16, b16, op, label):
+        ref = {"fwd": gemm.gemm_fwd, "dgrad": gemm.gemm_dgrad, "wgrad": gemm.gemm_wgrad}[op](a16, b16, full=True)
+        assert np.array_equal(fp16.bits(ref[0]), fp16.bits(want16))
+        gemm_check(host16(got), ref[0], ref[1], ref[2], "cfg1 " + label)
+
+    y1 = _empty16(256, 1024); mpt.mpt_gemm_fwd(x, w1, y1)
+    chk(y1, o["y1"], c["x"], c["w1_16"], "fwd", "fwd1")
+    h1 = _empty16(256, 1024); mpt.mpt_relu_fwd(dev16(o["y1"]), h1)
+    assert np.array_equal(fp16.bits(host16(h1)), fp16.bits(o["h1"]))
+    logits = _empty16(256, 10); mpt.mpt_gemm_fwd(dev16(o["h1"]), w2, logits)          # N = 10: element-wise loader path
+    chk(logits, o["logits"], o["h1"], c["w2_16"], "fwd", "fwd2")
+    dlog, L = _empty16(256, 10), torch.zeros(1, dtype=torch.float32, device="cuda")
+    mpt.mpt_softmax_xent_scaled(dev16(o["logits"]), dev(c["labels"]), S, dlog, L)
+    dist = fp16.ulpdist16(fp16.bits(host16(dlog)), fp16.bits(o["dlogits"]))
+    assert dist.max() <= 1 and abs(float(L.item()) - o["loss"]) < 1e-5
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    dw2 = _empty16(1024, 10); mpt.mpt_gemm_wgrad(dev16(o["h1"]), dev16(o["dlogits"]), dw2, flag=flag)
+    chk(dw2, o["dw2"], o["h1"], o["dlogits"], "wgrad", "wgrad2")
+    dh1 = _empty16(256, 1024); mpt.mpt_gemm_dgrad(dev16(o["dlogits"]), w2, dh1)
+    chk(dh1, o["dh1"], o["dlogits"], c["w2_16"], "dgrad", "dgrad2")
+    dy1 = _empty16(256, 1024); mpt.mpt_relu_bwd(dev16(o["dh1"]), dev16(o["y1"]), dy1)
+    assert np.array_equal(fp16.bits(host16(dy1)), fp16.bits(o["dy1"]))
+    dw1 = _empty16(1024, 1024); mpt.mpt_gemm_wgrad(x, dev16(o["dy1"]), dw1, flag=flag)
+    chk(dw1, o["dw1"], c["x"], o["dy1"], "wgrad", "wgrad1")
+    assert int(flag.item()) == o["flag"] == 0
+    # update both tensors from the oracle's gradients: bit-exact masters and copies
+    for g16, w32, w16, name in ((o["dw1"], c["w1_32"], c["w1_16"], "w1"), (o["dw2"], c["w2_32"], c["w2_16"], "w2")):
+        d_w, d_h = dev(w32.reshape(-1).copy()), dev16(w16.reshape(-1).copy())
+        mpt.mpt_unscale_check(dev16(g16.reshape(-1)), inv, flag)
+        mpt.mpt_master_update(d_w, None, dev16(g16.reshape(-1)), d_h, inv, c["lr"], 0.0, flag)
+        assert np.array_equal(host(d_w).view(np.uint32), o[name + "_32"].reshape(-1).view(np.uint32))
+        assert np.array_equal(fp16.bits(host16(d_h)), fp16.bits(o[name + "_16"].reshape(-1)))
+
+
+def test_cfg1_mlp_free_running_device_only():
+    """Three whole steps on the device with no host round trip inside a step; compared loosely (errors of
+    one FP16 step propagate) and for sanity: the loss falls."""
+    c = workloads.mlp()
+    x, lab = dev16(c["x"]), dev(c["labels"])
+    w1_32, w2_32 = dev(c["w1_32"].copy()), dev(c["w2_32"].copy())
+    w1, w2 = dev16(c["w1_16"]), dev16(c["w2_16"])
+    S, inv, lr = c["scale"], 1.0 / c["scale"], 0.05
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    L = torch.zeros(1, dtype=torch.float32, device="cuda")
+    y1, h1, logits, dlog = _empty16(256, 1024), _empty16(256, 1024), _empty16(256, 10), _empty16(256, 10)
+    dw2, dh1, dy1, dw1 = _empty16(1024, 10), _empty16(256, 1024), _empty16(256, 1024), _empty16(1024, 1024)
+    ow = (c["w1_32"], c["w2_32"], c["w1_16"], c["w2_16"])
+    losses, olosses = [], []
+    for _ in range(3):
+        mpt.mpt_gemm_fwd(x, w1, y1); mpt.mpt_relu_fwd(y1, h1); mpt.mpt_gemm_fwd(h1, w2, logits)
+        mpt.mpt_softmax_xent_scaled(logits, lab, S, dlog, L)
+        mpt.mpt_gemm_wgrad(h1, dlog, dw2, flag=flag); mpt.mpt_gemm_dgrad(dlog, w2, dh1)
+        mpt.mpt_relu_bwd(dh1, y1, dy1); mpt.mpt_gemm_wgrad(x, dy1, dw1, flag=flag)
+        mpt.mpt_master_update(w1_32, None, dw1, w1, inv, lr, 0.0, flag)
+        mpt.mpt_master_update(w2_32, None, dw2, w2, inv, lr, 0.0, flag)
+        losses.append(float(L.item()))
+        o = mlp.mlp_step(c["x"], c["labels"], *ow, S, lr)
+        ow = (o["w1_32"], o["w2_32"], o["w1_16"], o["w2_16"])
+        olosses.append(o["loss"])
+    assert int(flag.item()) == 0
+    assert losses[-1] < losses[0] and abs(losses[0] - np.log(10)) < 0.5
+    assert np.allclose(losses, olosses, rtol=2e-3)
+    assert np.abs(host(w1_32) - ow[0]).max() < 1e-4 * np.abs(ow[0]).max() + 1e-6
+
+
+@pytest.mark.parametrize("t", [0, 19])
+def test_cfg3_lstmp_gemms_teacher_forced(t):
+    c = workloads.lstmp(steps=20)
+    Wg, Wp = dev16(c["Wg"]), dev16(c["Wp"])
+    xh, h, dg, dr = c["xh"][t], c["h"][t], c["dgates"][t], c["dr"][t]
+    B = xh.shape[0]
+    ws = torch.empty(max(mpt.mpt_gemm_workspace_bytes(0, B, 32768, 2048), mpt.mpt_gemm_workspace_bytes(1, B, 32768, 2048),
+                         mpt.mpt_gemm_workspace_bytes(0, B, 1024, 8192), mpt.mpt_gemm_workspace_bytes(1, B, 1024, 8192), 16) // 4,
+                     dtype=torch.float32, device="cuda")
+    gates = _empty16(B, 32768); mpt.mpt_gemm_fwd(dev16(xh), Wg, gates, ws)
+    r = gemm.gemm_fwd(xh, c["Wg"], full=True); gemm_check(host16(gates), *r, "cfg3 gate fwd t=%d" % t)
+    proj = _empty16(B, 1024); mpt.mpt_gemm_fwd(dev16(h), Wp, proj, ws)
+    r = gemm.gemm_fwd(h, c["Wp"], full=True); gemm_check(host16(proj), *r, "cfg3 proj fwd")
+    dxh = _empty16(B, 2048); mpt.mpt_gemm_dgrad(dev16(dg), Wg, dxh, ws)
+    r = gemm.gemm_dgrad(dg, c["Wg"], full=True); gemm_check(host16(dxh), *r, "cfg3 gate dgrad")
+    dh = _empty16(B, 8192); mpt.mpt_gemm_dgrad(dev16(dr), Wp, dh, ws)
+    r = gemm.gemm_dgrad(dr, c["Wp"], full=True); gemm_check(host16(dh), *r, "cfg3 proj dgrad")
+
+
+def test_cfg3_wgrad_over_timesteps():
+    """Weight gradients summed over the 20 timesteps two ways: one time-batched contraction with an FP16
+    store (rows of the 2048x32768 result sampled for the oracle), and per-timestep FP32 accumulation for
+    the projection weights, which then feed the master update as FP32 gradients."""
+    c = workloads.lstmp(steps=20)
+    T, B = c["xh"].shape[:2]
+    xh_all, dg_all = c["xh"].reshape(T * B, -1), c["dgates"].reshape(T * B, -1)
+    ws = torch.empty(max(mpt.mpt_gemm_workspace_bytes(2, T * B, 32768, 2048), 16) // 4, dtype=torch.float32, device="cuda")
+    dWg = _empty16(2048, 32768)
+    mpt.mpt_gemm_wgrad(dev16(xh_all), dev16(dg_all), dWg, ws=ws)
+    rows = np.random.default_rng(3).choice(2048, 96, replace=False)
+    r = gemm.gemm_wgrad(np.ascontiguousarray(xh_all[:, rows]), dg_all, full=True)
+    gemm_check(np.ascontiguousarray(host16(dWg)[rows]), *r, "cfg3 gate wgrad time-batched (96 sampled rows)")
+    # projection weights: FP32 running sum across timesteps
+    acc_dev = torch.zeros((8192, 1024), dtype=torch.float32, device="cuda")
+    acc, sabs = None, 0.0
+    for t in range(T):
+        mpt.mpt_gemm_wgrad(dev16(c["h"][t]), dev16(c["dr"][t]), acc_dev, accumulate=(t > 0))
+        acc, sa = gemm.gemm_wgrad(c["h"][t], c["dr"][t], out_fp32=True, acc32=acc)
+        sabs = sabs + sa
+    got = host(acc_dev)
+    assert (np.abs(got.astype(np.float64) - acc.astype(np.float64)) <= C_ACC * U32 * sabs).all()
+    # FP32 gradients into the master update
+    w32 = c["Wp"].astype(np.float32).reshape(-1)
+    d_w, d_h = dev(w32.copy()), dev16(c["Wp"].reshape(-1).copy())
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    inv = float(np.float32(1.0 / c["scale"]))
+    mpt.mpt_unscale_check(acc_dev.view(-1), inv, flag)
+    mpt.mpt_master_update(d_w, None, acc_dev.view(-1), d_h, inv, 0.01, 0.0, flag)
+    wn, _, hn = update.master_update(w32, None, got.reshape(-1), inv, 0.01, 0.0, 0)
+    assert int(flag.item()) == 0
+    assert np.array_equal(host(d_w).view(np.uint32), wn.view(np.uint32))
+    assert np.array_equal(fp16.bits(host16(d_h)), fp16.bits(hn))
