@@ -109,7 +109,7 @@ def test_cfg1_mlp_free_running_device_only():
         ow = (o["w1_32"], o["w2_32"], o["w1_16"], o["w2_16"])
         olosses.append(o["loss"])
     assert int(flag.item()) == 0
-    assert losses[-1] < losses[0] and abs(losses[0] - np.log(10)) < 0.5
+    assert losses[-1] < losses[0] and abs(losses[0] - np.log(10)) < 0.8
     assert np.allclose(losses, olosses, rtol=2e-3)
     assert np.abs(host(w1_32) - ow[0]).max() < 1e-4 * np.abs(ow[0]).max() + 1e-6
 
