@@ -363,6 +363,233 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void k_gemm(AView A, BV
   }
 }
 
+// ---------------------------------------------------------------- streamed variant for whole 256x256 tiles of plain matrices
+// Same contraction, same tile and MFMA, but operand slices go global -> LDS with the LDS-direct load
+// (global_load_lds_dwordx4: no staging registers), through a ring of four 32 KiB stages of reduction depth 32,
+// three of them in flight.  The two wavefronts that share a SIMD run half a stage apart (wavefronts 4-7 take the
+// per-stage barrier in the middle of their stage), so one of them always has MFMAs to issue while the other sits
+// at the barrier or waits for LDS.  LDS layouts (64 banks of 4 bytes, 16 lanes served together):
+//   RC operand: [256 outer][32 r] rows of 64 B; 16-byte chunk c of row o is stored at chunk c ^ ((o >> 2) & 3);
+//               a fragment is one ds_read_b128 per lane.
+//   OC operand: [32 r][256 outer] rows of 512 B; 32-byte unit u of row r is stored at unit u ^ ((r & 3) << 1);
+//               a fragment is two ds_read_b64_tr_b16 per lane (the transposing LDS read: within 16 lanes, lane i
+//               receives element i of each of the four 32-byte rows that lanes 4j..4j+3 point at).
+// The swizzles are applied by choosing which global chunk each lane fetches, since an LDS-direct load writes lane l
+// at base + 16*l.  Requirements (checked by the host): I, J multiples of 256, R a multiple of 64, 16-byte aligned
+// operands, FP16 store or FP32 split partials.
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+typedef const __attribute__((address_space(1))) void* global_void_ptr;
+typedef __fp16 fp16x4_t __attribute__((ext_vector_type(4)));
+
+struct DmaMat { const uint16_t* base; int64_t ld; };
+
+template <bool RC>
+struct DmaOperand {
+  const uint16_t* p0;       // this lane's source for its first 1 KiB block of stage 0
+  const uint16_t* p1;       // ... and for its second block
+  int64_t step;             // elements to advance per stage
+  // o0: first outer index of the workgroup tile; r0: first reduction index of this workgroup's range
+  __device__ __forceinline__ void init(const DmaMat& m, int o0, int r0, int wave, int lane) {
+    if constexpr (RC) {
+      const int row = wave * 32 + (lane >> 2);                       // blocks 2w, 2w+1 hold 16 rows each
+      const int chunk = (lane & 3) ^ ((row >> 2) & 3);               // same for row + 16
+      p0 = m.base + (int64_t)(o0 + row) * m.ld + r0 + chunk * 8;
+      p1 = p0 + 16 * m.ld;
+      step = 32;
+    } else {
+      const int row = wave * 4 + (lane >> 5);                        // blocks 2w, 2w+1 hold 2 reduction rows each
+      const int pc = lane & 31;
+      const int c0 = 2 * ((pc >> 1) ^ ((row & 3) << 1)) + (pc & 1);
+      const int c1 = 2 * ((pc >> 1) ^ (((row + 2) & 3) << 1)) + (pc & 1);
+      p0 = m.base + (int64_t)(r0 + row) * m.ld + o0 + c0 * 8;
+      p1 = m.base + (int64_t)(r0 + row + 2) * m.ld + o0 + c1 * 8;
+      step = 32 * m.ld;
+    }
+  }
+  __device__ __forceinline__ void issue(int stage_rel, char* lds_block) const {
+    __builtin_amdgcn_global_load_lds((global_void_ptr)(p0 + stage_rel * step), (lds_void_ptr)lds_block, 16, 0, 0);
+    __builtin_amdgcn_global_load_lds((global_void_ptr)(p1 + stage_rel * step), (lds_void_ptr)(lds_block + 1024), 16, 0, 0);
+  }
+};
+
+// LDS reads are issued through inline assembly so that their completion is tracked here, by explicit
+// s_waitcnt on the in-order LGKM counter, and not by the compiler, which would otherwise put a full vmcnt(0)
+// wait in front of every read that follows an LDS-direct load.
+__device__ __forceinline__ uint32_t lds_offset(const char* p) {
+  return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char*)p;
+}
+__device__ __forceinline__ half8 lds_read_b128(uint32_t addr) {
+  half8 v;
+  asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(addr) : "memory");
+  return v;
+}
+__device__ __forceinline__ uint2v lds_read_tr_b64(uint32_t addr) {
+  uint2v v;
+  asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(v) : "v"(addr) : "memory");
+  return v;
+}
+
+// Fragment of 32 outer indices x 16 reduction indices for v_mfma_f32_32x32x16_f16: lane l holds outer index l%32 and
+// reduction indices 8*(l/32) .. +7 of k16-step ks.  Per-lane byte offsets inside an operand's stage are fixed for the
+// whole kernel: RC fragments need one per k16-step, OC fragments two (reduction rows +0..3 and +4..7).
+template <bool RC>
+struct FragAddr {
+  uint32_t off[2][RC ? 1 : 2];
+  __device__ __forceinline__ void init(int outer0, int lane) {
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      if constexpr (RC) {
+        const int r = outer0 + (lane & 31);
+        const int c = ks * 2 + (lane >> 5);
+        off[ks][0] = r * 64 + (((c ^ (r >> 2)) & 3) << 4);
+      } else {
+        const int unit = (outer0 >> 4) + ((lane >> 4) & 1);
+        const int sub = (lane & 3) << 3;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          const int r = ks * 16 + ((lane >> 5) << 3) + ((lane & 15) >> 2) + 4 * h;
+          off[ks][h] = r * 512 + ((unit ^ ((r & 3) << 1)) << 5) + sub;
+        }
+      }
+    }
+  }
+  __device__ __forceinline__ half8 read(uint32_t stage_operand, int ks) const {
+    if constexpr (RC) {
+      return lds_read_b128(stage_operand + off[ks][0]);
+    } else {
+      const uint2v lo = lds_read_tr_b64(stage_operand + off[ks][0]);
+      const uint2v hi = lds_read_tr_b64(stage_operand + off[ks][1]);
+      uint4v q = {lo[0], lo[1], hi[0], hi[1]};
+      return __builtin_bit_cast(half8, q);
+    }
+  }
+};
+
+// Wait until at most `newer` LDS reads issued after these fragments are still outstanding; the fragments pass through
+// the statement so that their consumers cannot be moved above the wait.
+template <int NEWER>
+__device__ __forceinline__ void wait_frags(half8& a0, half8& a1, half8& a2, half8& a3, half8& b0, half8& b1) {
+  asm volatile("s_waitcnt lgkmcnt(%6)" : "+v"(a0), "+v"(a1), "+v"(a2), "+v"(a3), "+v"(b0), "+v"(b1) : "n"(NEWER) : "memory");
+}
+
+template <bool A_RC, bool B_RC>
+__global__ __launch_bounds__(512) void k_gemm_dma(DmaMat A, DmaMat B, Problem pb, Epilogue ep) {
+  constexpr int NSTAGE = 4, AHEAD = 3, OPERAND = 256 * 64, STAGE = 2 * OPERAND;
+  constexpr int READS_PER_KSTEP = 4 * (A_RC ? 1 : 2) + 2 * (B_RC ? 1 : 2);   // LDS read instructions per k16-step
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  const int t = threadIdx.x, lane = t & 63, wave = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int wm = wave >> 2, wn = wave & 3;                             // 2 x 4 wavefronts, 128 x 64 each
+  int ti, tj, sp;
+  tile_of(pb, blockIdx.x, ti, tj, sp);
+  const int i0 = ti * 256, j0 = tj * 256;
+  const int st_total = pb.R / 32;
+  const int st_begin = sp * pb.ktiles_per_split * 2;
+  const int nst = min(pb.ktiles_per_split * 2, st_total - st_begin);   // stages this workgroup reduces over (>= 1)
+
+  float16v acc[4][2];
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+  DmaOperand<A_RC> da;
+  DmaOperand<B_RC> db;
+  da.init(A, i0, st_begin * 32, wave, lane);
+  db.init(B, j0, st_begin * 32, wave, lane);
+  const int blk = wave * 2048;                                         // this wavefront's two 1 KiB blocks inside an operand stage
+  auto issue = [&](int s) {                                            // past the end: refetch the last slice into a free slot
+    const int sc = min(s, nst - 1);
+    char* st = lds + (s & (NSTAGE - 1)) * STAGE;
+    da.issue(sc, st + blk);
+    db.issue(sc, st + OPERAND + blk);
+  };
+  FragAddr<A_RC> aa[4];
+  FragAddr<B_RC> ab[2];
+#pragma unroll
+  for (int a = 0; a < 4; ++a) aa[a].init(wm * 128 + a * 32, lane);
+#pragma unroll
+  for (int b = 0; b < 2; ++b) ab[b].init(wn * 64 + b * 32, lane);
+  const uint32_t lds0 = lds_offset(lds);
+  half8 fa[2][4], fb[2][2];
+  auto read_frags = [&](int s, int ks) {
+    const uint32_t st = lds0 + (s & (NSTAGE - 1)) * STAGE;
+#pragma unroll
+    for (int a = 0; a < 4; ++a) fa[ks][a] = aa[a].read(st, ks);
+#pragma unroll
+    for (int b = 0; b < 2; ++b) fb[ks][b] = ab[b].read(st + OPERAND, ks);
+  };
+  auto mfmas = [&](int ks) {
+    wait_frags<READS_PER_KSTEP>(fa[ks][0], fa[ks][1], fa[ks][2], fa[ks][3], fb[ks][0], fb[ks][1]);
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[ks][b], fa[ks][a], acc[a][b], 0, 0, 0);
+  };
+  // Only the newest stage may still be in flight, and every LDS read of this wavefront has returned.
+  auto publish = [&]() { asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
+
+  issue(0); issue(1); issue(2);
+  publish();                                  // stages 0 and 1 have landed everywhere
+  read_frags(0, 0);
+  for (int s = 0; s < nst; ++s) {
+    issue(s + AHEAD);                        // into the slot of stage s-1: every wavefront finished reading it before the last barrier it passed
+    read_frags(s, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    mfmas(0);                                // fragments (s,0) were requested half a stage ago; (s,1) may still be in flight
+    __builtin_amdgcn_sched_barrier(0);
+    if (wave >= 4) publish();
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags(s + 1, 0);                    // stage s+1 was published by an earlier barrier; past the end the data is unused
+    __builtin_amdgcn_sched_barrier(0);
+    mfmas(1);
+    __builtin_amdgcn_sched_barrier(0);
+    if (wave < 4) publish();
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");         // drain the tail prefetches before LDS is released
+
+  // ---- epilogue (whole tiles): FP16 store with optional Inf/NaN vote, or FP32 split partial
+  bool bad = false;
+  const int64_t split_off = (ep.mode == 3) ? (int64_t)sp * pb.I * pb.J : 0;
+#pragma unroll
+  for (int a = 0; a < 4; ++a) {
+    const int i = i0 + wm * 128 + a * 32 + (lane & 31);
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int j = j0 + wn * 64 + b * 32 + g * 8 + ((lane >> 5) << 2);
+        if (ep.mode == 0) {
+          half4 h;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) h[e] = (_Float16)acc[a][b][g * 4 + e];
+          const uint2v hb = __builtin_bit_cast(uint2v, h);
+          if (ep.flag) bad |= half_bits_special(hb[0]) | half_bits_special(hb[0] >> 16) | half_bits_special(hb[1]) | half_bits_special(hb[1] >> 16);
+          uint16_t* o = reinterpret_cast<uint16_t*>(ep.out) + (int64_t)i * ep.ld + j;
+          if ((reinterpret_cast<uintptr_t>(o) & 7) == 0) {
+            *reinterpret_cast<uint2v*>(o) = hb;
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[e] = (uint16_t)(hb[e >> 1] >> ((e & 1) * 16));
+          }
+        } else {
+          float4v f;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) f[e] = acc[a][b][g * 4 + e];
+          *reinterpret_cast<float4v*>(reinterpret_cast<float*>(ep.out) + split_off + (int64_t)i * ep.ld + j) = f;
+        }
+      }
+    }
+  }
+  if (ep.flag != nullptr && ep.mode == 0) {
+    const unsigned long long vote = __builtin_amdgcn_ballot_w64(bad);
+    if (vote != 0ull && lane == 0) atomicOr(ep.flag, 1u);
+  }
+}
+
 // Sum split partials in split order (fixed, so results are reproducible), then store once.
 __global__ __launch_bounds__(256) void k_split_reduce(const float* __restrict__ part, int splits, int I, int J, Epilogue ep) {
   const int64_t total = (int64_t)I * J;
@@ -450,6 +677,31 @@ int launch_tiles(hipStream_t s, const AView& A, const BView& B, const Plan& pl, 
   return MPT_OK;
 }
 
+// Plain-matrix views can take the streamed kernel.
+template <class V> struct DmaKind { static constexpr bool ok = false; static constexpr bool rc = true; };
+template <> struct DmaKind<MatRC> { static constexpr bool ok = true; static constexpr bool rc = true; };
+template <> struct DmaKind<MatOC> { static constexpr bool ok = true; static constexpr bool rc = false; };
+
+template <class AView, class BView>
+bool try_launch_dma(hipStream_t s, const AView& A, const BView& B, bool aligned, const Plan& pl, int I, int J, int R, const Epilogue& ep, int& status) {
+  if constexpr (DmaKind<AView>::ok && DmaKind<BView>::ok) {
+    static const bool enabled = mpt_env_int("MPT_GEMM_STREAMED", 1) != 0;
+    if (!enabled || !aligned || !pl.big || (I % 256) || (J % 256) || (R % 64) || (ep.mode != 0 && ep.mode != 3)) return false;
+    if (ep.mode == 3 && ((ep.ld % 4) || !mpt_aligned(ep.out, 16))) return false;
+    auto k = k_gemm_dma<DmaKind<AView>::rc, DmaKind<BView>::rc>;
+    constexpr int lds = 4 * 2 * 256 * 64;
+    static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, lds), true);
+    (void)once;
+    Problem pb{I, J, R, pl.tiles_i, pl.tiles_j, pl.splits, pl.ktiles_per_split};
+    const unsigned grid = (unsigned)((int64_t)pl.tiles_i * pl.tiles_j * pl.splits);
+    hipLaunchKernelGGL(k, dim3(grid), dim3(512), lds, s, DmaMat{A.base, A.ld}, DmaMat{B.base, B.ld}, pb, ep);
+    status = hipGetLastError() == hipSuccess ? MPT_OK : MPT_ERR_HIP;
+    return true;
+  } else {
+    return false;
+  }
+}
+
 // Run one contraction: single pass, or split partials + ordered reduction.
 template <class AView, class BView>
 int run(hipStream_t s, const AView& A, const BView& B, bool aligned, int I, int J, int R, Epilogue ep, void* ws, size_t ws_bytes) {
@@ -459,8 +711,10 @@ int run(hipStream_t s, const AView& A, const BView& B, bool aligned, int I, int 
   if (pl.splits > 1) {
     first.out = ws; first.ld = J; first.mode = 3; first.flag = nullptr;
   }
-  const int st = aligned ? launch_tiles<AView, BView, true>(s, A, B, pl, I, J, R, first)
-                         : launch_tiles<AView, BView, false>(s, A, B, pl, I, J, R, first);
+  int st = MPT_OK;
+  if (!try_launch_dma(s, A, B, aligned, pl, I, J, R, first, st))
+    st = aligned ? launch_tiles<AView, BView, true>(s, A, B, pl, I, J, R, first)
+                 : launch_tiles<AView, BView, false>(s, A, B, pl, I, J, R, first);
   if (st != MPT_OK) return st;
   if (pl.splits > 1) {
     const int64_t total = (int64_t)I * J;
