@@ -56,16 +56,16 @@ __device__ __forceinline__ float step1(float w, float& m, float graw, float inv,
 // quads, so every load and store instruction of a wavefront covers one contiguous span
 // (1 KiB of an FP32 stream, 512 B of an FP16 stream).  Six streams move per element:
 // gradient, master and momentum in; master, momentum and FP16 copy out.
-template <bool MOM, bool G32, bool NT>
-__global__ __launch_bounds__(kThreads) void k_master_update(
+template <bool MOM, bool G32, bool NT, int BS>
+__global__ __launch_bounds__(BS) void k_master_update(
     size_t n, float* __restrict__ w32, float* __restrict__ m32, const void* __restrict__ grad,
     uint16_t* __restrict__ w16, float inv_scale, const mpt_scaler* __restrict__ scaler, float lr, float mu,
     const uint32_t* __restrict__ flag) {
   if (flag != nullptr && *flag != 0u) return;              // overflow: the whole step is a no-op
   const float inv = scaler != nullptr ? scaler->inv_scale : inv_scale;
   const size_t nquad = n >> 2;
-  const size_t stride = (size_t)gridDim.x * kThreads;
-  for (size_t q = (size_t)blockIdx.x * kThreads + threadIdx.x; q < nquad; q += stride) {
+  const size_t stride = (size_t)gridDim.x * BS;
+  for (size_t q = (size_t)blockIdx.x * BS + threadIdx.x; q < nquad; q += stride) {
     float g[4];
     if constexpr (G32) {
       const f4 a = ld<NT>(reinterpret_cast<const f4*>(grad) + q);
@@ -385,8 +385,19 @@ extern "C" int mpt_master_update(void* stream, size_t n, float* w32, float* m32,
   const bool mom = m32 != nullptr;
   const bool g32 = grad_is_fp32 != 0;
   if (vec) {
-    const unsigned grid = grid_for((n + 3) / 4);
-#define MPT_MU(M, G, T) hipLaunchKernelGGL((k_master_update<M, G, T>), dim3(grid), dim3(kThreads), 0, s, n, w32, m32, grad, w16, inv_scale, scaler, lr, momentum, flag)
+    static const int bs = mpt_env_int("MPT_EW_BLOCK", 64);              // 64 or 256 (tuning only)
+    const size_t quads = (n + 3) / 4;
+#define MPT_MU(M, G, T)                                                                                                   \
+  do {                                                                                                                    \
+    if (bs == 64) {                                                                                                       \
+      const size_t blocks = (quads + 63) / 64;                                                                            \
+      hipLaunchKernelGGL((k_master_update<M, G, T, 64>), dim3((unsigned)(blocks > 0x7FFFFFFFu ? 0x7FFFFFFFu : blocks)), dim3(64), 0, s, n, w32, m32, \
+                         grad, w16, inv_scale, scaler, lr, momentum, flag);                                                 \
+    } else {                                                                                                              \
+      hipLaunchKernelGGL((k_master_update<M, G, T, 256>), dim3(grid_for(quads)), dim3(256), 0, s, n, w32, m32, grad, w16,   \
+                         inv_scale, scaler, lr, momentum, flag);                                                            \
+    }                                                                                                                     \
+  } while (0)
     const int sel = (mom ? 4 : 0) | (g32 ? 2 : 0) | (nt ? 1 : 0);
     switch (sel) {
       case 0: MPT_MU(false, false, false); break;

@@ -242,7 +242,7 @@ __device__ __forceinline__ void tile_of(const Problem& pb, int wg, int& ti, int&
 
 __device__ __forceinline__ bool half_bits_special(uint32_t b) { return (b & 0x7C00u) == 0x7C00u; }
 
-template <class AView, class BView, bool ALIGNED, int BM, int BN, int WM, int WN>
+template <class AView, class BView, bool A_ALIGNED, bool B_ALIGNED, int BM, int BN, int WM, int WN>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void k_gemm(AView A, BView B, Problem pb, Epilogue ep) {
   constexpr int NT = (BM / WM) * (BN / WN) * 64;
   constexpr int FM = WM / 32, FN = WN / 32;
@@ -267,8 +267,8 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void k_gemm(AView A, BV
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
-  TileLoader<AView, ALIGNED, BM, NT> la;
-  TileLoader<BView, ALIGNED, BN, NT> lb;
+  TileLoader<AView, A_ALIGNED, BM, NT> la;
+  TileLoader<BView, B_ALIGNED, BN, NT> lb;
 
   if (kt_begin < kt_end) {
     la.load(A, i0, kt_begin * BK, t);
@@ -472,7 +472,7 @@ __device__ __forceinline__ void wait_frags(half8& a0, half8& a1, half8& a2, half
   asm volatile("s_waitcnt lgkmcnt(%6)" : "+v"(a0), "+v"(a1), "+v"(a2), "+v"(a3), "+v"(b0), "+v"(b1) : "n"(NEWER) : "memory");
 }
 
-template <bool A_RC, bool B_RC>
+template <bool A_RC, bool B_RC, bool ACC_AGPR>
 __global__ __launch_bounds__(512) void k_gemm_dma(DmaMat A, DmaMat B, Problem pb, Epilogue ep) {
   constexpr int NSTAGE = 4, AHEAD = 3, OPERAND = 256 * 64, STAGE = 2 * OPERAND;
   constexpr int READS_PER_KSTEP = 4 * (A_RC ? 1 : 2) + 2 * (B_RC ? 1 : 2);   // LDS read instructions per k16-step
@@ -525,8 +525,13 @@ __global__ __launch_bounds__(512) void k_gemm_dma(DmaMat A, DmaMat B, Problem pb
 #pragma unroll
     for (int a = 0; a < 4; ++a)
 #pragma unroll
-      for (int b = 0; b < 2; ++b)
-        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[ks][b], fa[ks][a], acc[a][b], 0, 0, 0);
+      for (int b = 0; b < 2; ++b) {
+        if constexpr (ACC_AGPR) {
+          asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(acc[a][b]) : "v"(fb[ks][b]), "v"(fa[ks][a]));
+        } else {
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[ks][b], fa[ks][a], acc[a][b], 0, 0, 0);
+        }
+      }
   };
   // Only the newest stage may still be in flight, and every LDS read of this wavefront has returned.
   auto publish = [&]() { asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
@@ -549,7 +554,9 @@ __global__ __launch_bounds__(512) void k_gemm_dma(DmaMat A, DmaMat B, Problem pb
     if (wave < 4) publish();
     __builtin_amdgcn_sched_barrier(0);
   }
-  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");         // drain the tail prefetches before LDS is released
+  // drain the tail prefetches before LDS is released; the no-ops cover the last MFMA's write-back before the
+  // accumulators are read
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
 
   // ---- epilogue (whole tiles): FP16 store with optional Inf/NaN vote, or FP32 split partial
   bool bad = false;
@@ -656,18 +663,18 @@ size_t plan_ws_bytes(const Plan& p, int64_t I, int64_t J) {
   return p.splits > 1 ? (size_t)p.splits * (size_t)I * (size_t)J * sizeof(float) : 0;
 }
 
-template <class AView, class BView, bool ALIGNED>
+template <class AView, class BView, bool A_ALIGNED, bool B_ALIGNED>
 int launch_tiles(hipStream_t s, const AView& A, const BView& B, const Plan& pl, int I, int J, int R, const Epilogue& ep) {
   Problem pb{I, J, R, pl.tiles_i, pl.tiles_j, pl.splits, pl.ktiles_per_split};
   const unsigned grid = (unsigned)((int64_t)pl.tiles_i * pl.tiles_j * pl.splits);
   if (pl.big) {
-    auto k = k_gemm<AView, BView, ALIGNED, 256, 256, 128, 64>;
+    auto k = k_gemm<AView, BView, A_ALIGNED, B_ALIGNED, 256, 256, 128, 64>;
     constexpr int lds = 2 * (256 + 256) * ROWB;
     static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, lds), true);
     (void)once;
     hipLaunchKernelGGL(k, dim3(grid), dim3(512), lds, s, A, B, pb, ep);
   } else {
-    auto k = k_gemm<AView, BView, ALIGNED, 128, 128, 64, 64>;
+    auto k = k_gemm<AView, BView, A_ALIGNED, B_ALIGNED, 128, 128, 64, 64>;
     constexpr int lds = 2 * (128 + 128) * ROWB;
     static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, lds), true);
     (void)once;
@@ -688,9 +695,11 @@ bool try_launch_dma(hipStream_t s, const AView& A, const BView& B, bool aligned,
     static const bool enabled = mpt_env_int("MPT_GEMM_STREAMED", 1) != 0;
     if (!enabled || !aligned || !pl.big || (I % 256) || (J % 256) || (R % 64) || (ep.mode != 0 && ep.mode != 3)) return false;
     if (ep.mode == 3 && ((ep.ld % 4) || !mpt_aligned(ep.out, 16))) return false;
-    auto k = k_gemm_dma<DmaKind<AView>::rc, DmaKind<BView>::rc>;
+    static const bool agpr = mpt_env_int("MPT_GEMM_ACC_AGPR", 0) != 0;   // tuning only
+    auto k = agpr ? k_gemm_dma<DmaKind<AView>::rc, DmaKind<BView>::rc, true> : k_gemm_dma<DmaKind<AView>::rc, DmaKind<BView>::rc, false>;
     constexpr int lds = 4 * 2 * 256 * 64;
-    static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, lds), true);
+    static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_dma<DmaKind<AView>::rc, DmaKind<BView>::rc, true>), hipFuncAttributeMaxDynamicSharedMemorySize, lds),
+                        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_dma<DmaKind<AView>::rc, DmaKind<BView>::rc, false>), hipFuncAttributeMaxDynamicSharedMemorySize, lds), true);
     (void)once;
     Problem pb{I, J, R, pl.tiles_i, pl.tiles_j, pl.splits, pl.ktiles_per_split};
     const unsigned grid = (unsigned)((int64_t)pl.tiles_i * pl.tiles_j * pl.splits);
@@ -704,7 +713,8 @@ bool try_launch_dma(hipStream_t s, const AView& A, const BView& B, bool aligned,
 
 // Run one contraction: single pass, or split partials + ordered reduction.
 template <class AView, class BView>
-int run(hipStream_t s, const AView& A, const BView& B, bool aligned, int I, int J, int R, Epilogue ep, void* ws, size_t ws_bytes) {
+int run(hipStream_t s, const AView& A, const BView& B, bool a_aligned, bool b_aligned, int I, int J, int R, Epilogue ep, void* ws, size_t ws_bytes) {
+  const bool aligned = a_aligned && b_aligned;
   const Plan pl = make_plan(I, J, R, ws != nullptr);
   if (ws != nullptr && ws_bytes < plan_ws_bytes(pl, I, J)) return MPT_ERR_WORKSPACE;
   Epilogue first = ep;
@@ -713,8 +723,10 @@ int run(hipStream_t s, const AView& A, const BView& B, bool aligned, int I, int 
   }
   int st = MPT_OK;
   if (!try_launch_dma(s, A, B, aligned, pl, I, J, R, first, st))
-    st = aligned ? launch_tiles<AView, BView, true>(s, A, B, pl, I, J, R, first)
-                 : launch_tiles<AView, BView, false>(s, A, B, pl, I, J, R, first);
+    st = a_aligned ? (b_aligned ? launch_tiles<AView, BView, true, true>(s, A, B, pl, I, J, R, first)
+                                : launch_tiles<AView, BView, true, false>(s, A, B, pl, I, J, R, first))
+                   : (b_aligned ? launch_tiles<AView, BView, false, true>(s, A, B, pl, I, J, R, first)
+                                : launch_tiles<AView, BView, false, false>(s, A, B, pl, I, J, R, first));
   if (st != MPT_OK) return st;
   if (pl.splits > 1) {
     const int64_t total = (int64_t)I * J;
@@ -758,8 +770,7 @@ extern "C" int mpt_gemm_fwd(void* stream, int64_t M, int64_t N, int64_t K, const
   MatRC A{X, ldx, (int)M, (int)K};
   MatOC B{W, ldw, (int)N, (int)K};
   Epilogue ep{Y, ldy, 0, nullptr};
-  const bool fast = mat_fast(X, ldx, K) && mat_fast(W, ldw, N);
-  return run(static_cast<hipStream_t>(stream), A, B, fast, (int)M, (int)N, (int)K, ep, ws, ws_bytes);
+  return run(static_cast<hipStream_t>(stream), A, B, mat_fast(X, ldx, K), mat_fast(W, ldw, N), (int)M, (int)N, (int)K, ep, ws, ws_bytes);
 }
 
 extern "C" int mpt_gemm_dgrad(void* stream, int64_t M, int64_t N, int64_t K, const uint16_t* dY, int64_t ldy,
@@ -770,8 +781,7 @@ extern "C" int mpt_gemm_dgrad(void* stream, int64_t M, int64_t N, int64_t K, con
   MatRC A{dY, ldy, (int)M, (int)N};
   MatRC B{W, ldw, (int)K, (int)N};
   Epilogue ep{dX, ldx, 0, nullptr};
-  const bool fast = mat_fast(dY, ldy, N) && mat_fast(W, ldw, N);
-  return run(static_cast<hipStream_t>(stream), A, B, fast, (int)M, (int)K, (int)N, ep, ws, ws_bytes);
+  return run(static_cast<hipStream_t>(stream), A, B, mat_fast(dY, ldy, N), mat_fast(W, ldw, N), (int)M, (int)K, (int)N, ep, ws, ws_bytes);
 }
 
 extern "C" int mpt_gemm_wgrad(void* stream, int64_t M, int64_t N, int64_t K, const uint16_t* X, int64_t ldx,
@@ -786,8 +796,7 @@ extern "C" int mpt_gemm_wgrad(void* stream, int64_t M, int64_t N, int64_t K, con
   MatOC A{X, ldx, (int)K, (int)M};
   MatOC B{dY, ldy, (int)N, (int)M};
   Epilogue ep{dW, lddw, out_fp32 ? (accumulate ? 2 : 1) : 0, flag};
-  const bool fast = mat_fast(X, ldx, K) && mat_fast(dY, ldy, N);
-  return run(static_cast<hipStream_t>(stream), A, B, fast, (int)K, (int)N, (int)M, ep, ws, ws_bytes);
+  return run(static_cast<hipStream_t>(stream), A, B, mat_fast(X, ldx, K), mat_fast(dY, ldy, N), (int)K, (int)N, (int)M, ep, ws, ws_bytes);
 }
 
 // ---------------------------------------------------------------- C ABI: 3x3 convolution
@@ -824,7 +833,7 @@ extern "C" int mpt_conv3x3_fwd(void* stream, int64_t Nb, int64_t H, int64_t W, i
   ImgRC A{x, (int)H, (int)W, (int)C, P, R, +1, FastDiv((uint32_t)(H * W)), FastDiv((uint32_t)W), FastDiv((uint32_t)C)};
   MatRC B{w, 9 * C, (int)Kf, R};
   Epilogue ep{y, Kf, 0, nullptr};
-  return run(static_cast<hipStream_t>(stream), A, B, true, P, (int)Kf, R, ep, ws, ws_bytes);
+  return run(static_cast<hipStream_t>(stream), A, B, true, true, P, (int)Kf, R, ep, ws, ws_bytes);
 }
 
 extern "C" int mpt_conv3x3_dgrad(void* stream, int64_t Nb, int64_t H, int64_t W, int64_t C, int64_t Kf, const uint16_t* dy,
@@ -836,7 +845,7 @@ extern "C" int mpt_conv3x3_dgrad(void* stream, int64_t Nb, int64_t H, int64_t W,
   ImgRC A{dy, (int)H, (int)W, (int)Kf, P, R, -1, FastDiv((uint32_t)(H * W)), FastDiv((uint32_t)W), FastDiv((uint32_t)Kf)};
   FilterOC B{w, (int)C, (int)Kf, (int)C, R, FastDiv((uint32_t)Kf)};
   Epilogue ep{dx, C, 0, nullptr};
-  return run(static_cast<hipStream_t>(stream), A, B, true, P, (int)C, R, ep, ws, ws_bytes);
+  return run(static_cast<hipStream_t>(stream), A, B, true, true, P, (int)C, R, ep, ws, ws_bytes);
 }
 
 extern "C" int mpt_conv3x3_wgrad(void* stream, int64_t Nb, int64_t H, int64_t W, int64_t C, int64_t Kf, const uint16_t* x,
@@ -850,5 +859,5 @@ extern "C" int mpt_conv3x3_wgrad(void* stream, int64_t Nb, int64_t H, int64_t W,
   MatOC A{dy, Kf, (int)Kf, P};
   ImgOC B{x, (int)H, (int)W, (int)C, J, P, FastDiv((uint32_t)(H * W)), FastDiv((uint32_t)W), FastDiv((uint32_t)C)};
   Epilogue ep{dw, J, 0, flag};
-  return run(static_cast<hipStream_t>(stream), A, B, true, (int)Kf, J, P, ep, ws, ws_bytes);
+  return run(static_cast<hipStream_t>(stream), A, B, true, true, (int)Kf, J, P, ep, ws, ws_bytes);
 }
