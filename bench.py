@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0             # MI355X HBM3E peak
 N_SQUARE = 4096
 N_FLAT = 116_000_000
 # HBM traffic per GEMM launch (bytes) from rocprofv3 FETCH_SIZE/WRITE_SIZE counter runs, scaled by the
-# same counters on a copy kernel of known size; see profiles/k_gemm_and_update_hbm_traffic.md.
+# same counters on a copy kernel of known size; see profiles/k_gemm_dma_and_update_hbm_traffic.md.
 GEMM_TRAFFIC_BYTES = 235.4e6      # 201.8 MB read + 33.6 MB written per 4096^3 launch
 UPDATE_TRAFFIC_BYTES = 2320.0e6   # 1160 MB read + 1160 MB written per 116M-element launch
 
@@ -123,10 +123,23 @@ def main():
 
     # the other half of the metric: fused master update on the 116M-parameter flat buffer
     del X, G, Y, dX, dW, W32, M32
-    w = torch.empty(N_FLAT, dtype=torch.float32, device=dev).uniform_(-0.05, 0.05)
-    m = torch.zeros(N_FLAT, dtype=torch.float32, device=dev)
-    g = (torch.randn(N_FLAT, device=dev) * 64).to(torch.float16)
-    h = w.to(torch.float16)
+    # one flat allocation carved into master / momentum / gradient / FP16 copy at 2 MiB boundaries, the way a
+    # framework lays out a flat parameter buffer (separately cached allocations at odd offsets cost ~4 % here)
+    MiB2 = 1 << 21
+    sizes = [N_FLAT * 4, N_FLAT * 4, N_FLAT * 2, N_FLAT * 2]
+    offs, o = [], 0
+    for sz in sizes:
+        offs.append(o)
+        o += (sz + MiB2 - 1) // MiB2 * MiB2
+    pool = torch.empty(o, dtype=torch.uint8, device=dev)
+    w = pool[offs[0]:offs[0] + sizes[0]].view(torch.float32)
+    m = pool[offs[1]:offs[1] + sizes[1]].view(torch.float32)
+    g = pool[offs[2]:offs[2] + sizes[2]].view(torch.float16)
+    h = pool[offs[3]:offs[3] + sizes[3]].view(torch.float16)
+    w.uniform_(-0.05, 0.05)
+    m.zero_()
+    g.copy_(torch.randn(N_FLAT, device=dev) * 64)
+    h.copy_(w)
     flag.zero_()
     for _ in range(3):
         mpt.mpt_master_update(w, m, g, h, 2.0 ** -16, lr, mu, flag)
@@ -150,7 +163,7 @@ def main():
                        "kernel": "k_master_update (momentum, FP16 grad), 116M elements, 20 B/element",
                        "avg_launch_us": round(upd_ms * 1e3, 2),
                        "unscale_check_GBs": round(2.0 * N_FLAT / (chk_ms * 1e-3) / 1e9, 1)}
-    del w, m, g, h
+    del w, m, g, h, pool
 
     cpu = None
     if not args.no_cpu_baseline:
