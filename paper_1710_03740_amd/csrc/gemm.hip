@@ -371,9 +371,10 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void k_gemm(AView A, BV
 // at the barrier or waits for LDS.  LDS layouts (64 banks of 4 bytes, 16 lanes served together):
 //   RC operand: [256 outer][32 r] rows of 64 B; 16-byte chunk c of row o is stored at chunk c ^ ((o >> 2) & 3);
 //               a fragment is one ds_read_b128 per lane.
-//   OC operand: [32 r][256 outer] rows of 512 B; 32-byte unit u of row r is stored at unit u ^ ((r & 3) << 1);
+//   OC operand: [32 r][256 outer] rows of 512 B; 32-byte unit u of row r is stored at unit u ^ ((r & 3) | ((r >> 1) & 4));
 //               a fragment is two ds_read_b64_tr_b16 per lane (the transposing LDS read: within 16 lanes, lane i
-//               receives element i of each of the four 32-byte rows that lanes 4j..4j+3 point at).
+//               receives element i of each of the four 32-byte rows that lanes 4j..4j+3 point at; lanes 0-31 and
+//               32-63 are served in separate passes, and the key keeps the 8 rows of a pass on distinct banks).
 // The swizzles are applied by choosing which global chunk each lane fetches, since an LDS-direct load writes lane l
 // at base + 16*l.  Requirements (checked by the host): I, J multiples of 256, R a multiple of 64, 16-byte aligned
 // operands, FP16 store or FP32 split partials.
@@ -382,6 +383,9 @@ typedef const __attribute__((address_space(1))) void* global_void_ptr;
 typedef __fp16 fp16x4_t __attribute__((ext_vector_type(4)));
 
 struct DmaMat { const uint16_t* base; int64_t ld; };
+
+// XOR key of reduction row r for the 32-byte units of an OC stage row (see the layout note above).
+__device__ __forceinline__ int oc_key(int r) { return (r & 3) | ((r >> 1) & 4); }
 
 template <bool RC>
 struct DmaOperand {
@@ -399,8 +403,8 @@ struct DmaOperand {
     } else {
       const int row = wave * 4 + (lane >> 5);                        // blocks 2w, 2w+1 hold 2 reduction rows each
       const int pc = lane & 31;
-      const int c0 = 2 * ((pc >> 1) ^ ((row & 3) << 1)) + (pc & 1);
-      const int c1 = 2 * ((pc >> 1) ^ (((row + 2) & 3) << 1)) + (pc & 1);
+      const int c0 = 2 * ((pc >> 1) ^ oc_key(row)) + (pc & 1);
+      const int c1 = 2 * ((pc >> 1) ^ oc_key(row + 2)) + (pc & 1);
       p0 = m.base + (int64_t)(r0 + row) * m.ld + o0 + c0 * 8;
       p1 = m.base + (int64_t)(r0 + row + 2) * m.ld + o0 + c1 * 8;
       step = 32 * m.ld;
@@ -429,56 +433,65 @@ __device__ __forceinline__ uint2v lds_read_tr_b64(uint32_t addr) {
   return v;
 }
 
-// Fragment of 32 outer indices x 16 reduction indices for v_mfma_f32_32x32x16_f16: lane l holds outer index l%32 and
-// reduction indices 8*(l/32) .. +7 of k16-step ks.  Per-lane byte offsets inside an operand's stage are fixed for the
-// whole kernel: RC fragments need one per k16-step, OC fragments two (reduction rows +0..3 and +4..7).
+// Fragment of 16 outer indices x 32 reduction indices (a whole stage) for v_mfma_f32_16x16x32_f16: lane l holds outer
+// index l%16 and reduction indices 8*(l/16) .. +7.  Per-lane byte offsets inside an operand's stage are fixed for the
+// whole kernel: RC fragments need one (a 16-byte chunk), OC fragments two (reduction rows +0..3 and +4..7, one
+// transposing read each).
 template <bool RC>
 struct FragAddr {
-  uint32_t off[2][RC ? 1 : 2];
+  uint32_t off[RC ? 1 : 2];
   __device__ __forceinline__ void init(int outer0, int lane) {
+    if constexpr (RC) {
+      const int r = outer0 + (lane & 15);
+      const int c = lane >> 4;
+      off[0] = r * 64 + (((c ^ (r >> 2)) & 3) << 4);
+    } else {
+      const int unit = outer0 >> 4;
+      const int sub = (lane & 3) << 3;
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      if constexpr (RC) {
-        const int r = outer0 + (lane & 31);
-        const int c = ks * 2 + (lane >> 5);
-        off[ks][0] = r * 64 + (((c ^ (r >> 2)) & 3) << 4);
-      } else {
-        const int unit = (outer0 >> 4) + ((lane >> 4) & 1);
-        const int sub = (lane & 3) << 3;
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-          const int r = ks * 16 + ((lane >> 5) << 3) + ((lane & 15) >> 2) + 4 * h;
-          off[ks][h] = r * 512 + ((unit ^ ((r & 3) << 1)) << 5) + sub;
-        }
+      for (int h = 0; h < 2; ++h) {
+        const int r = ((lane >> 4) << 3) + 4 * h + ((lane & 15) >> 2);
+        off[h] = r * 512 + ((unit ^ oc_key(r)) << 5) + sub;
       }
     }
   }
-  __device__ __forceinline__ half8 read(uint32_t stage_operand, int ks) const {
+  __device__ __forceinline__ half8 read(uint32_t stage_operand) const {
     if constexpr (RC) {
-      return lds_read_b128(stage_operand + off[ks][0]);
+      return lds_read_b128(stage_operand + off[0]);
     } else {
-      const uint2v lo = lds_read_tr_b64(stage_operand + off[ks][0]);
-      const uint2v hi = lds_read_tr_b64(stage_operand + off[ks][1]);
+      const uint2v lo = lds_read_tr_b64(stage_operand + off[0]);
+      const uint2v hi = lds_read_tr_b64(stage_operand + off[1]);
       uint4v q = {lo[0], lo[1], hi[0], hi[1]};
       return __builtin_bit_cast(half8, q);
     }
   }
 };
 
-// Wait until at most `newer` LDS reads issued after these fragments are still outstanding; the fragments pass through
-// the statement so that their consumers cannot be moved above the wait.
+// Wait until at most NEWER LDS reads issued after these fragments are still outstanding (the LGKM counter is
+// in order and 4 bits wide); the fragments pass through the statement so that their consumers stay below it.
 template <int NEWER>
-__device__ __forceinline__ void wait_frags(half8& a0, half8& a1, half8& a2, half8& a3, half8& b0, half8& b1) {
-  asm volatile("s_waitcnt lgkmcnt(%6)" : "+v"(a0), "+v"(a1), "+v"(a2), "+v"(a3), "+v"(b0), "+v"(b1) : "n"(NEWER) : "memory");
+__device__ __forceinline__ void wait_frags8(half8 (&f)[4], half8 (&g)[4]) {
+  asm volatile("s_waitcnt lgkmcnt(%8)"
+               : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3]), "+v"(g[0]), "+v"(g[1]), "+v"(g[2]), "+v"(g[3])
+               : "n"(NEWER < 15 ? NEWER : 15)
+               : "memory");
+}
+template <int NEWER>
+__device__ __forceinline__ void wait_frags4(half8 (&f)[4]) {
+  asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3]) : "n"(NEWER < 15 ? NEWER : 15) : "memory");
 }
 
-template <bool A_RC, bool B_RC, bool ACC_AGPR>
+// Workgroup tile 256 x 256, 8 wavefronts as 2 x 4, 128 x 64 each = 8 x 4 blocks of v_mfma_f32_16x16x32_f16 (this shape
+// moves half the accumulator bytes per FLOP of the 32x32x16 shape, which matters on a power-limited clock).  A stage
+// (reduction depth 32) is one MFMA k-step; it is issued as two halves of 16 MFMAs (A blocks 0-3, then 4-7) so that
+// the fragments of the other half / the next stage are fetched underneath.
+template <bool A_RC, bool B_RC>
 __global__ __launch_bounds__(512) void k_gemm_dma(DmaMat A, DmaMat B, Problem pb, Epilogue ep) {
   constexpr int NSTAGE = 4, AHEAD = 3, OPERAND = 256 * 64, STAGE = 2 * OPERAND;
-  constexpr int READS_PER_KSTEP = 4 * (A_RC ? 1 : 2) + 2 * (B_RC ? 1 : 2);   // LDS read instructions per k16-step
+  constexpr int RA = 4 * (A_RC ? 1 : 2), RB = 4 * (B_RC ? 1 : 2);      // LDS read instructions per 4 A / 4 B fragments
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   const int t = threadIdx.x, lane = t & 63, wave = __builtin_amdgcn_readfirstlane(t >> 6);
-  const int wm = wave >> 2, wn = wave & 3;                             // 2 x 4 wavefronts, 128 x 64 each
+  const int wm = wave >> 2, wn = wave & 3;
   int ti, tj, sp;
   tile_of(pb, blockIdx.x, ti, tj, sp);
   const int i0 = ti * 256, j0 = tj * 256;
@@ -486,13 +499,13 @@ __global__ __launch_bounds__(512) void k_gemm_dma(DmaMat A, DmaMat B, Problem pb
   const int st_begin = sp * pb.ktiles_per_split * 2;
   const int nst = min(pb.ktiles_per_split * 2, st_total - st_begin);   // stages this workgroup reduces over (>= 1)
 
-  float16v acc[4][2];
+  float4v acc[8][4];
 #pragma unroll
-  for (int a = 0; a < 4; ++a)
+  for (int a = 0; a < 8; ++a)
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
+    for (int b = 0; b < 4; ++b)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+      for (int v = 0; v < 4; ++v) acc[a][b][v] = 0.f;
 
   DmaOperand<A_RC> da;
   DmaOperand<B_RC> db;
@@ -505,89 +518,92 @@ __global__ __launch_bounds__(512) void k_gemm_dma(DmaMat A, DmaMat B, Problem pb
     da.issue(sc, st + blk);
     db.issue(sc, st + OPERAND + blk);
   };
-  FragAddr<A_RC> aa[4];
-  FragAddr<B_RC> ab[2];
+  FragAddr<A_RC> aa[8];
+  FragAddr<B_RC> ab[4];
 #pragma unroll
-  for (int a = 0; a < 4; ++a) aa[a].init(wm * 128 + a * 32, lane);
+  for (int a = 0; a < 8; ++a) aa[a].init(wm * 128 + a * 16, lane);
 #pragma unroll
-  for (int b = 0; b < 2; ++b) ab[b].init(wn * 64 + b * 32, lane);
+  for (int b = 0; b < 4; ++b) ab[b].init(wn * 64 + b * 16, lane);
   const uint32_t lds0 = lds_offset(lds);
-  half8 fa[2][4], fb[2][2];
-  auto read_frags = [&](int s, int ks) {
-    const uint32_t st = lds0 + (s & (NSTAGE - 1)) * STAGE;
+  half8 fal[4], fah[4], fb[2][4];                                      // A blocks 0-3, A blocks 4-7, B blocks (double buffered)
+  auto stage_base = [&](int s) { return lds0 + (uint32_t)((s & (NSTAGE - 1)) * STAGE); };
+  auto read_lo = [&](int s) {                                          // B blocks and A blocks 0-3 of stage s
+    const uint32_t st = stage_base(s);
 #pragma unroll
-    for (int a = 0; a < 4; ++a) fa[ks][a] = aa[a].read(st, ks);
+    for (int b = 0; b < 4; ++b) fb[s & 1][b] = ab[b].read(st + OPERAND);
 #pragma unroll
-    for (int b = 0; b < 2; ++b) fb[ks][b] = ab[b].read(st + OPERAND, ks);
+    for (int a = 0; a < 4; ++a) fal[a] = aa[a].read(st);
   };
-  auto mfmas = [&](int ks) {
-    wait_frags<READS_PER_KSTEP>(fa[ks][0], fa[ks][1], fa[ks][2], fa[ks][3], fb[ks][0], fb[ks][1]);
+  auto read_hi = [&](int s) {                                          // A blocks 4-7 of stage s
+    const uint32_t st = stage_base(s);
+#pragma unroll
+    for (int a = 0; a < 4; ++a) fah[a] = aa[4 + a].read(st);
+  };
+  auto mfma_half = [&](half8 (&fa)[4], half8 (&fbv)[4], int abase) {
 #pragma unroll
     for (int a = 0; a < 4; ++a)
 #pragma unroll
-      for (int b = 0; b < 2; ++b) {
-        if constexpr (ACC_AGPR) {
-          asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(acc[a][b]) : "v"(fb[ks][b]), "v"(fa[ks][a]));
-        } else {
-          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[ks][b], fa[ks][a], acc[a][b], 0, 0, 0);
-        }
-      }
+      for (int b = 0; b < 4; ++b)   // operands swapped: each lane ends up with 4 consecutive output columns of one row
+        acc[abase + a][b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fbv[b], fa[a], acc[abase + a][b], 0, 0, 0);
   };
   // Only the newest stage may still be in flight, and every LDS read of this wavefront has returned.
   auto publish = [&]() { asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
 
   issue(0); issue(1); issue(2);
   publish();                                  // stages 0 and 1 have landed everywhere
-  read_frags(0, 0);
-  for (int s = 0; s < nst; ++s) {
+  read_lo(0);
+  // The loop body is written for an even and an odd stage so that the B double buffer is indexed statically.
+  auto one_stage = [&](int s, half8 (&fb_cur)[4]) {
     issue(s + AHEAD);                        // into the slot of stage s-1: every wavefront finished reading it before the last barrier it passed
-    read_frags(s, 1);
+    read_hi(s);
     __builtin_amdgcn_sched_barrier(0);
-    mfmas(0);                                // fragments (s,0) were requested half a stage ago; (s,1) may still be in flight
+    wait_frags8<RA>(fal, fb_cur);            // requested half a stage ago; only the A 4-7 reads may still be in flight
+    mfma_half(fal, fb_cur, 0);
     __builtin_amdgcn_sched_barrier(0);
     if (wave >= 4) publish();
     __builtin_amdgcn_sched_barrier(0);
-    read_frags(s + 1, 0);                    // stage s+1 was published by an earlier barrier; past the end the data is unused
+    read_lo(s + 1);                          // stage s+1 was published by an earlier barrier; past the end the data is unused
     __builtin_amdgcn_sched_barrier(0);
-    mfmas(1);
+    wait_frags4<RA + RB>(fah);
+    mfma_half(fah, fb_cur, 4);
     __builtin_amdgcn_sched_barrier(0);
     if (wave < 4) publish();
     __builtin_amdgcn_sched_barrier(0);
+  };
+  int s = 0;
+  for (; s + 1 < nst; s += 2) {
+    one_stage(s, fb[0]);
+    one_stage(s + 1, fb[1]);
   }
-  // drain the tail prefetches before LDS is released; the no-ops cover the last MFMA's write-back before the
-  // accumulators are read
-  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+  if (s < nst) one_stage(s, fb[0]);
+  // drain the tail prefetches before LDS is released
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
 
-  // ---- epilogue (whole tiles): FP16 store with optional Inf/NaN vote, or FP32 split partial
+  // ---- epilogue (whole tiles): FP16 store with optional Inf/NaN vote, or FP32 split partial.
+  // acc[a][b][e]: row i = 16a + lane%16, column j = 16b + 4*(lane/16) + e of the wavefront's 128 x 64 block.
   bool bad = false;
   const int64_t split_off = (ep.mode == 3) ? (int64_t)sp * pb.I * pb.J : 0;
 #pragma unroll
-  for (int a = 0; a < 4; ++a) {
-    const int i = i0 + wm * 128 + a * 32 + (lane & 31);
+  for (int a = 0; a < 8; ++a) {
+    const int i = i0 + wm * 128 + a * 16 + (lane & 15);
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
+    for (int b = 0; b < 4; ++b) {
+      const int j = j0 + wn * 64 + b * 16 + ((lane >> 4) << 2);
+      if (ep.mode == 0) {
+        half4 h;
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int j = j0 + wn * 64 + b * 32 + g * 8 + ((lane >> 5) << 2);
-        if (ep.mode == 0) {
-          half4 h;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) h[e] = (_Float16)acc[a][b][g * 4 + e];
-          const uint2v hb = __builtin_bit_cast(uint2v, h);
-          if (ep.flag) bad |= half_bits_special(hb[0]) | half_bits_special(hb[0] >> 16) | half_bits_special(hb[1]) | half_bits_special(hb[1] >> 16);
-          uint16_t* o = reinterpret_cast<uint16_t*>(ep.out) + (int64_t)i * ep.ld + j;
-          if ((reinterpret_cast<uintptr_t>(o) & 7) == 0) {
-            *reinterpret_cast<uint2v*>(o) = hb;
-          } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) o[e] = (uint16_t)(hb[e >> 1] >> ((e & 1) * 16));
-          }
+        for (int e = 0; e < 4; ++e) h[e] = (_Float16)acc[a][b][e];
+        const uint2v hb = __builtin_bit_cast(uint2v, h);
+        if (ep.flag) bad |= half_bits_special(hb[0]) | half_bits_special(hb[0] >> 16) | half_bits_special(hb[1]) | half_bits_special(hb[1] >> 16);
+        uint16_t* o = reinterpret_cast<uint16_t*>(ep.out) + (int64_t)i * ep.ld + j;
+        if ((reinterpret_cast<uintptr_t>(o) & 7) == 0) {
+          *reinterpret_cast<uint2v*>(o) = hb;
         } else {
-          float4v f;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) f[e] = acc[a][b][g * 4 + e];
-          *reinterpret_cast<float4v*>(reinterpret_cast<float*>(ep.out) + split_off + (int64_t)i * ep.ld + j) = f;
+          for (int e = 0; e < 4; ++e) o[e] = (uint16_t)(hb[e >> 1] >> ((e & 1) * 16));
         }
+      } else {
+        *reinterpret_cast<float4v*>(reinterpret_cast<float*>(ep.out) + split_off + (int64_t)i * ep.ld + j) = acc[a][b];
       }
     }
   }
@@ -695,11 +711,9 @@ bool try_launch_dma(hipStream_t s, const AView& A, const BView& B, bool aligned,
     static const bool enabled = mpt_env_int("MPT_GEMM_STREAMED", 1) != 0;
     if (!enabled || !aligned || !pl.big || (I % 256) || (J % 256) || (R % 64) || (ep.mode != 0 && ep.mode != 3)) return false;
     if (ep.mode == 3 && ((ep.ld % 4) || !mpt_aligned(ep.out, 16))) return false;
-    static const bool agpr = mpt_env_int("MPT_GEMM_ACC_AGPR", 0) != 0;   // tuning only
-    auto k = agpr ? k_gemm_dma<DmaKind<AView>::rc, DmaKind<BView>::rc, true> : k_gemm_dma<DmaKind<AView>::rc, DmaKind<BView>::rc, false>;
+    auto k = k_gemm_dma<DmaKind<AView>::rc, DmaKind<BView>::rc>;
     constexpr int lds = 4 * 2 * 256 * 64;
-    static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_dma<DmaKind<AView>::rc, DmaKind<BView>::rc, true>), hipFuncAttributeMaxDynamicSharedMemorySize, lds),
-                        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_gemm_dma<DmaKind<AView>::rc, DmaKind<BView>::rc, false>), hipFuncAttributeMaxDynamicSharedMemorySize, lds), true);
+    static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, lds), true);
     (void)once;
     Problem pb{I, J, R, pl.tiles_i, pl.tiles_j, pl.splits, pl.ktiles_per_split};
     const unsigned grid = (unsigned)((int64_t)pl.tiles_i * pl.tiles_j * pl.splits);
