@@ -369,7 +369,8 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void k_gemm(AView A, BV
 // three of them in flight.  The two wavefronts that share a SIMD run half a stage apart (wavefronts 4-7 take the
 // per-stage barrier in the middle of their stage), so one of them always has MFMAs to issue while the other sits
 // at the barrier or waits for LDS.  LDS layouts (64 banks of 4 bytes, 16 lanes served together):
-//   RC operand: [256 outer][32 r] rows of 64 B; 16-byte chunk c of row o is stored at chunk c ^ ((o >> 2) & 3);
+//   RC operand: [256 outer][32 r] rows of 64 B; 16-byte chunk c of row o is stored at chunk c ^ ((o >> 1) & 3)
+//               (found by measurement to be the conflict-free key when 16 lanes read 16 rows x the same chunk);
 //               a fragment is one ds_read_b128 per lane.
 //   OC operand: [32 r][256 outer] rows of 512 B; 32-byte unit u of row r is stored at unit u ^ ((r & 3) | ((r >> 1) & 4));
 //               a fragment is two ds_read_b64_tr_b16 per lane (the transposing LDS read: within 16 lanes, lane i
@@ -396,7 +397,7 @@ struct DmaOperand {
   __device__ __forceinline__ void init(const DmaMat& m, int o0, int r0, int wave, int lane) {
     if constexpr (RC) {
       const int row = wave * 32 + (lane >> 2);                       // blocks 2w, 2w+1 hold 16 rows each
-      const int chunk = (lane & 3) ^ ((row >> 2) & 3);               // same for row + 16
+      const int chunk = (lane & 3) ^ ((row >> 1) & 3);               // same for row + 16
       p0 = m.base + (int64_t)(o0 + row) * m.ld + r0 + chunk * 8;
       p1 = p0 + 16 * m.ld;
       step = 32;
@@ -444,7 +445,7 @@ struct FragAddr {
     if constexpr (RC) {
       const int r = outer0 + (lane & 15);
       const int c = lane >> 4;
-      off[0] = r * 64 + (((c ^ (r >> 2)) & 3) << 4);
+      off[0] = r * 64 + (((c ^ (r >> 1)) & 3) << 4);
     } else {
       const int unit = outer0 >> 4;
       const int sub = (lane & 3) << 3;
@@ -485,9 +486,9 @@ __device__ __forceinline__ void wait_frags4(half8 (&f)[4]) {
 // moves half the accumulator bytes per FLOP of the 32x32x16 shape, which matters on a power-limited clock).  A stage
 // (reduction depth 32) is one MFMA k-step; it is issued as two halves of 16 MFMAs (A blocks 0-3, then 4-7) so that
 // the fragments of the other half / the next stage are fetched underneath.
-template <bool A_RC, bool B_RC>
+template <bool A_RC, bool B_RC, int NSTAGE>
 __global__ __launch_bounds__(512) void k_gemm_dma(DmaMat A, DmaMat B, Problem pb, Epilogue ep) {
-  constexpr int NSTAGE = 4, AHEAD = 3, OPERAND = 256 * 64, STAGE = 2 * OPERAND;
+  constexpr int AHEAD = NSTAGE - 1, OPERAND = 256 * 64, STAGE = 2 * OPERAND;
   constexpr int RA = 4 * (A_RC ? 1 : 2), RB = 4 * (B_RC ? 1 : 2);      // LDS read instructions per 4 A / 4 B fragments
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   const int t = threadIdx.x, lane = t & 63, wave = __builtin_amdgcn_readfirstlane(t >> 6);
@@ -514,7 +515,7 @@ __global__ __launch_bounds__(512) void k_gemm_dma(DmaMat A, DmaMat B, Problem pb
   const int blk = wave * 2048;                                         // this wavefront's two 1 KiB blocks inside an operand stage
   auto issue = [&](int s) {                                            // past the end: refetch the last slice into a free slot
     const int sc = min(s, nst - 1);
-    char* st = lds + (s & (NSTAGE - 1)) * STAGE;
+    char* st = lds + (s % NSTAGE) * STAGE;
     da.issue(sc, st + blk);
     db.issue(sc, st + OPERAND + blk);
   };
@@ -526,7 +527,7 @@ __global__ __launch_bounds__(512) void k_gemm_dma(DmaMat A, DmaMat B, Problem pb
   for (int b = 0; b < 4; ++b) ab[b].init(wn * 64 + b * 16, lane);
   const uint32_t lds0 = lds_offset(lds);
   half8 fal[4], fah[4], fb[2][4];                                      // A blocks 0-3, A blocks 4-7, B blocks (double buffered)
-  auto stage_base = [&](int s) { return lds0 + (uint32_t)((s & (NSTAGE - 1)) * STAGE); };
+  auto stage_base = [&](int s) { return lds0 + (uint32_t)((s % NSTAGE) * STAGE); };
   auto read_lo = [&](int s) {                                          // B blocks and A blocks 0-3 of stage s
     const uint32_t st = stage_base(s);
 #pragma unroll
@@ -547,9 +548,10 @@ __global__ __launch_bounds__(512) void k_gemm_dma(DmaMat A, DmaMat B, Problem pb
         acc[abase + a][b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fbv[b], fa[a], acc[abase + a][b], 0, 0, 0);
   };
   // Only the newest stage may still be in flight, and every LDS read of this wavefront has returned.
-  auto publish = [&]() { asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
+  auto publish = [&]() { asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(4 * (AHEAD - 2)) : "memory"); };
 
-  issue(0); issue(1); issue(2);
+#pragma unroll
+  for (int q = 0; q < AHEAD; ++q) issue(q);
   publish();                                  // stages 0 and 1 have landed everywhere
   read_lo(0);
   // The loop body is written for an even and an odd stage so that the B double buffer is indexed statically.
@@ -711,10 +713,14 @@ bool try_launch_dma(hipStream_t s, const AView& A, const BView& B, bool aligned,
     static const bool enabled = mpt_env_int("MPT_GEMM_STREAMED", 1) != 0;
     if (!enabled || !aligned || !pl.big || (I % 256) || (J % 256) || (R % 64) || (ep.mode != 0 && ep.mode != 3)) return false;
     if (ep.mode == 3 && ((ep.ld % 4) || !mpt_aligned(ep.out, 16))) return false;
-    auto k = k_gemm_dma<DmaKind<AView>::rc, DmaKind<BView>::rc>;
-    constexpr int lds = 4 * 2 * 256 * 64;
-    static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, lds), true);
+    static const int nstage = mpt_env_int("MPT_GEMM_STAGES", 4);          // 4 or 5 ring slots of 32 KiB (tuning only)
+    auto k4 = k_gemm_dma<DmaKind<AView>::rc, DmaKind<BView>::rc, 4>;
+    auto k5 = k_gemm_dma<DmaKind<AView>::rc, DmaKind<BView>::rc, 5>;
+    static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(k4), hipFuncAttributeMaxDynamicSharedMemorySize, 4 * 32768),
+                        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k5), hipFuncAttributeMaxDynamicSharedMemorySize, 5 * 32768), true);
     (void)once;
+    auto k = nstage == 5 ? k5 : k4;
+    const int lds = (nstage == 5 ? 5 : 4) * 32768;
     Problem pb{I, J, R, pl.tiles_i, pl.tiles_j, pl.splits, pl.ktiles_per_split};
     const unsigned grid = (unsigned)((int64_t)pl.tiles_i * pl.tiles_j * pl.splits);
     hipLaunchKernelGGL(k, dim3(grid), dim3(512), lds, s, DmaMat{A.base, A.ld}, DmaMat{B.base, B.ld}, pb, ep);
