@@ -117,7 +117,7 @@ def main():
     achieved = 2.0 * n ** 3 / (gemm_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "achieved": round(achieved, 1), "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / MFMA_F16_PEAK_TFLOPS, 4), "traffic": GEMM_TRAFFIC_BYTES,
-                "kernel": "k_gemm_dma: streamed 256x256 tile, K=32 stages (avg of fwd, dgrad, wgrad)", "avg_launch_us": round(gemm_ms * 1e3, 2),
+                "kernel": "k_gemm_dma: streamed 256x256 tile of 16x16x32 MFMA blocks, K=32 stages (avg of fwd, dgrad, wgrad)", "avg_launch_us": round(gemm_ms * 1e3, 2),
                 "per_pass_us": {k: round(1e3 * sum(ev[i].elapsed_time(ev[i + 1]) for ev in gemm_events) / len(gemm_events), 2)
                                 for i, k in enumerate(("fwd", "dgrad", "wgrad"))}}
 
@@ -160,7 +160,7 @@ def main():
     chk_ms = e0.elapsed_time(e1) / reps
     roofline_update = {"bound": "hbm", "achieved": round(upd_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                        "frac": round(upd_gbs / HBM_PEAK_GBS, 4), "traffic": UPDATE_TRAFFIC_BYTES,
-                       "kernel": "k_master_update (momentum, FP16 grad), 116M elements, 20 B/element",
+                       "kernel": "k_master_update (momentum, FP16 grad), 116M elements, 20 B/element, 2 elements per thread",
                        "avg_launch_us": round(upd_ms * 1e3, 2),
                        "unscale_check_GBs": round(2.0 * N_FLAT / (chk_ms * 1e-3) / 1e9, 1)}
     del w, m, g, h, pool
