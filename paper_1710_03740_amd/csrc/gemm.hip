@@ -411,9 +411,9 @@ struct DmaOperand {
       step = 32 * m.ld;
     }
   }
-  __device__ __forceinline__ void issue(int stage_rel, char* lds_block) const {
-    __builtin_amdgcn_global_load_lds((global_void_ptr)(p0 + stage_rel * step), (lds_void_ptr)lds_block, 16, 0, 0);
-    __builtin_amdgcn_global_load_lds((global_void_ptr)(p1 + stage_rel * step), (lds_void_ptr)(lds_block + 1024), 16, 0, 0);
+  __device__ __forceinline__ void issue(int stage_rel, char* lds_block, int which) const {
+    if (which == 0) __builtin_amdgcn_global_load_lds((global_void_ptr)(p0 + stage_rel * step), (lds_void_ptr)lds_block, 16, 0, 0);
+    else __builtin_amdgcn_global_load_lds((global_void_ptr)(p1 + stage_rel * step), (lds_void_ptr)(lds_block + 1024), 16, 0, 0);
   }
 };
 
@@ -513,11 +513,15 @@ __global__ __launch_bounds__(512) void k_gemm_dma(DmaMat A, DmaMat B, Problem pb
   da.init(A, i0, st_begin * 32, wave, lane);
   db.init(B, j0, st_begin * 32, wave, lane);
   const int blk = wave * 2048;                                         // this wavefront's two 1 KiB blocks inside an operand stage
-  auto issue = [&](int s) {                                            // past the end: refetch the last slice into a free slot
+  auto issue1 = [&](int s, int q) {                                    // one of the 4 loads of stage s; past the end: refetch the last slice into a free slot
     const int sc = min(s, nst - 1);
     char* st = lds + (s % NSTAGE) * STAGE;
-    da.issue(sc, st + blk);
-    db.issue(sc, st + OPERAND + blk);
+    if (q < 2) da.issue(sc, st + blk, q);
+    else db.issue(sc, st + OPERAND + blk, q - 2);
+  };
+  auto issue = [&](int s) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) issue1(s, q);
   };
   FragAddr<A_RC> aa[8];
   FragAddr<B_RC> ab[4];
@@ -540,12 +544,21 @@ __global__ __launch_bounds__(512) void k_gemm_dma(DmaMat A, DmaMat B, Problem pb
 #pragma unroll
     for (int a = 0; a < 4; ++a) fah[a] = aa[4 + a].read(st);
   };
-  auto mfma_half = [&](half8 (&fa)[4], half8 (&fbv)[4], int abase) {
+  // 16 MFMAs; when `load_stage` >= 0, two of the four LDS-direct loads of that stage are issued, one after every
+  // eighth MFMA (A's pair in the first half of a stage, B's pair in the second), so that the vector-memory unit
+  // drains between them instead of blocking the wavefront on a burst.
+  auto mfma_half = [&](half8 (&fa)[4], half8 (&fbv)[4], int abase, int load_stage) {
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
+    for (int a = 0; a < 4; ++a) {
 #pragma unroll
       for (int b = 0; b < 4; ++b)   // operands swapped: each lane ends up with 4 consecutive output columns of one row
         acc[abase + a][b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fbv[b], fa[a], acc[abase + a][b], 0, 0, 0);
+      if (load_stage >= 0 && (a & 1)) {
+        __builtin_amdgcn_sched_barrier(0);
+        issue1(load_stage, (abase >> 1) + (a >> 1));
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
   };
   // Only the newest stage may still be in flight, and every LDS read of this wavefront has returned.
   auto publish = [&]() { asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(4 * (AHEAD - 2)) : "memory"); };
@@ -556,18 +569,18 @@ __global__ __launch_bounds__(512) void k_gemm_dma(DmaMat A, DmaMat B, Problem pb
   read_lo(0);
   // The loop body is written for an even and an odd stage so that the B double buffer is indexed statically.
   auto one_stage = [&](int s, half8 (&fb_cur)[4]) {
-    issue(s + AHEAD);                        // into the slot of stage s-1: every wavefront finished reading it before the last barrier it passed
     read_hi(s);
     __builtin_amdgcn_sched_barrier(0);
     wait_frags8<RA>(fal, fb_cur);            // requested half a stage ago; only the A 4-7 reads may still be in flight
-    mfma_half(fal, fb_cur, 0);
+    // loads of stage s+AHEAD go into the slot of stage s-1: every wavefront finished reading it before the last barrier it passed
+    mfma_half(fal, fb_cur, 0, s + AHEAD);
     __builtin_amdgcn_sched_barrier(0);
     if (wave >= 4) publish();
     __builtin_amdgcn_sched_barrier(0);
     read_lo(s + 1);                          // stage s+1 was published by an earlier barrier; past the end the data is unused
     __builtin_amdgcn_sched_barrier(0);
     wait_frags4<RA + RB>(fah);
-    mfma_half(fah, fb_cur, 4);
+    mfma_half(fah, fb_cur, 4, s + AHEAD);
     __builtin_amdgcn_sched_barrier(0);
     if (wave < 4) publish();
     __builtin_amdgcn_sched_barrier(0);
