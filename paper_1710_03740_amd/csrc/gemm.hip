@@ -560,12 +560,15 @@ __global__ __launch_bounds__(512) void k_gemm_dma(DmaMat A, DmaMat B, Problem pb
       }
     }
   };
-  // Only the newest stage may still be in flight, and every LDS read of this wavefront has returned.
-  auto publish = [&]() { asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(4 * (AHEAD - 2)) : "memory"); };
+  // Before the barrier that publishes stage s+2: only loads of the newest stage (s+AHEAD) may still be in flight, and
+  // every LDS read of this wavefront has returned.  Wavefronts 0-3 reach their barrier after both halves of the
+  // stage (all 4 newest loads issued), wavefronts 4-7 after the first half (2 issued).
+  auto publish_end = [&]() { asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(4 * (AHEAD - 2)) : "memory"); };
+  auto publish_mid = [&]() { asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(4 * (AHEAD - 2) - 2) : "memory"); };
 
 #pragma unroll
   for (int q = 0; q < AHEAD; ++q) issue(q);
-  publish();                                  // stages 0 and 1 have landed everywhere
+  publish_end();                              // stages 0 and 1 have landed everywhere
   read_lo(0);
   // The loop body is written for an even and an odd stage so that the B double buffer is indexed statically.
   auto one_stage = [&](int s, half8 (&fb_cur)[4]) {
@@ -575,14 +578,14 @@ __global__ __launch_bounds__(512) void k_gemm_dma(DmaMat A, DmaMat B, Problem pb
     // loads of stage s+AHEAD go into the slot of stage s-1: every wavefront finished reading it before the last barrier it passed
     mfma_half(fal, fb_cur, 0, s + AHEAD);
     __builtin_amdgcn_sched_barrier(0);
-    if (wave >= 4) publish();
+    if (wave >= 4) publish_mid();
     __builtin_amdgcn_sched_barrier(0);
     read_lo(s + 1);                          // stage s+1 was published by an earlier barrier; past the end the data is unused
     __builtin_amdgcn_sched_barrier(0);
     wait_frags4<RA + RB>(fah);
     mfma_half(fah, fb_cur, 4, s + AHEAD);
     __builtin_amdgcn_sched_barrier(0);
-    if (wave < 4) publish();
+    if (wave < 4) publish_end();
     __builtin_amdgcn_sched_barrier(0);
   };
   int s = 0;
