@@ -15,6 +15,7 @@
 // LDS is double buffered: global loads for tile t+1 are issued before the MFMAs
 // of tile t and written to the other buffer after them; one barrier per tile.
 #include "mpt_internal.h"
+#include <type_traits>
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
@@ -631,6 +632,210 @@ __global__ __launch_bounds__(512) void k_gemm_dma(DmaMat A, DmaMat B, Problem pb
   }
 }
 
+// ---------------------------------------------------------------- streamed variant with one wavefront per SIMD
+// Same ring, layouts and fragments as k_gemm_dma, but 4 wavefronts as 2 x 2, each owning 128 x 128 of the tile
+// (8 x 8 MFMA blocks, 256 accumulator registers): a stage costs 16 fragment reads per 64 MFMAs instead of 12 per 32,
+// i.e. two thirds of the LDS read traffic, and only four wavefronts meet at the per-stage barrier.  With a single
+// wavefront per SIMD nothing else covers a stall, so everything is software-pipelined inside the wavefront:
+// a stage is 8 steps (one A block against the 8 B blocks); step a requests A block a+2 (wrapping into the next stage),
+// steps 4-7 also request the next stage's B blocks, and every step issues one of the wavefront's 8 LDS-direct loads.
+template <bool RC>
+struct DmaOperand4 {
+  const uint16_t* p[4];     // this lane's source for its four 1 KiB blocks of stage 0
+  int64_t step;             // elements to advance per stage
+  __device__ __forceinline__ void init(const DmaMat& m, int o0, int r0, int wave, int lane) {
+    if constexpr (RC) {
+      const int row = wave * 64 + (lane >> 2);                       // blocks 4w .. 4w+3 hold 16 rows each
+      const int chunk = (lane & 3) ^ ((row >> 1) & 3);               // same for row + 16k
+#pragma unroll
+      for (int k = 0; k < 4; ++k) p[k] = m.base + (int64_t)(o0 + row + 16 * k) * m.ld + r0 + chunk * 8;
+      step = 32;
+    } else {
+      const int pc = lane & 31;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int row = wave * 8 + 2 * k + (lane >> 5);              // blocks 4w .. 4w+3 hold 2 reduction rows each
+        const int c = 2 * ((pc >> 1) ^ oc_key(row)) + (pc & 1);
+        p[k] = m.base + (int64_t)(r0 + row) * m.ld + o0 + c * 8;
+      }
+      step = 32 * m.ld;
+    }
+  }
+  template <int K>
+  __device__ __forceinline__ void issue(int stage_rel, char* lds_blocks) const {
+    __builtin_amdgcn_global_load_lds((global_void_ptr)(p[K] + stage_rel * step), (lds_void_ptr)(lds_blocks + K * 1024), 16, 0, 0);
+  }
+};
+
+// MFMA with the accumulator pinned, in place, to the accumulation half of the register file: the 256 accumulator
+// registers of a 128 x 128 wavefront block fill that half exactly, and left to itself the register allocator shuffles
+// them through the other half.  Issued as assembly, the instruction is opaque to the compiler's hazard handling; the
+// kernel keeps every reuse of an accumulator at least 7 MFMAs apart and idles 32 cycles before the epilogue reads them.
+__device__ __forceinline__ void mfma_acc(float4v& acc, const half8& x, const half8& y) {
+  asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(x), "v"(y));
+}
+template <int NEWER>
+__device__ __forceinline__ void wait_frag1(half8& f) {
+  asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(f) : "n"(NEWER < 15 ? NEWER : 15) : "memory");
+}
+template <int NEWER>
+__device__ __forceinline__ void wait_frags9(half8& f, half8 (&g)[8]) {
+  asm volatile("s_waitcnt lgkmcnt(%9)"
+               : "+v"(f), "+v"(g[0]), "+v"(g[1]), "+v"(g[2]), "+v"(g[3]), "+v"(g[4]), "+v"(g[5]), "+v"(g[6]), "+v"(g[7])
+               : "n"(NEWER < 15 ? NEWER : 15)
+               : "memory");
+}
+
+template <bool A_RC, bool B_RC>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_gemm_dma4(DmaMat A, DmaMat B, Problem pb, Epilogue ep) {
+  constexpr int NSTAGE = 4, AHEAD = 3, OPERAND = 256 * 64, STAGE = 2 * OPERAND;
+  constexpr int RA1 = A_RC ? 1 : 2, RB1 = B_RC ? 1 : 2;               // LDS read instructions per fragment
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  const int t = threadIdx.x, lane = t & 63, wave = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+  int ti, tj, sp;
+  tile_of(pb, blockIdx.x, ti, tj, sp);
+  const int i0 = ti * 256, j0 = tj * 256;
+  const int st_total = pb.R / 32;
+  const int st_begin = sp * pb.ktiles_per_split * 2;
+  const int nst = min(pb.ktiles_per_split * 2, st_total - st_begin);   // stages this workgroup reduces over (>= 1)
+
+  float4v acc[8][8];
+#pragma unroll
+  for (int a = 0; a < 8; ++a)
+#pragma unroll
+    for (int b = 0; b < 8; ++b)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) acc[a][b][v] = 0.f;
+
+  DmaOperand4<A_RC> da;
+  DmaOperand4<B_RC> db;
+  da.init(A, i0, st_begin * 32, wave, lane);
+  db.init(B, j0, st_begin * 32, wave, lane);
+  const int blk = wave * 4096;                                         // this wavefront's four 1 KiB blocks inside an operand stage
+  // load q (0-3: A blocks, 4-7: B blocks) of stage s; past the end: refetch the last slice into a free slot
+  auto issue1 = [&](int s, auto qc) {
+    constexpr int q = decltype(qc)::value;
+    const int sc = min(s, nst - 1);
+    char* st = lds + (s % NSTAGE) * STAGE;
+    if constexpr (q < 4) da.template issue<q>(sc, st + blk);
+    else db.template issue<q - 4>(sc, st + OPERAND + blk);
+  };
+  FragAddr<A_RC> aa[8];
+  FragAddr<B_RC> ab[8];
+#pragma unroll
+  for (int a = 0; a < 8; ++a) aa[a].init(wm * 128 + a * 16, lane);
+#pragma unroll
+  for (int b = 0; b < 8; ++b) ab[b].init(wn * 128 + b * 16, lane);
+  const uint32_t lds0 = lds_offset(lds);
+  half8 fa[8], fb[2][8];                                               // A blocks of the running stage(s); B blocks, double buffered
+  auto stage_base = [&](int s) { return lds0 + (uint32_t)((s % NSTAGE) * STAGE); };
+
+  // prologue: stages 0 and 1 whole, and the A half of stage 2 (the first steps of stage 0 add its B half)
+#define MPT_ISSUE(s, q) issue1((s), std::integral_constant<int, (q)>{})
+  MPT_ISSUE(0, 0); MPT_ISSUE(0, 1); MPT_ISSUE(0, 2); MPT_ISSUE(0, 3); MPT_ISSUE(0, 4); MPT_ISSUE(0, 5); MPT_ISSUE(0, 6); MPT_ISSUE(0, 7);
+  MPT_ISSUE(1, 0); MPT_ISSUE(1, 1); MPT_ISSUE(1, 2); MPT_ISSUE(1, 3); MPT_ISSUE(1, 4); MPT_ISSUE(1, 5); MPT_ISSUE(1, 6); MPT_ISSUE(1, 7);
+  MPT_ISSUE(2, 0); MPT_ISSUE(2, 1); MPT_ISSUE(2, 2); MPT_ISSUE(2, 3);
+  asm volatile("s_waitcnt vmcnt(4)\n\ts_barrier" ::: "memory");        // stages 0 and 1 have landed everywhere
+#pragma unroll
+  for (int b = 0; b < 8; ++b) fb[0][b] = ab[b].read(stage_base(0) + OPERAND);
+  fa[0] = aa[0].read(stage_base(0));
+  fa[1] = aa[1].read(stage_base(0));
+
+  // One step: requests, wait for this step's operands, 8 MFMAs with one LDS-direct load in their middle.
+  // LDS reads complete in order, so "A block a has arrived" is "at most W reads issued after it are outstanding";
+  // A block a was the last request of step a-2, hence W = reads of steps a-1 and a.  Step 0 also needs the whole
+  // B buffer, whose last request precedes the A requests of steps 7 and 0.
+  auto step = [&](int s, auto ac, half8 (&fb_cur)[8], half8 (&fb_nxt)[8]) {
+    constexpr int a = decltype(ac)::value;
+    if constexpr (a == 4) {
+      // Stage s+1 is about to be read and the slot of stage s-1 about to be refilled: every wavefront's loads of
+      // stage s+1 must have landed (only the 8 loads of stage s+2 may be in flight) and every wavefront must be
+      // past stage s-1, all of whose reads were consumed by MFMAs already issued.
+      asm volatile("s_waitcnt vmcnt(8)\n\ts_barrier" ::: "memory");
+    }
+    if constexpr (a >= 4) {
+      fb_nxt[2 * (a - 4)] = ab[2 * (a - 4)].read(stage_base(s + 1) + OPERAND);
+      fb_nxt[2 * (a - 4) + 1] = ab[2 * (a - 4) + 1].read(stage_base(s + 1) + OPERAND);
+    }
+    constexpr int na = (a + 2) & 7;
+    fa[na] = aa[na].read(stage_base(s + ((a + 2) >> 3)));              // steps 6, 7 read the next stage (published at step 4)
+    __builtin_amdgcn_sched_barrier(0);
+    constexpr int W = a < 4 ? 2 * RA1 : (a == 4 ? 2 * RA1 + 2 * RB1 : 2 * RA1 + 4 * RB1);
+    if constexpr (a == 0) wait_frags9<W>(fa[0], fb_cur);
+    else wait_frag1<W>(fa[a]);
+#pragma unroll
+    for (int b = 0; b < 8; ++b) {   // operands swapped: each lane ends up with 4 consecutive output columns of one row
+      mfma_acc(acc[a][b], fb_cur[b], fa[a]);
+      if (b == 3) {
+        __builtin_amdgcn_sched_barrier(0);
+        // steps 4-7 start stage s+3 (A blocks) into the slot just vacated; steps 0-3 finish stage s+2 (B blocks)
+        if constexpr (a >= 4) issue1(s + AHEAD, std::integral_constant<int, a - 4>{});
+        else issue1(s + AHEAD - 1, std::integral_constant<int, a + 4>{});
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  auto one_stage = [&](int s, half8 (&fb_cur)[8], half8 (&fb_nxt)[8]) {
+    step(s, std::integral_constant<int, 0>{}, fb_cur, fb_nxt);
+    step(s, std::integral_constant<int, 1>{}, fb_cur, fb_nxt);
+    step(s, std::integral_constant<int, 2>{}, fb_cur, fb_nxt);
+    step(s, std::integral_constant<int, 3>{}, fb_cur, fb_nxt);
+    step(s, std::integral_constant<int, 4>{}, fb_cur, fb_nxt);
+    step(s, std::integral_constant<int, 5>{}, fb_cur, fb_nxt);
+    step(s, std::integral_constant<int, 6>{}, fb_cur, fb_nxt);
+    step(s, std::integral_constant<int, 7>{}, fb_cur, fb_nxt);
+  };
+#undef MPT_ISSUE
+  // nst is even: the reduction length is a multiple of 64 and splits are cut at multiples of 64
+  for (int s = 0; s < nst; s += 2) {
+    one_stage(s, fb[0], fb[1]);
+    one_stage(s + 1, fb[1], fb[0]);
+  }
+  // drain the tail prefetches before LDS is released, and let the last MFMAs retire before their results are read
+  asm volatile("s_nop 15\n\ts_nop 15\n\ts_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_sched_barrier(0);
+
+  // ---- epilogue (whole tiles, FP16 store with optional Inf/NaN vote; the host sends only unsplit problems with a
+  // 16-byte aligned output and ld % 8 == 0 here).
+  // acc[a][b][e]: row i = 16a + lane%16, column j = 16b + 4*(lane/16) + e of the wavefront's 128 x 128 block.
+  bool bad = false;
+  {
+    // FP16 store through LDS, so that global stores are whole 256-byte row segments instead of 32-byte pieces:
+    // each wavefront rounds its block to FP16 into its own 32 KiB of the (now idle) ring as [128 rows][256 B],
+    // 16-byte unit u of row r kept at unit u ^ (r & 15), then streams it out 16 bytes per lane, 16 lanes per row.
+    __syncthreads();                                                   // every wavefront is done reading the ring
+    char* mine = lds + wave * 32768;
+    const int li = lane & 15, lg = lane >> 4;
+#pragma unroll
+    for (int a = 0; a < 8; ++a)
+#pragma unroll
+      for (int b = 0; b < 8; ++b) {
+        asm volatile("" : "+a"(acc[a][b]) : : "memory");              // keeps the copy out of the accumulation registers here, one block at a time
+        half4 h;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) h[e] = (_Float16)acc[a][b][e];
+        *reinterpret_cast<half4*>(mine + (a * 16 + li) * 256 + (((2 * b + (lg >> 1)) ^ li) << 4) + (lg & 1) * 8) = h;
+      }
+    uint16_t* out = reinterpret_cast<uint16_t*>(ep.out) + (int64_t)(i0 + wm * 128) * ep.ld + j0 + wn * 128 + li * 8;
+#pragma unroll 8
+    for (int it = 0; it < 32; ++it) {
+      const int r = it * 4 + lg;
+      const uint4v q = *reinterpret_cast<const uint4v*>(mine + r * 256 + ((li ^ (r & 15)) << 4));
+      if (ep.flag) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) bad |= half_bits_special(q[e]) | half_bits_special(q[e] >> 16);
+      }
+      *reinterpret_cast<uint4v*>(out + (int64_t)r * ep.ld) = q;
+    }
+  }
+  if (ep.flag != nullptr) {
+    const unsigned long long vote = __builtin_amdgcn_ballot_w64(bad);
+    if (vote != 0ull && lane == 0) atomicOr(ep.flag, 1u);
+  }
+}
+
 // Sum split partials in split order (fixed, so results are reproducible), then store once.
 __global__ __launch_bounds__(256) void k_split_reduce(const float* __restrict__ part, int splits, int I, int J, Epilogue ep) {
   const int64_t total = (int64_t)I * J;
@@ -729,17 +934,27 @@ bool try_launch_dma(hipStream_t s, const AView& A, const BView& B, bool aligned,
     static const bool enabled = mpt_env_int("MPT_GEMM_STREAMED", 1) != 0;
     if (!enabled || !aligned || !pl.big || (I % 256) || (J % 256) || (R % 64) || (ep.mode != 0 && ep.mode != 3)) return false;
     if (ep.mode == 3 && ((ep.ld % 4) || !mpt_aligned(ep.out, 16))) return false;
+    // FP16 stores of unsplit problems into 16-byte aligned rows take the one-wavefront-per-SIMD kernel (same speed at one
+    // tile per CU, about 5 % faster over several); split partials and odd output strides take k_gemm_dma.
+    static const int nwaves = mpt_env_int("MPT_GEMM_WAVES", 4);           // 8 forces k_gemm_dma (tuning only)
+    const bool four = nwaves == 4 && ep.mode == 0 && pl.splits == 1 && (ep.ld % 8) == 0 && mpt_aligned(ep.out, 16);
     static const int nstage = mpt_env_int("MPT_GEMM_STAGES", 4);          // 4 or 5 ring slots of 32 KiB (tuning only)
     auto k4 = k_gemm_dma<DmaKind<AView>::rc, DmaKind<BView>::rc, 4>;
     auto k5 = k_gemm_dma<DmaKind<AView>::rc, DmaKind<BView>::rc, 5>;
+    auto kw4 = k_gemm_dma4<DmaKind<AView>::rc, DmaKind<BView>::rc>;
     static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(k4), hipFuncAttributeMaxDynamicSharedMemorySize, 4 * 32768),
-                        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k5), hipFuncAttributeMaxDynamicSharedMemorySize, 5 * 32768), true);
+                        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k5), hipFuncAttributeMaxDynamicSharedMemorySize, 5 * 32768),
+                        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kw4), hipFuncAttributeMaxDynamicSharedMemorySize, 4 * 32768), true);
     (void)once;
-    auto k = nstage == 5 ? k5 : k4;
-    const int lds = (nstage == 5 ? 5 : 4) * 32768;
     Problem pb{I, J, R, pl.tiles_i, pl.tiles_j, pl.splits, pl.ktiles_per_split};
     const unsigned grid = (unsigned)((int64_t)pl.tiles_i * pl.tiles_j * pl.splits);
-    hipLaunchKernelGGL(k, dim3(grid), dim3(512), lds, s, DmaMat{A.base, A.ld}, DmaMat{B.base, B.ld}, pb, ep);
+    if (four) {
+      hipLaunchKernelGGL(kw4, dim3(grid), dim3(256), 4 * 32768, s, DmaMat{A.base, A.ld}, DmaMat{B.base, B.ld}, pb, ep);
+    } else {
+      auto k = nstage == 5 ? k5 : k4;
+      const int lds = (nstage == 5 ? 5 : 4) * 32768;
+      hipLaunchKernelGGL(k, dim3(grid), dim3(512), lds, s, DmaMat{A.base, A.ld}, DmaMat{B.base, B.ld}, pb, ep);
+    }
     status = hipGetLastError() == hipSuccess ? MPT_OK : MPT_ERR_HIP;
     return true;
   } else {

@@ -87,6 +87,46 @@ def test_leading_dimensions_and_unaligned_bases():
     assert not out[:, :3].any() and not out[:, N + 3:].any()       # nothing written outside the view
 
 
+@pytest.mark.parametrize("pad", [0, 8, 4, 1])
+def test_whole_tile_kernels_over_more_tiles_than_cus(pad):
+    """272 whole 256 x 256 tiles (more than one per CU), reduction depth of 4 and 6 stages, with output row strides
+    that keep 16-byte, 8-byte and 2-byte alignment: every store path of the whole-tile kernels."""
+    M, N = 4352, 4096
+    rng = np.random.default_rng(77 + pad)
+    for K in ((128, 192) if pad == 0 else (128,)):
+        X = rng.standard_normal((M, K)).astype(np.float16)
+        W = (rng.standard_normal((K, N)) * 0.05).astype(np.float16)
+        Yb = torch.full((M, N + pad), 7.0, dtype=torch.float16, device="cuda")
+        mpt.mpt_gemm_fwd(dev16(X), dev16(W), Yb[:, :N])
+        y, sa, s = gemm.gemm_fwd(X, W, full=True)
+        out = host16(Yb)
+        gemm_check(np.ascontiguousarray(out[:, :N]), y, sa, s, "fwd pad %d K %d" % (pad, K))
+        assert (out[:, N:] == 7.0).all()                          # nothing written outside the view
+        if pad == 0:
+            dY = (np.exp2(rng.uniform(-20, -3, (M, N))) * rng.choice([-1, 1], (M, N))).astype(np.float16)
+            Wd = (rng.standard_normal((4096, N)) * 0.05).astype(np.float16)     # dgrad output 4352 x 4096, reduce over N
+            dx, sa, s = gemm.gemm_dgrad(dY[:, :K], Wd[:, :K], full=True)
+            gemm_check(run_dgrad(np.ascontiguousarray(dY[:, :K]), np.ascontiguousarray(Wd[:, :K])), dx, sa, s, "dgrad K %d" % K)
+            Xw = rng.standard_normal((K, M)).astype(np.float16)                  # wgrad output 4352 x 4096, reduce over K rows
+            dYw = np.ascontiguousarray(dY[:K, :])
+            dw, sa, s = gemm.gemm_wgrad(Xw, dYw, full=True)
+            gemm_check(run_wgrad(Xw, dYw), dw, sa, s, "wgrad K %d" % K)
+
+
+def test_whole_tile_wgrad_flag():
+    M, K, N = 64, 4352, 4096
+    X = np.full((M, K), 2.0 ** -3, dtype=np.float16)
+    dY = np.full((M, N), 2.0 ** -3, dtype=np.float16)
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    run_wgrad(X, dY, flag=flag)
+    assert int(flag.item()) == 0
+    X[:, K - 1] = 300.0
+    dY[:, N - 1] = 300.0                                           # one element of the last tile sums to 64 * 9e4 -> Inf
+    dW = run_wgrad(X, dY, flag=flag)
+    assert fp16.bits(dW)[K - 1, N - 1] == 0x7C00 and int(flag.item()) == 1
+    assert np.isfinite(dW.astype(np.float32)).sum() == K * N - 1
+
+
 def test_overflow_stores_inf_and_raises_wgrad_flag():
     X = np.full((64, 8), 200.0, dtype=np.float16)
     dY = np.full((64, 8), 100.0, dtype=np.float16)
