@@ -117,7 +117,7 @@ def main():
     achieved = 2.0 * n ** 3 / (gemm_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "achieved": round(achieved, 1), "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / MFMA_F16_PEAK_TFLOPS, 4), "traffic": GEMM_TRAFFIC_BYTES,
-                "kernel": "k_gemm_dma: streamed 256x256 tile of 16x16x32 MFMA blocks, K=32 stages (avg of fwd, dgrad, wgrad)", "avg_launch_us": round(gemm_ms * 1e3, 2),
+                "kernel": "k_gemm_dma4: streamed 256x256 tile, 4 wavefronts x 128x128 of 16x16x32 MFMA blocks, K=32 stages (avg of fwd, dgrad, wgrad)", "avg_launch_us": round(gemm_ms * 1e3, 2),
                 "per_pass_us": {k: round(1e3 * sum(ev[i].elapsed_time(ev[i + 1]) for ev in gemm_events) / len(gemm_events), 2)
                                 for i, k in enumerate(("fwd", "dgrad", "wgrad"))}}
 

@@ -53,9 +53,9 @@ int mpt_version(void);
  * Dense contractions (Sec. 3.3: FP16 products, FP32 accumulation, one RNE
  * rounding to FP16 on store; Sec. 3.1 / Fig. 1: forward, backward-activation
  * and backward-weight of a layer).  X[M,K] activations, W[K,N] weights,
- * Y[M,N] outputs, dY[M,N] upstream gradient.  Any M,N,K >= 1 (each < 2^31 and
- * every matrix below 2^31 elements per operand row span).  Fast path: base pointers 16-byte aligned
- * and leading dimensions multiples of 8; anything else (2-byte alignment is the
+ * Y[M,N] outputs, dY[M,N] upstream gradient, all row-major with a leading
+ * dimension in elements.  Any M,N,K from 1 to 2^31 - 513 (else MPT_ERR_SHAPE).
+ * Fast path: base pointers 16-byte aligned and leading dimensions multiples of 8; anything else (2-byte alignment is the
  * minimum) takes a slower element-wise loader with identical results.
  *
  * Workspace: split-reduction needs FP32 partials in caller memory.  Pass
