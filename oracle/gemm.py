@@ -42,6 +42,23 @@ def gemm_dgrad(dY16, W16, full=False):
     return _ret(s, sabs, full)
 
 
+def gemm_fwd_relu(X16, W16, full=False):
+    """H[m,n] = rne16(max(sum_k X[m,k] W[k,n], 0)): the layer's pointwise non-linearity
+    (Sec. 3.3, third category) applied to the wide sum before its one rounding."""
+    s, sabs = _contract(to_f64(X16), to_f64(W16))
+    with np.errstate(invalid="ignore"):
+        s = np.where(s > 0, s, 0.0)                  # same rule as the stand-alone ReLU: anything not > 0 (NaN too) gives 0
+    return _ret(s, sabs, full)
+
+
+def gemm_dgrad_relu(dY16, W16, H16, full=False):
+    """dX[m,k] = rne16(sum_n dY[m,n] W[k,n]) where H[m,k] > 0, else 0: the backward pass of
+    the layer below's ReLU folded into the store (H is that layer's FP16 output)."""
+    s, sabs = _contract(to_f64(dY16), to_f64(W16).T)
+    s = np.where(to_f64(H16) > 0, s, 0.0)
+    return _ret(s, sabs, full)
+
+
 def gemm_wgrad(X16, dY16, out_fp32=False, acc32=None, full=False):
     """dW[k,n] = sum_m X[m,k] dY[m,n].
 

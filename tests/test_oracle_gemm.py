@@ -130,3 +130,25 @@ def test_planted_mistakes_are_caught():
     assert not np.array_equal(gemm.gemm_fwd(X, W.T.copy())[0].astype(np.int64), Xi @ Wi)
     assert not np.array_equal(gemm.gemm_dgrad(dY, W)[0].astype(np.int64), dYi @ Wi)
     assert not np.array_equal(gemm.gemm_wgrad(X, dY)[0].astype(np.int64), dYi.T @ Xi)
+
+
+def test_fused_relu_forms_equal_the_unfused_composition():
+    """Rounding commutes with max(., 0) (RNE is monotone and keeps the sign), so folding the ReLU into the store
+    must give exactly what the separate pointwise pass gives; same for the backward mask."""
+    from oracle import loss
+    rng = np.random.default_rng(21)
+    X = rng.standard_normal((37, 50)).astype(np.float16)
+    W = (rng.standard_normal((50, 29)) * 0.2).astype(np.float16)
+    h, _ = gemm.gemm_fwd_relu(X, W)
+    y, _ = gemm.gemm_fwd(X, W)
+    assert np.array_equal(fp16.bits(h), fp16.bits(loss.relu_fwd(y)))
+    assert (h == 0).mean() > 0.3 and (h > 0).mean() > 0.3
+    dY = (rng.standard_normal((37, 29)) * 2.0 ** -8).astype(np.float16)
+    H = loss.relu_fwd(rng.standard_normal((37, 50)).astype(np.float16))
+    dx, _ = gemm.gemm_dgrad_relu(dY, W, H)
+    d0, _ = gemm.gemm_dgrad(dY, W)
+    assert np.array_equal(fp16.bits(dx), fp16.bits(loss.relu_bwd(d0, H)))
+    # a hand-made case: one row, weights +-1
+    x = np.array([[1.0, 2.0]], dtype=np.float16); w = np.array([[1.0, -1.0], [1.0, -1.0]], dtype=np.float16)
+    assert gemm.gemm_fwd_relu(x, w)[0].tolist() == [[3.0, 0.0]]
+    assert gemm.gemm_dgrad_relu(np.array([[1.0, 2.0]], dtype=np.float16), w, np.array([[0.0, 5.0]], dtype=np.float16))[0].tolist() == [[0.0, -1.0]]
