@@ -82,6 +82,24 @@ int mpt_gemm_dgrad(void* stream, int64_t M, int64_t N, int64_t K,
                    uint16_t* dX_dev, int64_t ldx,
                    void* ws_dev, size_t ws_bytes);
 
+/* The pointwise non-linearity of a layer (Sec. 3.3, third category) folded into the store of the contraction that
+ * produces its input, so the activation tensor makes one trip to memory instead of three:
+ *   fwd_relu:   H[m,n]  = rne16( max( sum_k X[m,k] * W[k,n], 0 ) )      (anything not > 0, NaN included, stores +0)
+ *   dgrad_relu: dX[m,k] = H[m,k] > 0 ? rne16( sum_n dY[m,n] * W[k,n] ) : +0
+ * where H[M,K] (ldh >= K) is the FP16 output that the layer below stored with fwd_relu.  Same shapes, alignment
+ * rules, workspace and error behaviour as mpt_gemm_fwd / mpt_gemm_dgrad; H is only read. */
+int mpt_gemm_fwd_relu(void* stream, int64_t M, int64_t N, int64_t K,
+                      const uint16_t* X_dev, int64_t ldx,
+                      const uint16_t* W_dev, int64_t ldw,
+                      uint16_t* H_dev, int64_t ldh,
+                      void* ws_dev, size_t ws_bytes);
+int mpt_gemm_dgrad_relu(void* stream, int64_t M, int64_t N, int64_t K,
+                        const uint16_t* dY_dev, int64_t ldy,
+                        const uint16_t* W_dev, int64_t ldw,
+                        const uint16_t* H_dev, int64_t ldh,
+                        uint16_t* dX_dev, int64_t ldx,
+                        void* ws_dev, size_t ws_bytes);
+
 /* dW[k,n] = sum_m X[m,k] * dY[m,n].
  *   out_fp32 = 0: dW_dev is uint16_t*, FP16 store (the paper's stored weight gradient); accumulate must be 0.
  *   out_fp32 = 1: dW_dev is float*, FP32 store; accumulate = 1 adds this call's sum to the buffer's
@@ -195,6 +213,47 @@ int mpt_relu_bwd(void* stream, size_t n, const uint16_t* dh_dev, const uint16_t*
 int mpt_softmax_xent_scaled(void* stream, int64_t B, int64_t C,
                             const uint16_t* logits_dev, int64_t ldl, const int32_t* labels_dev,
                             float scale, float* loss_dev, uint16_t* dlogits_dev, int64_t ldd);
+
+/* ------------------------------------------------------------------------- *
+ * Batch normalisation over an FP16 tensor x[P, C], channels contiguous, row
+ * stride ldx >= C elements (an NHWC activation with P = N*H*W).  Sec. 3.3: the
+ * statistics are large reductions and are accumulated wide; the layer reads
+ * and writes FP16 and computes in FP32.  Training-mode definition (the paper
+ * prints no formulas), per channel c:
+ *   mean_c = (1/P) sum_p x[p,c]        var_c = (1/P) sum_p (x[p,c] - mean_c)^2
+ *   y[p,c] = rne16( x*scale_c + shift_c ),  scale_c = gamma_c * (1/sqrt(var_c + eps)),
+ *            shift_c = beta_c - mean_c*scale_c      (then max(.,0) if relu != 0)
+ *   dbeta_c = sum_p dy[p,c]     dgamma_c = sum_p dy[p,c] * xhat[p,c],
+ *            xhat = (x - mean_c) * (1/sqrt(var_c + eps))
+ *   dx[p,c] = rne16( a_c * ((dy - dbeta_c/P) - xhat * dgamma_c/P) ),  a_c = gamma_c * (1/sqrt(var_c + eps))
+ * Every pointwise operation is an individually rounded FP32 operation in the
+ * order written (no fused multiply-add), so results are reproducible bit for
+ * bit from the same statistics.  Reductions run as FP32 chains of at most 16
+ * rows folded into FP64, in a fixed order (run-to-run identical), and are
+ * rounded once to FP32.  dy may carry the loss scale; dgamma / dbeta / dx
+ * then carry it too (everything is linear in dy).
+ *
+ * All pointers are device pointers owned by the caller; mean, var, gamma,
+ * beta, dgamma, dbeta are FP32[C].  Fast path: 16-byte aligned tensors, C and
+ * row strides multiples of 8; anything else takes a scalar path with the same
+ * results.  ws_dev: caller scratch of at least mpt_bn_workspace_bytes(P, C)
+ * bytes, 16-byte aligned (FP64 partial sums), required by the two reductions.
+ * Errors (nothing enqueued): NULL, SHAPE (P or C < 1, stride < C), ALIGN,
+ * WORKSPACE, ARG (eps negative or not finite).
+ * ------------------------------------------------------------------------- */
+size_t mpt_bn_workspace_bytes(int64_t P, int64_t C);
+int mpt_bn_stats(void* stream, int64_t P, int64_t C, const uint16_t* x_dev, int64_t ldx,
+                 float* mean_dev, float* var_dev, void* ws_dev, size_t ws_bytes);
+int mpt_bn_apply(void* stream, int64_t P, int64_t C, const uint16_t* x_dev, int64_t ldx,
+                 const float* mean_dev, const float* var_dev, const float* gamma_dev, const float* beta_dev,
+                 float eps, int relu, uint16_t* y_dev, int64_t ldy);
+int mpt_bn_bwd_reduce(void* stream, int64_t P, int64_t C, const uint16_t* x_dev, int64_t ldx,
+                      const uint16_t* dy_dev, int64_t lddy, const float* mean_dev, const float* var_dev, float eps,
+                      float* dgamma_dev, float* dbeta_dev, void* ws_dev, size_t ws_bytes);
+int mpt_bn_bwd_apply(void* stream, int64_t P, int64_t C, const uint16_t* x_dev, int64_t ldx,
+                     const uint16_t* dy_dev, int64_t lddy, const float* mean_dev, const float* var_dev,
+                     const float* gamma_dev, float eps, const float* dgamma_dev, const float* dbeta_dev,
+                     uint16_t* dx_dev, int64_t lddx);
 
 #ifdef __cplusplus
 }

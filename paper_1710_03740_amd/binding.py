@@ -38,6 +38,8 @@ SIGNATURES = {
     "mpt_gemm_workspace_bytes": (c_sz, [c_i, c_i64, c_i64, c_i64]),
     "mpt_gemm_fwd": (c_i, _GEMM),
     "mpt_gemm_dgrad": (c_i, _GEMM),
+    "mpt_gemm_fwd_relu": (c_i, _GEMM),
+    "mpt_gemm_dgrad_relu": (c_i, [c_vp, c_i64, c_i64, c_i64, c_vp, c_i64, c_vp, c_i64, c_vp, c_i64, c_vp, c_i64, c_vp, c_sz]),
     "mpt_gemm_wgrad": (c_i, [c_vp, c_i64, c_i64, c_i64, c_vp, c_i64, c_vp, c_i64, c_vp, c_i64, c_i, c_i, c_vp, c_vp, c_sz]),
     "mpt_conv3x3_workspace_bytes": (c_sz, [c_i, c_i64, c_i64, c_i64, c_i64, c_i64]),
     "mpt_conv3x3_fwd": (c_i, _CONV),
@@ -51,6 +53,11 @@ SIGNATURES = {
     "mpt_relu_fwd": (c_i, [c_vp, c_sz, c_vp, c_vp]),
     "mpt_relu_bwd": (c_i, [c_vp, c_sz, c_vp, c_vp, c_vp]),
     "mpt_softmax_xent_scaled": (c_i, [c_vp, c_i64, c_i64, c_vp, c_i64, c_vp, c_f, c_vp, c_vp, c_i64]),
+    "mpt_bn_workspace_bytes": (c_sz, [c_i64, c_i64]),
+    "mpt_bn_stats": (c_i, [c_vp, c_i64, c_i64, c_vp, c_i64, c_vp, c_vp, c_vp, c_sz]),
+    "mpt_bn_apply": (c_i, [c_vp, c_i64, c_i64, c_vp, c_i64, c_vp, c_vp, c_vp, c_vp, c_f, c_i, c_vp, c_i64]),
+    "mpt_bn_bwd_reduce": (c_i, [c_vp, c_i64, c_i64, c_vp, c_i64, c_vp, c_i64, c_vp, c_vp, c_f, c_vp, c_vp, c_vp, c_sz]),
+    "mpt_bn_bwd_apply": (c_i, [c_vp, c_i64, c_i64, c_vp, c_i64, c_vp, c_i64, c_vp, c_vp, c_vp, c_f, c_vp, c_vp, c_vp, c_i64]),
 }
 
 _lib = None
@@ -121,6 +128,23 @@ def mpt_gemm_dgrad(dY, W, dX, ws=None):
     K = W.shape[0]
     p, b = _ws(ws)
     _check("mpt_gemm_dgrad", lib().mpt_gemm_dgrad(_stream(), M, N, K, _p(dY), dY.stride(0), _p(W), W.stride(0), _p(dX), dX.stride(0), p, b))
+
+
+def mpt_gemm_fwd_relu(X, W, H, ws=None):
+    _dev(X, W, H, ws)
+    M, K = X.shape
+    N = W.shape[1]
+    p, b = _ws(ws)
+    _check("mpt_gemm_fwd_relu", lib().mpt_gemm_fwd_relu(_stream(), M, N, K, _p(X), X.stride(0), _p(W), W.stride(0), _p(H), H.stride(0), p, b))
+
+
+def mpt_gemm_dgrad_relu(dY, W, H, dX, ws=None):
+    _dev(dY, W, H, dX, ws)
+    M, N = dY.shape
+    K = W.shape[0]
+    p, b = _ws(ws)
+    _check("mpt_gemm_dgrad_relu", lib().mpt_gemm_dgrad_relu(_stream(), M, N, K, _p(dY), dY.stride(0), _p(W), W.stride(0),
+                                                            _p(H), H.stride(0), _p(dX), dX.stride(0), p, b))
 
 
 def mpt_gemm_wgrad(X, dY, dW, accumulate=False, flag=None, ws=None):
@@ -215,3 +239,37 @@ def mpt_softmax_xent_scaled(logits, labels, scale, dlogits, loss=None):
     B, C = logits.shape
     _check("mpt_softmax_xent_scaled", lib().mpt_softmax_xent_scaled(_stream(), B, C, _p(logits), logits.stride(0), _p(labels),
                                                                     scale, _p(loss), _p(dlogits), dlogits.stride(0)))
+
+
+# ---------------------------------------------------------------- batch normalisation (x viewed as [P, C])
+def mpt_bn_workspace_bytes(P, C):
+    return lib().mpt_bn_workspace_bytes(P, C)
+
+
+def mpt_bn_stats(x, mean, var, ws):
+    _dev(x, mean, var, ws)
+    P, C = x.shape
+    p, b = _ws(ws)
+    _check("mpt_bn_stats", lib().mpt_bn_stats(_stream(), P, C, _p(x), x.stride(0), _p(mean), _p(var), p, b))
+
+
+def mpt_bn_apply(x, mean, var, gamma, beta, eps, y, relu=False):
+    _dev(x, mean, var, gamma, beta, y)
+    P, C = x.shape
+    _check("mpt_bn_apply", lib().mpt_bn_apply(_stream(), P, C, _p(x), x.stride(0), _p(mean), _p(var), _p(gamma), _p(beta),
+                                              eps, 1 if relu else 0, _p(y), y.stride(0)))
+
+
+def mpt_bn_bwd_reduce(x, dy, mean, var, eps, dgamma, dbeta, ws):
+    _dev(x, dy, mean, var, dgamma, dbeta, ws)
+    P, C = x.shape
+    p, b = _ws(ws)
+    _check("mpt_bn_bwd_reduce", lib().mpt_bn_bwd_reduce(_stream(), P, C, _p(x), x.stride(0), _p(dy), dy.stride(0), _p(mean), _p(var),
+                                                        eps, _p(dgamma), _p(dbeta), p, b))
+
+
+def mpt_bn_bwd_apply(x, dy, mean, var, gamma, eps, dgamma, dbeta, dx):
+    _dev(x, dy, mean, var, gamma, dgamma, dbeta, dx)
+    P, C = x.shape
+    _check("mpt_bn_bwd_apply", lib().mpt_bn_bwd_apply(_stream(), P, C, _p(x), x.stride(0), _p(dy), dy.stride(0), _p(mean), _p(var),
+                                                      _p(gamma), eps, _p(dgamma), _p(dbeta), _p(dx), dx.stride(0)))

@@ -221,7 +221,7 @@ __global__ void k_scaler_update(mpt_scaler* __restrict__ s, uint32_t* __restrict
     }
   }
   s->scale = scale;
-  s->inv_scale = __fdiv_rn(1.0f, scale);
+  s->inv_scale = div_rn(1.0f, scale);
   s->good_steps = good;
   *flag = 0u;
 }
@@ -297,7 +297,7 @@ __global__ __launch_bounds__(kThreads) void k_softmax_xent_grad(
   const int32_t lab = labels[row];
   _Float16* d = reinterpret_cast<_Float16*>(dlogits) + row * ldd;
   for (int64_t c = lane; c < C; c += 64) {
-    const float p = __fdiv_rn(expf(__fsub_rn((float)z[c], mx)), sum);
+    const float p = div_rn(expf(__fsub_rn((float)z[c], mx)), sum);
     d[c] = (_Float16)__fmul_rn(__fsub_rn(p, c == lab ? 1.0f : 0.0f), factor);
   }
 }
@@ -325,7 +325,7 @@ __global__ __launch_bounds__(kThreads) void k_softmax_xent_loss(
   if (threadIdx.x == 0) {
     float t = 0.f;
     for (int i = 0; i < kThreads / 64; ++i) t = __fadd_rn(t, part[i]);
-    loss[0] = __fdiv_rn(t, (float)B);
+    loss[0] = div_rn(t, (float)B);
   }
 }
 

@@ -214,7 +214,31 @@ struct Epilogue {
   int64_t ld;
   int mode;             // 0: FP16 store, 1: FP32 store, 2: FP32 accumulate, 3: FP32 partial [split][I][J]
   uint32_t* flag;       // nullable; OR 1 when an FP16/FP32 stored value is Inf/NaN (modes 0..2)
+  int act;              // FP16 store only.  0: none; 1: ReLU, store 0 unless the value is > 0;
+                        // 2: store 0 unless mask[i][j] > 0 (the ReLU of the layer below, backward)
+  const uint16_t* mask; // act == 2: FP16 matrix of the output's shape
+  int64_t ldmask;
 };
+
+// FP16 bit pattern of a value > 0 (Inf included, NaN not).
+__device__ __forceinline__ bool half_bits_positive(uint32_t b) { return (uint16_t)((b & 0xFFFFu) - 1u) < 0x7C00u; }
+// Pointwise stage of an FP16 store: 4 consecutive outputs of row i starting at column j (n of them inside the matrix).
+__device__ __forceinline__ uint2v apply_act4(uint2v hb, const Epilogue& ep, int64_t i, int64_t j, int n) {
+  if (ep.act == 0) return hb;
+  uint32_t keep = 0;
+  if (ep.act == 1) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) keep |= (uint32_t)half_bits_positive(hb[e >> 1] >> ((e & 1) * 16)) << e;
+  } else {
+    const uint16_t* m = ep.mask + i * ep.ldmask + j;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (e < n) keep |= (uint32_t)half_bits_positive(m[e]) << e;
+  }
+  hb[0] &= ((keep & 1u) ? 0x0000FFFFu : 0u) | ((keep & 2u) ? 0xFFFF0000u : 0u);
+  hb[1] &= ((keep & 4u) ? 0x0000FFFFu : 0u) | ((keep & 8u) ? 0xFFFF0000u : 0u);
+  return hb;
+}
 
 struct Problem {
   int I, J, R;          // output rows, output cols, reduction length
@@ -336,7 +360,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void k_gemm(AView A, BV
           half4 h;
 #pragma unroll
           for (int e = 0; e < 4; ++e) h[e] = (_Float16)x[e];
-          const uint2v hb = __builtin_bit_cast(uint2v, h);
+          const uint2v hb = apply_act4(__builtin_bit_cast(uint2v, h), ep, i, j, nj);
           if (ep.flag) {
 #pragma unroll
             for (int e = 0; e < 4; ++e) bad |= (e < nj) & half_bits_special(hb[e >> 1] >> ((e & 1) * 16));
@@ -612,7 +636,7 @@ __global__ __launch_bounds__(512) void k_gemm_dma(DmaMat A, DmaMat B, Problem pb
         half4 h;
 #pragma unroll
         for (int e = 0; e < 4; ++e) h[e] = (_Float16)acc[a][b][e];
-        const uint2v hb = __builtin_bit_cast(uint2v, h);
+        const uint2v hb = apply_act4(__builtin_bit_cast(uint2v, h), ep, i, j, 4);
         if (ep.flag) bad |= half_bits_special(hb[0]) | half_bits_special(hb[0] >> 16) | half_bits_special(hb[1]) | half_bits_special(hb[1] >> 16);
         uint16_t* o = reinterpret_cast<uint16_t*>(ep.out) + (int64_t)i * ep.ld + j;
         if ((reinterpret_cast<uintptr_t>(o) & 7) == 0) {
@@ -822,7 +846,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #pragma unroll 8
     for (int it = 0; it < 32; ++it) {
       const int r = it * 4 + lg;
-      const uint4v q = *reinterpret_cast<const uint4v*>(mine + r * 256 + ((li ^ (r & 15)) << 4));
+      uint4v q = *reinterpret_cast<const uint4v*>(mine + r * 256 + ((li ^ (r & 15)) << 4));
+      if (ep.act == 1) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          q[e] &= (half_bits_positive(q[e]) ? 0x0000FFFFu : 0u) | (half_bits_positive(q[e] >> 16) ? 0xFFFF0000u : 0u);
+      } else if (ep.act == 2) {                                        // the host sends only 16-byte aligned masks with ldmask % 8 == 0 here
+        const uint4v m = *reinterpret_cast<const uint4v*>(ep.mask + (int64_t)(i0 + wm * 128 + r) * ep.ldmask + j0 + wn * 128 + li * 8);
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          q[e] &= (half_bits_positive(m[e]) ? 0x0000FFFFu : 0u) | (half_bits_positive(m[e] >> 16) ? 0xFFFF0000u : 0u);
+      }
       if (ep.flag) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) bad |= half_bits_special(q[e]) | half_bits_special(q[e] >> 16);
@@ -847,7 +881,9 @@ __global__ __launch_bounds__(256) void k_split_reduce(const float* __restrict__ 
     const int64_t i = idx / J, j = idx - i * J;
     if (ep.mode == 0) {
       const _Float16 h = (_Float16)s;
-      const uint16_t hb = __builtin_bit_cast(uint16_t, h);
+      uint16_t hb = __builtin_bit_cast(uint16_t, h);
+      if (ep.act == 1 && !half_bits_positive(hb)) hb = 0;
+      if (ep.act == 2 && !half_bits_positive(ep.mask[i * ep.ldmask + j])) hb = 0;
       bad = half_bits_special(hb);
       reinterpret_cast<uint16_t*>(ep.out)[i * ep.ld + j] = hb;
     } else {
@@ -937,7 +973,8 @@ bool try_launch_dma(hipStream_t s, const AView& A, const BView& B, bool aligned,
     // FP16 stores of unsplit problems into 16-byte aligned rows take the one-wavefront-per-SIMD kernel (same speed at one
     // tile per CU, about 5 % faster over several); split partials and odd output strides take k_gemm_dma.
     static const int nwaves = mpt_env_int("MPT_GEMM_WAVES", 4);           // 8 forces k_gemm_dma (tuning only)
-    const bool four = nwaves == 4 && ep.mode == 0 && pl.splits == 1 && (ep.ld % 8) == 0 && mpt_aligned(ep.out, 16);
+    const bool four = nwaves == 4 && ep.mode == 0 && pl.splits == 1 && (ep.ld % 8) == 0 && mpt_aligned(ep.out, 16) &&
+                      (ep.act != 2 || ((ep.ldmask % 8) == 0 && mpt_aligned(ep.mask, 16)));
     static const int nstage = mpt_env_int("MPT_GEMM_STAGES", 4);          // 4 or 5 ring slots of 32 KiB (tuning only)
     auto k4 = k_gemm_dma<DmaKind<AView>::rc, DmaKind<BView>::rc, 4>;
     auto k5 = k_gemm_dma<DmaKind<AView>::rc, DmaKind<BView>::rc, 5>;
@@ -1013,26 +1050,50 @@ extern "C" size_t mpt_gemm_workspace_bytes(int op, int64_t M, int64_t N, int64_t
   return plan_ws_bytes(make_plan(I, J, R, true), I, J);
 }
 
-extern "C" int mpt_gemm_fwd(void* stream, int64_t M, int64_t N, int64_t K, const uint16_t* X, int64_t ldx,
-                            const uint16_t* W, int64_t ldw, uint16_t* Y, int64_t ldy, void* ws, size_t ws_bytes) {
+namespace {
+int gemm_fwd_impl(void* stream, int64_t M, int64_t N, int64_t K, const uint16_t* X, int64_t ldx, const uint16_t* W, int64_t ldw,
+                  uint16_t* Y, int64_t ldy, int act, void* ws, size_t ws_bytes) {
   if (X == nullptr || W == nullptr || Y == nullptr) return MPT_ERR_NULL;
   if (!dims_ok(M, N, K) || ldx < K || ldw < N || ldy < N) return MPT_ERR_SHAPE;
   if (!mpt_aligned(X, 2) || !mpt_aligned(W, 2) || !mpt_aligned(Y, 2) || (ws && !mpt_aligned(ws, 16))) return MPT_ERR_ALIGN;
   MatRC A{X, ldx, (int)M, (int)K};
   MatOC B{W, ldw, (int)N, (int)K};
-  Epilogue ep{Y, ldy, 0, nullptr};
+  Epilogue ep{Y, ldy, 0, nullptr, act, nullptr, 0};
   return run(static_cast<hipStream_t>(stream), A, B, mat_fast(X, ldx, K), mat_fast(W, ldw, N), (int)M, (int)N, (int)K, ep, ws, ws_bytes);
+}
+
+int gemm_dgrad_impl(void* stream, int64_t M, int64_t N, int64_t K, const uint16_t* dY, int64_t ldy, const uint16_t* W, int64_t ldw,
+                    const uint16_t* H, int64_t ldh, bool masked, uint16_t* dX, int64_t ldx, void* ws, size_t ws_bytes) {
+  if (dY == nullptr || W == nullptr || dX == nullptr || (masked && H == nullptr)) return MPT_ERR_NULL;
+  if (!dims_ok(M, N, K) || ldy < N || ldw < N || ldx < K || (masked && ldh < K)) return MPT_ERR_SHAPE;
+  if (!mpt_aligned(dY, 2) || !mpt_aligned(W, 2) || !mpt_aligned(dX, 2) || (masked && !mpt_aligned(H, 2)) || (ws && !mpt_aligned(ws, 16)))
+    return MPT_ERR_ALIGN;
+  MatRC A{dY, ldy, (int)M, (int)N};
+  MatRC B{W, ldw, (int)K, (int)N};
+  Epilogue ep{dX, ldx, 0, nullptr, masked ? 2 : 0, masked ? H : nullptr, masked ? ldh : 0};
+  return run(static_cast<hipStream_t>(stream), A, B, mat_fast(dY, ldy, N), mat_fast(W, ldw, N), (int)M, (int)K, (int)N, ep, ws, ws_bytes);
+}
+}  // namespace
+
+extern "C" int mpt_gemm_fwd(void* stream, int64_t M, int64_t N, int64_t K, const uint16_t* X, int64_t ldx,
+                            const uint16_t* W, int64_t ldw, uint16_t* Y, int64_t ldy, void* ws, size_t ws_bytes) {
+  return gemm_fwd_impl(stream, M, N, K, X, ldx, W, ldw, Y, ldy, 0, ws, ws_bytes);
+}
+
+extern "C" int mpt_gemm_fwd_relu(void* stream, int64_t M, int64_t N, int64_t K, const uint16_t* X, int64_t ldx,
+                                 const uint16_t* W, int64_t ldw, uint16_t* H, int64_t ldh, void* ws, size_t ws_bytes) {
+  return gemm_fwd_impl(stream, M, N, K, X, ldx, W, ldw, H, ldh, 1, ws, ws_bytes);
 }
 
 extern "C" int mpt_gemm_dgrad(void* stream, int64_t M, int64_t N, int64_t K, const uint16_t* dY, int64_t ldy,
                               const uint16_t* W, int64_t ldw, uint16_t* dX, int64_t ldx, void* ws, size_t ws_bytes) {
-  if (dY == nullptr || W == nullptr || dX == nullptr) return MPT_ERR_NULL;
-  if (!dims_ok(M, N, K) || ldy < N || ldw < N || ldx < K) return MPT_ERR_SHAPE;
-  if (!mpt_aligned(dY, 2) || !mpt_aligned(W, 2) || !mpt_aligned(dX, 2) || (ws && !mpt_aligned(ws, 16))) return MPT_ERR_ALIGN;
-  MatRC A{dY, ldy, (int)M, (int)N};
-  MatRC B{W, ldw, (int)K, (int)N};
-  Epilogue ep{dX, ldx, 0, nullptr};
-  return run(static_cast<hipStream_t>(stream), A, B, mat_fast(dY, ldy, N), mat_fast(W, ldw, N), (int)M, (int)K, (int)N, ep, ws, ws_bytes);
+  return gemm_dgrad_impl(stream, M, N, K, dY, ldy, W, ldw, nullptr, 0, false, dX, ldx, ws, ws_bytes);
+}
+
+extern "C" int mpt_gemm_dgrad_relu(void* stream, int64_t M, int64_t N, int64_t K, const uint16_t* dY, int64_t ldy,
+                                   const uint16_t* W, int64_t ldw, const uint16_t* H, int64_t ldh, uint16_t* dX, int64_t ldx,
+                                   void* ws, size_t ws_bytes) {
+  return gemm_dgrad_impl(stream, M, N, K, dY, ldy, W, ldw, H, ldh, true, dX, ldx, ws, ws_bytes);
 }
 
 extern "C" int mpt_gemm_wgrad(void* stream, int64_t M, int64_t N, int64_t K, const uint16_t* X, int64_t ldx,
@@ -1046,7 +1107,7 @@ extern "C" int mpt_gemm_wgrad(void* stream, int64_t M, int64_t N, int64_t K, con
     return MPT_ERR_ALIGN;
   MatOC A{X, ldx, (int)K, (int)M};
   MatOC B{dY, ldy, (int)N, (int)M};
-  Epilogue ep{dW, lddw, out_fp32 ? (accumulate ? 2 : 1) : 0, flag};
+  Epilogue ep{dW, lddw, out_fp32 ? (accumulate ? 2 : 1) : 0, flag, 0, nullptr, 0};
   return run(static_cast<hipStream_t>(stream), A, B, mat_fast(X, ldx, K), mat_fast(dY, ldy, N), (int)K, (int)N, (int)M, ep, ws, ws_bytes);
 }
 
@@ -1083,7 +1144,7 @@ extern "C" int mpt_conv3x3_fwd(void* stream, int64_t Nb, int64_t H, int64_t W, i
   const int P = (int)(Nb * H * W), R = (int)(9 * C);
   ImgRC A{x, (int)H, (int)W, (int)C, P, R, +1, FastDiv((uint32_t)(H * W)), FastDiv((uint32_t)W), FastDiv((uint32_t)C)};
   MatRC B{w, 9 * C, (int)Kf, R};
-  Epilogue ep{y, Kf, 0, nullptr};
+  Epilogue ep{y, Kf, 0, nullptr, 0, nullptr, 0};
   return run(static_cast<hipStream_t>(stream), A, B, true, true, P, (int)Kf, R, ep, ws, ws_bytes);
 }
 
@@ -1095,7 +1156,7 @@ extern "C" int mpt_conv3x3_dgrad(void* stream, int64_t Nb, int64_t H, int64_t W,
   const int P = (int)(Nb * H * W), R = (int)(9 * Kf);
   ImgRC A{dy, (int)H, (int)W, (int)Kf, P, R, -1, FastDiv((uint32_t)(H * W)), FastDiv((uint32_t)W), FastDiv((uint32_t)Kf)};
   FilterOC B{w, (int)C, (int)Kf, (int)C, R, FastDiv((uint32_t)Kf)};
-  Epilogue ep{dx, C, 0, nullptr};
+  Epilogue ep{dx, C, 0, nullptr, 0, nullptr, 0};
   return run(static_cast<hipStream_t>(stream), A, B, true, true, P, (int)C, R, ep, ws, ws_bytes);
 }
 
@@ -1109,6 +1170,6 @@ extern "C" int mpt_conv3x3_wgrad(void* stream, int64_t Nb, int64_t H, int64_t W,
   const int P = (int)(Nb * H * W), J = (int)(9 * C);
   MatOC A{dy, Kf, (int)Kf, P};
   ImgOC B{x, (int)H, (int)W, (int)C, J, P, FastDiv((uint32_t)(H * W)), FastDiv((uint32_t)W), FastDiv((uint32_t)C)};
-  Epilogue ep{dw, J, 0, flag};
+  Epilogue ep{dw, J, 0, flag, 0, nullptr, 0};
   return run(static_cast<hipStream_t>(stream), A, B, true, true, (int)Kf, J, P, ep, ws, ws_bytes);
 }

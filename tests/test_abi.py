@@ -82,6 +82,23 @@ def test_argument_errors_before_any_launch(L):
     assert L.mpt_conv3x3_fwd(Z, 1, 4, 4, 12, 8, P, P, P, Z, 0) == -2               # C % 8 != 0
     assert L.mpt_conv3x3_dgrad(Z, 1, 4, 4, 8, 8, P, Z, P, Z, 0) == -1
     assert L.mpt_conv3x3_wgrad(Z, 1, 4, 4, 8, 8, P, P, odd, Z, Z, 0) == -3
+    assert L.mpt_gemm_fwd_relu(Z, 8, 8, 8, P, 8, P, 8, Z, 8, Z, 0) == -1
+    assert L.mpt_gemm_dgrad_relu(Z, 8, 8, 8, P, 8, P, 8, Z, 8, P, 8, Z, 0) == -1       # the mask is required
+    assert L.mpt_gemm_dgrad_relu(Z, 8, 8, 8, P, 8, P, 8, P, 7, P, 8, Z, 0) == -2       # mask row stride below K
+    assert L.mpt_gemm_dgrad_relu(Z, 8, 8, 8, P, 8, P, 8, odd, 8, P, 8, Z, 0) == -3
+    need = L.mpt_bn_workspace_bytes(1000, 64)
+    assert need > 0 and L.mpt_bn_workspace_bytes(0, 64) == 0
+    assert L.mpt_bn_stats(Z, 1000, 64, P, 64, P, P, Z, 0) == -1                        # the reductions need their scratch
+    assert L.mpt_bn_stats(Z, 1000, 64, P, 63, P, P, P, need) == -2
+    assert L.mpt_bn_stats(Z, 1000, 64, P, 64, P, P, P, need - 1) == -4
+    assert L.mpt_bn_stats(Z, 1000, 64, odd, 64, P, P, P, need) == -3
+    assert L.mpt_bn_apply(Z, 1000, 64, P, 64, P, P, P, P, -1.0, 0, P, 64) == -5
+    assert L.mpt_bn_apply(Z, 1000, 64, P, 64, P, P, P, Z, 1e-5, 0, P, 64) == -1
+    assert L.mpt_bn_apply(Z, 1000, 64, P, 64, P, P, P, P, 1e-5, 0, P, 8) == -2
+    assert L.mpt_bn_bwd_reduce(Z, 1000, 64, P, 64, P, 64, P, P, 1e-5, P, P, P, need - 8) == -4
+    assert L.mpt_bn_bwd_reduce(Z, 1000, 64, P, 64, Z, 64, P, P, 1e-5, P, P, P, need) == -1
+    assert L.mpt_bn_bwd_apply(Z, 1000, 64, P, 64, P, 64, P, P, P, float("nan"), P, P, P, 64) == -5
+    assert L.mpt_bn_bwd_apply(Z, 1000, 0, P, 64, P, 64, P, P, P, 1e-5, P, P, P, 64) == -2
     assert L.mpt_unscale_check(Z, Z, 0, 8, 1.0, Z, P) == -1
     assert L.mpt_unscale_check(Z, P, 0, 8, 0.0, Z, P) == -5
     assert L.mpt_unscale_check(Z, P, 0, 8, float("inf"), Z, P) == -5

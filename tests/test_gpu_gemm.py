@@ -210,3 +210,52 @@ def test_cfg2_square_4096(scale):
     flushed = float((c["g_true"] != 0)[(gb & 0x7FFF) == 0].mean()) if ((gb & 0x7FFF) == 0).any() else 0.0
     print("[cfg2] S=%g: upstream gradient flushed to zero %.3f, subnormal %.3f" %
           (scale, float(((gb & 0x7FFF) == 0).mean()), float((((gb & 0x7C00) == 0) & ((gb & 0x3FF) != 0)).mean())), flush=True)
+
+
+@pytest.mark.parametrize("M,N,K", [(130, 72, 200), (257, 129, 65), (256, 1024, 1024), (512, 384, 1024)])
+@pytest.mark.parametrize("split", [False, True])
+def test_relu_folded_into_the_stores(M, N, K, split):
+    rng = np.random.default_rng(M + N + K)
+    X = rng.standard_normal((M, K)).astype(np.float16)
+    W = (rng.standard_normal((K, N)) * 0.05).astype(np.float16)
+    H = torch.full((M, N), float("nan"), dtype=torch.float16, device="cuda")
+    mpt.mpt_gemm_fwd_relu(dev16(X), dev16(W), H, _ws(0, M, N, K) if split else None)
+    h, sa, s = gemm.gemm_fwd_relu(X, W, full=True)
+    got = host16(H)
+    gemm_check(got, h, sa, s, "fwd_relu")
+    y, _, s_raw = gemm.gemm_fwd(X, W, full=True)
+    clear = np.abs(s_raw) > 8 * 2.0 ** -24 * sa                     # away from the sign boundary the zero pattern is fixed
+    assert np.array_equal((got == 0)[clear], (s_raw <= 0)[clear]) and not np.signbit(got).any()
+    # backward: mask by the stored activation of the layer below
+    dY = (np.exp2(rng.uniform(-20, -3, (M, N))) * rng.choice([-1, 1], (M, N))).astype(np.float16)
+    Hb = np.maximum(rng.standard_normal((M, K)), 0).astype(np.float16)
+    dX = torch.full((M, K), float("nan"), dtype=torch.float16, device="cuda")
+    mpt.mpt_gemm_dgrad_relu(dev16(dY), dev16(W), dev16(Hb), dX, _ws(1, M, N, K) if split else None)
+    dx, sa, s = gemm.gemm_dgrad_relu(dY, W, Hb, full=True)
+    got = host16(dX)
+    gemm_check(got, dx, sa, s, "dgrad_relu")
+    assert not got[Hb <= 0].any() and not np.signbit(got[Hb <= 0]).any()
+
+
+def test_relu_folded_whole_tile_kernels():
+    """Shapes that take the whole-tile streamed kernels (aligned and odd-stride outputs and masks)."""
+    M, N, K = 4352, 4096, 128
+    rng = np.random.default_rng(3)
+    X = rng.standard_normal((M, K)).astype(np.float16)
+    W = (rng.standard_normal((K, N)) * 0.05).astype(np.float16)
+    h, sa, s = gemm.gemm_fwd_relu(X, W, full=True)
+    for pad in (0, 4):
+        Hb = torch.full((M, N + pad), 7.0, dtype=torch.float16, device="cuda")
+        mpt.mpt_gemm_fwd_relu(dev16(X), dev16(W), Hb[:, :N])
+        gemm_check(np.ascontiguousarray(host16(Hb)[:, :N]), h, sa, s, "fwd_relu pad %d" % pad)
+    dY = (np.exp2(rng.uniform(-20, -3, (M, K))) * rng.choice([-1, 1], (M, K))).astype(np.float16)   # reduce over K=128
+    Wd = (rng.standard_normal((N, K)) * 0.05).astype(np.float16)                                      # output M x N
+    mask = np.maximum(rng.standard_normal((M, N)), 0).astype(np.float16)
+    dx, sa, s = gemm.gemm_dgrad_relu(dY, Wd, mask, full=True)
+    for pad in (0, 4):
+        mb = torch.zeros((M, N + pad), dtype=torch.float16, device="cuda"); mb[:, :N] = dev16(mask)
+        dX = torch.full((M, N), float("nan"), dtype=torch.float16, device="cuda")
+        mpt.mpt_gemm_dgrad_relu(dev16(dY), dev16(Wd), mb[:, :N], dX)
+        got = host16(dX)
+        gemm_check(got, dx, sa, s, "dgrad_relu mask pad %d" % pad)
+        assert not got[mask <= 0].any()
