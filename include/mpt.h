@@ -238,7 +238,7 @@ int mpt_softmax_xent_scaled(void* stream, int64_t B, int64_t C,
  * row strides multiples of 8; anything else takes a scalar path with the same
  * results.  ws_dev: caller scratch of at least mpt_bn_workspace_bytes(P, C)
  * bytes, 16-byte aligned (FP64 partial sums), required by the two reductions.
- * Errors (nothing enqueued): NULL, SHAPE (P or C < 1, stride < C), ALIGN,
+ * Errors (nothing enqueued): NULL, SHAPE (P < 1 or >= 2^40, C < 1 or > 2^21, stride < C), ALIGN,
  * WORKSPACE, ARG (eps negative or not finite).
  * ------------------------------------------------------------------------- */
 size_t mpt_bn_workspace_bytes(int64_t P, int64_t C);

@@ -16,51 +16,62 @@ namespace {
 
 constexpr int kBlock = 256;
 constexpr int kChain = 16;        // rows summed in FP32 before folding into FP64
-constexpr int kMaxBlocks = 2048;
+constexpr int kMaxBlocks = 1024;
 
 struct BnShape {
   int64_t P;
   int C;
-  int cg;          // channel groups (threads along a row): ceil(C / V)
+  int cg;          // channel groups: ceil(C / V)
+  int tpr;         // threads of a workgroup along a row (each owns one channel group)
   int slots;       // rows a workgroup visits at once
-  int cgy;         // channel-group blocks (grid.y)
+  int cgy;         // workgroups along the channels (grid.y)
   int nblk;        // row blocks (grid.x)
   int64_t rows_per_block;
 };
 
+// A workgroup is tpr channel groups wide (at most a wavefront in the reductions, so that several rows are visited at
+// once whatever C is; up to the whole workgroup in the pointwise passes, whose stores like whole rows) and `slots` rows tall; wider tensors take more workgroups along the channels.  The reductions keep the grid
+// near 1024 workgroups so that the FP64 partial buffer stays a few percent of the tensor.
 template <int V>
-BnShape bn_shape(int64_t P, int64_t C) {
+BnShape bn_shape(int64_t P, int64_t C, int rows_per_thread, int max_blocks, int max_tpr) {
   BnShape s;
   s.P = P; s.C = (int)C;
   s.cg = (int)((C + V - 1) / V);
-  if (s.cg <= kBlock) { s.slots = kBlock / s.cg; s.cgy = 1; }
-  else { s.slots = 1; s.cgy = (s.cg + kBlock - 1) / kBlock; }
-  int64_t nb = (P + (int64_t)s.slots * kChain - 1) / ((int64_t)s.slots * kChain);
-  if (nb > kMaxBlocks) nb = kMaxBlocks;
+  s.tpr = s.cg < max_tpr ? s.cg : max_tpr;
+  s.slots = kBlock / s.tpr;
+  s.cgy = (s.cg + s.tpr - 1) / s.tpr;
+  int64_t nb = (P + (int64_t)s.slots * rows_per_thread - 1) / ((int64_t)s.slots * rows_per_thread);
+  int64_t cap = max_blocks / s.cgy;
+  if (cap < 1) cap = 1;
+  if (nb > cap) nb = cap;
   if (nb < 1) nb = 1;
   s.rows_per_block = (P + nb - 1) / nb;
   s.nblk = (int)((P + s.rows_per_block - 1) / s.rows_per_block);
   return s;
 }
+template <int V> BnShape bn_shape(int64_t P, int64_t C) { return bn_shape<V>(P, C, kChain, kMaxBlocks, 64); }
 
 // V channels of one row as floats; channels at or beyond C read as 0.
-template <int V>
+template <int V, bool NT>
 __device__ __forceinline__ void load_row(const uint16_t* __restrict__ base, int64_t ld, int64_t p, int c0, int C, float (&v)[V]) {
   if constexpr (V == 8) {
-    const h8v h = *reinterpret_cast<const h8v*>(base + p * ld + c0);
+    const h8v* q = reinterpret_cast<const h8v*>(base + p * ld + c0);
+    const h8v h = NT ? __builtin_nontemporal_load(q) : *q;
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] = (float)h[e];
   } else {
     v[0] = c0 < C ? (float)reinterpret_cast<const _Float16*>(base)[p * ld + c0] : 0.f;
   }
 }
-template <int V>
+template <int V, bool NT>
 __device__ __forceinline__ void store_row(uint16_t* __restrict__ base, int64_t ld, int64_t p, int c0, int C, const float (&v)[V]) {
   if constexpr (V == 8) {
     h8v h;
 #pragma unroll
     for (int e = 0; e < 8; ++e) h[e] = (_Float16)mpt_rounded_f32(v[e]);
-    *reinterpret_cast<h8v*>(base + p * ld + c0) = h;
+    h8v* q = reinterpret_cast<h8v*>(base + p * ld + c0);
+    if (NT) __builtin_nontemporal_store(h, q);
+    else *q = h;
   } else {
     if (c0 < C) reinterpret_cast<_Float16*>(base)[p * ld + c0] = (_Float16)mpt_rounded_f32(v[0]);
   }
@@ -68,14 +79,15 @@ __device__ __forceinline__ void store_row(uint16_t* __restrict__ base, int64_t l
 
 // thread -> (row slot, channel group); returns false for idle threads
 __device__ __forceinline__ bool bn_thread(const BnShape& s, int& slot, int& cgi) {
-  if (s.cgy == 1) { slot = threadIdx.x / s.cg; cgi = threadIdx.x - slot * s.cg; return slot < s.slots; }
-  slot = 0; cgi = blockIdx.y * kBlock + threadIdx.x; return cgi < s.cg;
+  slot = threadIdx.x / s.tpr;
+  cgi = blockIdx.y * s.tpr + (threadIdx.x - slot * s.tpr);
+  return slot < s.slots && cgi < s.cg;
 }
 
 // MODE 0: S1 = sum (x - k), S2 = sum (x - k)^2 with k = x[0, c].
 // MODE 1: S1 = sum dy, S2 = sum dy * ((x - mean) * invstd), each factor rounded to FP32 on its own.
 // part[blk][2][C] in FP64.
-template <int V, int MODE>
+template <int V, int MODE, bool NT>
 __global__ __launch_bounds__(kBlock) void k_bn_partial(BnShape s, const uint16_t* __restrict__ x, int64_t ldx,
                                                        const uint16_t* __restrict__ dy, int64_t lddy,
                                                        const float* __restrict__ mean, const float* __restrict__ var, float eps,
@@ -90,7 +102,7 @@ __global__ __launch_bounds__(kBlock) void k_bn_partial(BnShape s, const uint16_t
   if (active) {
     float k[V], istd[V];
     if constexpr (MODE == 0) {
-      load_row<V>(x, ldx, 0, c0, s.C, k);
+      load_row<V, false>(x, ldx, 0, c0, s.C, k);
     } else {
 #pragma unroll
       for (int e = 0; e < V; ++e) {
@@ -101,32 +113,49 @@ __global__ __launch_bounds__(kBlock) void k_bn_partial(BnShape s, const uint16_t
     }
     const int64_t r0 = (int64_t)blockIdx.x * s.rows_per_block;
     const int64_t r1 = min(r0 + s.rows_per_block, s.P);
+    auto add_row = [&](const float (&xv)[V], const float (&gv)[V], float (&c1)[V], float (&c2)[V]) {
+      if constexpr (MODE == 0) {
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+          const float d = __fsub_rn(xv[e], k[e]);
+          c1[e] = __fadd_rn(c1[e], d);
+          c2[e] = __fadd_rn(c2[e], __fmul_rn(d, d));
+        }
+      } else {
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+          const float xh = __fmul_rn(__fsub_rn(xv[e], k[e]), istd[e]);
+          c1[e] = __fadd_rn(c1[e], gv[e]);
+          c2[e] = __fadd_rn(c2[e], __fmul_rn(gv[e], xh));
+        }
+      }
+    };
     for (int64_t pb = r0 + slot; pb < r1; pb += (int64_t)s.slots * kChain) {
       float c1[V], c2[V];
 #pragma unroll
       for (int e = 0; e < V; ++e) c1[e] = c2[e] = 0.f;
-#pragma unroll 4
-      for (int i = 0; i < kChain; ++i) {
-        const int64_t p = pb + (int64_t)i * s.slots;
-        if (p >= r1) break;
-        float xv[V];
-        load_row<V>(x, ldx, p, c0, s.C, xv);
-        if constexpr (MODE == 0) {
+      if (pb + (int64_t)(kChain - 1) * s.slots < r1) {
+        // whole chain: rows are fetched four at a time ahead of the arithmetic, added in row order
 #pragma unroll
-          for (int e = 0; e < V; ++e) {
-            const float d = __fsub_rn(xv[e], k[e]);
-            c1[e] = __fadd_rn(c1[e], d);
-            c2[e] = __fadd_rn(c2[e], __fmul_rn(d, d));
-          }
-        } else {
-          float gv[V];
-          load_row<V>(dy, lddy, p, c0, s.C, gv);
+        for (int i0 = 0; i0 < kChain; i0 += 4) {
+          float xv[4][V], gv[4][V];
 #pragma unroll
-          for (int e = 0; e < V; ++e) {
-            const float xh = __fmul_rn(__fsub_rn(xv[e], k[e]), istd[e]);
-            c1[e] = __fadd_rn(c1[e], gv[e]);
-            c2[e] = __fadd_rn(c2[e], __fmul_rn(gv[e], xh));
+          for (int i = 0; i < 4; ++i) {
+            const int64_t p = pb + (int64_t)(i0 + i) * s.slots;
+            load_row<V, NT>(x, ldx, p, c0, s.C, xv[i]);
+            if constexpr (MODE == 1) load_row<V, NT>(dy, lddy, p, c0, s.C, gv[i]);
           }
+#pragma unroll
+          for (int i = 0; i < 4; ++i) add_row(xv[i], gv[i], c1, c2);
+        }
+      } else {
+        for (int i = 0; i < kChain; ++i) {
+          const int64_t p = pb + (int64_t)i * s.slots;
+          if (p >= r1) break;
+          float xv[V], gv[V];
+          load_row<V, NT>(x, ldx, p, c0, s.C, xv);
+          if constexpr (MODE == 1) load_row<V, NT>(dy, lddy, p, c0, s.C, gv);
+          add_row(xv, gv, c1, c2);
         }
       }
 #pragma unroll
@@ -144,7 +173,7 @@ __global__ __launch_bounds__(kBlock) void k_bn_partial(BnShape s, const uint16_t
       if (c >= s.C) continue;
       double t1 = 0.0, t2 = 0.0;
       for (int q = 0; q < s.slots; ++q) {
-        const int th = (s.cgy == 1) ? q * s.cg + cgi : threadIdx.x;
+        const int th = q * s.tpr + (threadIdx.x % s.tpr);
         t1 += red[0][th * V + e];
         t2 += red[1][th * V + e];
       }
@@ -154,17 +183,30 @@ __global__ __launch_bounds__(kBlock) void k_bn_partial(BnShape s, const uint16_t
   }
 }
 
-// One thread per channel: partials in block order, then the closing arithmetic in FP64, one rounding to FP32.
+// 16 channels per workgroup; 16 thread groups each sum a contiguous range of row blocks in block order, the 16
+// results are added in group order; then the closing arithmetic in FP64 and one rounding to FP32.
 template <int MODE>
-__global__ __launch_bounds__(64) void k_bn_finalize(BnShape s, const double* __restrict__ part, const uint16_t* __restrict__ x,
-                                                    float* __restrict__ out1, float* __restrict__ out2) {
-  const int c = blockIdx.x * 64 + threadIdx.x;
-  if (c >= s.C) return;
+__global__ __launch_bounds__(256) void k_bn_finalize(BnShape s, const double* __restrict__ part, const uint16_t* __restrict__ x,
+                                                     float* __restrict__ out1, float* __restrict__ out2) {
+  __shared__ double red[2][16][16];
+  const int cl = threadIdx.x & 15, grp = threadIdx.x >> 4;
+  const int c = blockIdx.x * 16 + cl;
+  const int per = (s.nblk + 15) / 16;
+  const int b0 = grp * per, b1 = min(b0 + per, s.nblk);
   double t1 = 0.0, t2 = 0.0;
-  for (int b = 0; b < s.nblk; ++b) {
-    t1 += part[((int64_t)b * 2 + 0) * s.C + c];
-    t2 += part[((int64_t)b * 2 + 1) * s.C + c];
+  if (c < s.C) {
+#pragma unroll 8
+    for (int b = b0; b < b1; ++b) {
+      t1 += part[((int64_t)b * 2 + 0) * s.C + c];
+      t2 += part[((int64_t)b * 2 + 1) * s.C + c];
+    }
   }
+  red[0][grp][cl] = t1;
+  red[1][grp][cl] = t2;
+  __syncthreads();
+  if (grp != 0 || c >= s.C) return;
+  t1 = t2 = 0.0;
+  for (int g = 0; g < 16; ++g) { t1 += red[0][g][cl]; t2 += red[1][g][cl]; }
   if constexpr (MODE == 0) {
     const double k = (double)(float)reinterpret_cast<const _Float16*>(x)[c];
     const double d1 = t1 / (double)s.P;
@@ -178,97 +220,140 @@ __global__ __launch_bounds__(64) void k_bn_finalize(BnShape s, const double* __r
   }
 }
 
-// y = rne16(x * scale + shift), scale = gamma * (1 / sqrt(var + eps)), shift = beta - mean * scale; optional ReLU.
+// Per-channel constants of a pointwise pass are formed once per workgroup (square root and divisions are tens of
+// instructions each) and handed to the row walkers through LDS.  Returns the first channel the workgroup covers
+// and how many it covers.
 template <int V>
+__device__ __forceinline__ int bn_covered(const BnShape& s, int& count) {
+  const int cbase = blockIdx.y * s.tpr * V;
+  count = min(s.C - cbase, s.tpr * V);
+  return cbase;
+}
+
+// y = rne16(x * scale + shift), scale = gamma * (1 / sqrt(var + eps)), shift = beta - mean * scale; optional ReLU.
+template <int V, bool NT>
 __global__ __launch_bounds__(kBlock) void k_bn_apply(BnShape s, const uint16_t* __restrict__ x, int64_t ldx,
                                                      const float* __restrict__ mean, const float* __restrict__ var,
                                                      const float* __restrict__ gamma, const float* __restrict__ beta, float eps, int relu,
                                                      uint16_t* __restrict__ y, int64_t ldy) {
+  __shared__ float cst[2][kBlock * V];
+  int count;
+  const int cbase = bn_covered<V>(s, count);
+  for (int j = threadIdx.x; j < count; j += kBlock) {
+    const int c = cbase + j;
+    const float sc = __fmul_rn(gamma[c], div_rn(1.0f, sqrt_rn(__fadd_rn(var[c], eps))));
+    cst[0][j] = sc;
+    cst[1][j] = __fsub_rn(beta[c], __fmul_rn(mean[c], sc));
+  }
+  __syncthreads();
   int slot, cgi;
   if (!bn_thread(s, slot, cgi)) return;
   const int c0 = cgi * V;
   float scale[V], shift[V];
 #pragma unroll
   for (int e = 0; e < V; ++e) {
-    const int c = c0 + e;
-    if (c < s.C) {
-      scale[e] = __fmul_rn(gamma[c], div_rn(1.0f, sqrt_rn(__fadd_rn(var[c], eps))));
-      shift[e] = __fsub_rn(beta[c], __fmul_rn(mean[c], scale[e]));
-    } else {
-      scale[e] = shift[e] = 0.f;
-    }
+    const int j = c0 - cbase + e;
+    scale[e] = j < count ? cst[0][j] : 0.f;
+    shift[e] = j < count ? cst[1][j] : 0.f;
   }
   const int64_t r0 = (int64_t)blockIdx.x * s.rows_per_block;
   const int64_t r1 = min(r0 + s.rows_per_block, s.P);
-#pragma unroll 4
-  for (int64_t p = r0 + slot; p < r1; p += s.slots) {
-    float v[V];
-    load_row<V>(x, ldx, p, c0, s.C, v);
+  auto one = [&](float (&v)[V]) {
 #pragma unroll
     for (int e = 0; e < V; ++e) {
       v[e] = __fadd_rn(__fmul_rn(v[e], scale[e]), shift[e]);
       if (relu) v[e] = v[e] > 0.f ? v[e] : 0.f;
     }
-    store_row<V>(y, ldy, p, c0, s.C, v);
+  };
+  int64_t p = r0 + slot;
+  for (; p + 3 * (int64_t)s.slots < r1; p += 4 * (int64_t)s.slots) {      // four rows in flight
+    float v[4][V];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) load_row<V, NT>(x, ldx, p + (int64_t)i * s.slots, c0, s.C, v[i]);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { one(v[i]); store_row<V, NT>(y, ldy, p + (int64_t)i * s.slots, c0, s.C, v[i]); }
+  }
+  for (; p < r1; p += s.slots) {
+    float v[V];
+    load_row<V, NT>(x, ldx, p, c0, s.C, v);
+    one(v);
+    store_row<V, NT>(y, ldy, p, c0, s.C, v);
   }
 }
 
 // dx = rne16( a * ((dy - b) - xhat * g) ), a = gamma * invstd, b = dbeta / P, g = dgamma / P, xhat = (x - mean) * invstd.
-template <int V>
+template <int V, bool NT>
 __global__ __launch_bounds__(kBlock) void k_bn_bwd_apply(BnShape s, const uint16_t* __restrict__ x, int64_t ldx,
                                                          const uint16_t* __restrict__ dy, int64_t lddy,
                                                          const float* __restrict__ mean, const float* __restrict__ var,
                                                          const float* __restrict__ gamma, float eps,
                                                          const float* __restrict__ dgamma, const float* __restrict__ dbeta,
                                                          uint16_t* __restrict__ dx, int64_t lddx) {
+  __shared__ float cst[5][kBlock * V];
+  int count;
+  const int cbase = bn_covered<V>(s, count);
+  const float Pf = (float)s.P;
+  for (int j = threadIdx.x; j < count; j += kBlock) {
+    const int c = cbase + j;
+    const float is = div_rn(1.0f, sqrt_rn(__fadd_rn(var[c], eps)));
+    cst[0][j] = mean[c];
+    cst[1][j] = is;
+    cst[2][j] = __fmul_rn(gamma[c], is);
+    cst[3][j] = div_rn(dbeta[c], Pf);
+    cst[4][j] = div_rn(dgamma[c], Pf);
+  }
+  __syncthreads();
   int slot, cgi;
   if (!bn_thread(s, slot, cgi)) return;
   const int c0 = cgi * V;
   float mu[V], istd[V], a[V], b[V], g[V];
-  const float Pf = (float)s.P;
 #pragma unroll
   for (int e = 0; e < V; ++e) {
-    const int c = c0 + e;
-    if (c < s.C) {
-      mu[e] = mean[c];
-      istd[e] = div_rn(1.0f, sqrt_rn(__fadd_rn(var[c], eps)));
-      a[e] = __fmul_rn(gamma[c], istd[e]);
-      b[e] = div_rn(dbeta[c], Pf);
-      g[e] = div_rn(dgamma[c], Pf);
-    } else {
-      mu[e] = istd[e] = a[e] = b[e] = g[e] = 0.f;
-    }
+    const int j = c0 - cbase + e;
+    const bool in = j < count;
+    mu[e] = in ? cst[0][j] : 0.f;
+    istd[e] = in ? cst[1][j] : 0.f;
+    a[e] = in ? cst[2][j] : 0.f;
+    b[e] = in ? cst[3][j] : 0.f;
+    g[e] = in ? cst[4][j] : 0.f;
   }
   const int64_t r0 = (int64_t)blockIdx.x * s.rows_per_block;
   const int64_t r1 = min(r0 + s.rows_per_block, s.P);
-#pragma unroll 2
-  for (int64_t p = r0 + slot; p < r1; p += s.slots) {
-    float xv[V], gv[V];
-    load_row<V>(x, ldx, p, c0, s.C, xv);
-    load_row<V>(dy, lddy, p, c0, s.C, gv);
+  auto one = [&](float (&xv)[V], const float (&gv)[V]) {
 #pragma unroll
     for (int e = 0; e < V; ++e) {
       const float xh = __fmul_rn(__fsub_rn(xv[e], mu[e]), istd[e]);
       const float t = __fsub_rn(__fsub_rn(gv[e], b[e]), __fmul_rn(xh, g[e]));
       xv[e] = __fmul_rn(a[e], t);
     }
-    store_row<V>(dx, lddx, p, c0, s.C, xv);
+  };
+  int64_t p = r0 + slot;
+  for (; p + (int64_t)s.slots < r1; p += 2 * (int64_t)s.slots) {          // two rows of both tensors in flight
+    float xv[2][V], gv[2][V];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      load_row<V, NT>(x, ldx, p + (int64_t)i * s.slots, c0, s.C, xv[i]);
+      load_row<V, NT>(dy, lddy, p + (int64_t)i * s.slots, c0, s.C, gv[i]);
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i) { one(xv[i], gv[i]); store_row<V, NT>(dx, lddx, p + (int64_t)i * s.slots, c0, s.C, xv[i]); }
+  }
+  for (; p < r1; p += s.slots) {
+    float xv[V], gv[V];
+    load_row<V, NT>(x, ldx, p, c0, s.C, xv);
+    load_row<V, NT>(dy, lddy, p, c0, s.C, gv);
+    one(xv, gv);
+    store_row<V, NT>(dx, lddx, p, c0, s.C, xv);
   }
 }
 
-bool bn_dims_ok(int64_t P, int64_t C) { return P >= 1 && C >= 1 && P < (1LL << 40) && C <= (1 << 24); }
+bool bn_dims_ok(int64_t P, int64_t C) { return P >= 1 && C >= 1 && P < (1LL << 40) && C <= (1 << 21); }
+// Tensors beyond the memory-side cache are streamed with nontemporal accesses (about 8 % faster there); smaller ones
+// are left cacheable, since their producer or consumer is likely to find them on chip (nontemporal costs 15 % there).
+bool bn_stream(int64_t P, int64_t C) { return P * C * 2 > (192LL << 20); }
 bool bn_vec(const void* p, int64_t ld, int64_t C) { return mpt_aligned(p, 16) && (ld % 8) == 0 && (C % 8) == 0; }
-// the pointwise passes need no partial buffer and may use more, shorter row blocks
-template <int V>
-BnShape bn_shape_pointwise(int64_t P, int64_t C) {
-  BnShape s = bn_shape<V>(P, C);
-  int64_t nb = (P + (int64_t)s.slots * 4 - 1) / ((int64_t)s.slots * 4);      // about 4 rows per thread
-  if (nb > 65535) nb = 65535;
-  if (nb < 1) nb = 1;
-  s.rows_per_block = (P + nb - 1) / nb;
-  s.nblk = (int)((P + s.rows_per_block - 1) / s.rows_per_block);
-  return s;
-}
+// the pointwise passes need no partial buffer and may use more, shorter row blocks (about 16 rows per thread)
+template <int V> BnShape bn_shape_pointwise(int64_t P, int64_t C) { return bn_shape<V>(P, C, 16, 1 << 20, kBlock); }
 
 }  // namespace
 
@@ -290,14 +375,16 @@ extern "C" int mpt_bn_stats(void* stream, int64_t P, int64_t C, const uint16_t* 
   double* part = reinterpret_cast<double*>(ws);
   if (bn_vec(x, ldx, C)) {
     const BnShape s = bn_shape<8>(P, C);
-    hipLaunchKernelGGL((k_bn_partial<8, 0>), dim3(s.nblk, s.cgy), dim3(kBlock), 0, st, s, x, ldx, nullptr, 0, nullptr, nullptr, 0.f, part);
+    if (bn_stream(P, C)) hipLaunchKernelGGL((k_bn_partial<8, 0, true>), dim3(s.nblk, s.cgy), dim3(kBlock), 0, st, s, x, ldx, nullptr, 0, nullptr, nullptr, 0.f, part);
+    else hipLaunchKernelGGL((k_bn_partial<8, 0, false>), dim3(s.nblk, s.cgy), dim3(kBlock), 0, st, s, x, ldx, nullptr, 0, nullptr, nullptr, 0.f, part);
     MPT_LAUNCH_CHECK();
-    hipLaunchKernelGGL((k_bn_finalize<0>), dim3((s.C + 63) / 64), dim3(64), 0, st, s, part, x, mean, var);
+    hipLaunchKernelGGL((k_bn_finalize<0>), dim3((s.C + 15) / 16), dim3(256), 0, st, s, part, x, mean, var);
   } else {
     const BnShape s = bn_shape<1>(P, C);
-    hipLaunchKernelGGL((k_bn_partial<1, 0>), dim3(s.nblk, s.cgy), dim3(kBlock), 0, st, s, x, ldx, nullptr, 0, nullptr, nullptr, 0.f, part);
+    if (bn_stream(P, C)) hipLaunchKernelGGL((k_bn_partial<1, 0, true>), dim3(s.nblk, s.cgy), dim3(kBlock), 0, st, s, x, ldx, nullptr, 0, nullptr, nullptr, 0.f, part);
+    else hipLaunchKernelGGL((k_bn_partial<1, 0, false>), dim3(s.nblk, s.cgy), dim3(kBlock), 0, st, s, x, ldx, nullptr, 0, nullptr, nullptr, 0.f, part);
     MPT_LAUNCH_CHECK();
-    hipLaunchKernelGGL((k_bn_finalize<0>), dim3((s.C + 63) / 64), dim3(64), 0, st, s, part, x, mean, var);
+    hipLaunchKernelGGL((k_bn_finalize<0>), dim3((s.C + 15) / 16), dim3(256), 0, st, s, part, x, mean, var);
   }
   MPT_LAUNCH_CHECK();
   return MPT_OK;
@@ -313,10 +400,12 @@ extern "C" int mpt_bn_apply(void* stream, int64_t P, int64_t C, const uint16_t* 
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (bn_vec(x, ldx, C) && bn_vec(y, ldy, C)) {
     const BnShape s = bn_shape_pointwise<8>(P, C);
-    hipLaunchKernelGGL((k_bn_apply<8>), dim3(s.nblk, s.cgy), dim3(kBlock), 0, st, s, x, ldx, mean, var, gamma, beta, eps, relu, y, ldy);
+    if (bn_stream(P, C)) hipLaunchKernelGGL((k_bn_apply<8, true>), dim3(s.nblk, s.cgy), dim3(kBlock), 0, st, s, x, ldx, mean, var, gamma, beta, eps, relu, y, ldy);
+    else hipLaunchKernelGGL((k_bn_apply<8, false>), dim3(s.nblk, s.cgy), dim3(kBlock), 0, st, s, x, ldx, mean, var, gamma, beta, eps, relu, y, ldy);
   } else {
     const BnShape s = bn_shape_pointwise<1>(P, C);
-    hipLaunchKernelGGL((k_bn_apply<1>), dim3(s.nblk, s.cgy), dim3(kBlock), 0, st, s, x, ldx, mean, var, gamma, beta, eps, relu, y, ldy);
+    if (bn_stream(P, C)) hipLaunchKernelGGL((k_bn_apply<1, true>), dim3(s.nblk, s.cgy), dim3(kBlock), 0, st, s, x, ldx, mean, var, gamma, beta, eps, relu, y, ldy);
+    else hipLaunchKernelGGL((k_bn_apply<1, false>), dim3(s.nblk, s.cgy), dim3(kBlock), 0, st, s, x, ldx, mean, var, gamma, beta, eps, relu, y, ldy);
   }
   MPT_LAUNCH_CHECK();
   return MPT_OK;
@@ -336,14 +425,16 @@ extern "C" int mpt_bn_bwd_reduce(void* stream, int64_t P, int64_t C, const uint1
   double* part = reinterpret_cast<double*>(ws);
   if (bn_vec(x, ldx, C) && bn_vec(dy, lddy, C)) {
     const BnShape s = bn_shape<8>(P, C);
-    hipLaunchKernelGGL((k_bn_partial<8, 1>), dim3(s.nblk, s.cgy), dim3(kBlock), 0, st, s, x, ldx, dy, lddy, mean, var, eps, part);
+    if (bn_stream(P, C)) hipLaunchKernelGGL((k_bn_partial<8, 1, true>), dim3(s.nblk, s.cgy), dim3(kBlock), 0, st, s, x, ldx, dy, lddy, mean, var, eps, part);
+    else hipLaunchKernelGGL((k_bn_partial<8, 1, false>), dim3(s.nblk, s.cgy), dim3(kBlock), 0, st, s, x, ldx, dy, lddy, mean, var, eps, part);
     MPT_LAUNCH_CHECK();
-    hipLaunchKernelGGL((k_bn_finalize<1>), dim3((s.C + 63) / 64), dim3(64), 0, st, s, part, x, dgamma, dbeta);
+    hipLaunchKernelGGL((k_bn_finalize<1>), dim3((s.C + 15) / 16), dim3(256), 0, st, s, part, x, dgamma, dbeta);
   } else {
     const BnShape s = bn_shape<1>(P, C);
-    hipLaunchKernelGGL((k_bn_partial<1, 1>), dim3(s.nblk, s.cgy), dim3(kBlock), 0, st, s, x, ldx, dy, lddy, mean, var, eps, part);
+    if (bn_stream(P, C)) hipLaunchKernelGGL((k_bn_partial<1, 1, true>), dim3(s.nblk, s.cgy), dim3(kBlock), 0, st, s, x, ldx, dy, lddy, mean, var, eps, part);
+    else hipLaunchKernelGGL((k_bn_partial<1, 1, false>), dim3(s.nblk, s.cgy), dim3(kBlock), 0, st, s, x, ldx, dy, lddy, mean, var, eps, part);
     MPT_LAUNCH_CHECK();
-    hipLaunchKernelGGL((k_bn_finalize<1>), dim3((s.C + 63) / 64), dim3(64), 0, st, s, part, x, dgamma, dbeta);
+    hipLaunchKernelGGL((k_bn_finalize<1>), dim3((s.C + 15) / 16), dim3(256), 0, st, s, part, x, dgamma, dbeta);
   }
   MPT_LAUNCH_CHECK();
   return MPT_OK;
@@ -363,10 +454,12 @@ extern "C" int mpt_bn_bwd_apply(void* stream, int64_t P, int64_t C, const uint16
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (bn_vec(x, ldx, C) && bn_vec(dy, lddy, C) && bn_vec(dx, lddx, C)) {
     const BnShape s = bn_shape_pointwise<8>(P, C);
-    hipLaunchKernelGGL((k_bn_bwd_apply<8>), dim3(s.nblk, s.cgy), dim3(kBlock), 0, st, s, x, ldx, dy, lddy, mean, var, gamma, eps, dgamma, dbeta, dx, lddx);
+    if (bn_stream(P, C)) hipLaunchKernelGGL((k_bn_bwd_apply<8, true>), dim3(s.nblk, s.cgy), dim3(kBlock), 0, st, s, x, ldx, dy, lddy, mean, var, gamma, eps, dgamma, dbeta, dx, lddx);
+    else hipLaunchKernelGGL((k_bn_bwd_apply<8, false>), dim3(s.nblk, s.cgy), dim3(kBlock), 0, st, s, x, ldx, dy, lddy, mean, var, gamma, eps, dgamma, dbeta, dx, lddx);
   } else {
     const BnShape s = bn_shape_pointwise<1>(P, C);
-    hipLaunchKernelGGL((k_bn_bwd_apply<1>), dim3(s.nblk, s.cgy), dim3(kBlock), 0, st, s, x, ldx, dy, lddy, mean, var, gamma, eps, dgamma, dbeta, dx, lddx);
+    if (bn_stream(P, C)) hipLaunchKernelGGL((k_bn_bwd_apply<1, true>), dim3(s.nblk, s.cgy), dim3(kBlock), 0, st, s, x, ldx, dy, lddy, mean, var, gamma, eps, dgamma, dbeta, dx, lddx);
+    else hipLaunchKernelGGL((k_bn_bwd_apply<1, false>), dim3(s.nblk, s.cgy), dim3(kBlock), 0, st, s, x, ldx, dy, lddy, mean, var, gamma, eps, dgamma, dbeta, dx, lddx);
   }
   MPT_LAUNCH_CHECK();
   return MPT_OK;

@@ -135,3 +135,42 @@ def test_conv_block_activation_shape():
     mpt.mpt_bn_stats(dev16(x), mean, var, _ws(P, C))
     dm, dv = _check_stats(x, host(mean), host(var))
     assert dm < 1e-6 and dv < 1e-5
+
+
+def test_tensor_beyond_the_memory_side_cache():
+    """205 MB activation (first-stage ResNet size, 256 x 56 x 56 positions x 128 channels): the streamed variants of
+    all four kernels.  Statistics against the oracle in full; pointwise outputs bit-exact on every 997th row."""
+    P, C = 256 * 56 * 56, 128
+    rng = np.random.default_rng(12)
+    x = (rng.standard_normal((P, C), dtype=np.float32) * 0.7 + 0.2).astype(np.float16)
+    dy = (rng.standard_normal((P, C), dtype=np.float32) * 2.0 ** -7).astype(np.float16)
+    gamma = rng.uniform(0.5, 1.5, C).astype(F); beta = rng.uniform(-1, 1, C).astype(F)
+    d_x, d_dy = dev16(x), dev16(dy)
+    mean = torch.empty(C, dtype=torch.float32, device="cuda"); var = torch.empty_like(mean)
+    ws = _ws(P, C)
+    mpt.mpt_bn_stats(d_x, mean, var, ws)
+    m32, v32 = host(mean), host(var)
+    dm, dv = _check_stats(x, m32, v32)
+    assert dm < 1e-6 and dv < 1e-5
+    rows = np.arange(0, P, 997)
+    y = torch.empty_like(d_x)
+    mpt.mpt_bn_apply(d_x, mean, var, dev(gamma), dev(beta), 1e-5, y, relu=True)
+    want = norm.bn_apply(x[rows], m32, v32, gamma, beta, 1e-5, relu=True)
+    assert np.array_equal(fp16.bits(host16(y[torch.from_numpy(rows).cuda()])), fp16.bits(want))
+    dgamma = torch.empty(C, dtype=torch.float32, device="cuda"); dbeta = torch.empty_like(dgamma)
+    mpt.mpt_bn_bwd_reduce(d_x, d_dy, mean, var, 1e-5, dgamma, dbeta, ws)
+    dg, db = norm.bn_bwd_reduce(x, dy, m32, v32, 1e-5)
+    dy64 = dy.astype(np.float64)
+    assert (np.abs(host(dbeta) - db) <= (CHAIN + 1) * U32 * np.abs(dy64).sum(axis=0) + U32 * np.abs(db)).all()
+    xhat = (x.astype(np.float64) - m32.astype(np.float64)) * (F(1.0) / np.sqrt(v32 + F(1e-5))).astype(np.float64)
+    assert (np.abs(host(dgamma) - dg) <= (CHAIN + 4) * U32 * np.abs(dy64 * xhat).sum(axis=0) + U32 * np.abs(dg)).all()
+    del xhat, dy64
+    dx = torch.empty_like(d_x)
+    mpt.mpt_bn_bwd_apply(d_x, d_dy, mean, var, dev(gamma), 1e-5, dgamma, dbeta, dx)
+    # the oracle's pointwise formula takes P from the row count: give it the sampled rows but the full P
+    Pf = F(P)
+    invstd = F(1.0) / np.sqrt(v32 + F(1e-5))
+    a = gamma * invstd; b = host(dbeta) / Pf; g = host(dgamma) / Pf
+    t = (dy[rows].astype(F) - b) - ((x[rows].astype(F) - m32) * invstd) * g
+    want = fp16.rne16((a * t).astype(np.float64))
+    assert np.array_equal(fp16.bits(host16(dx[torch.from_numpy(rows).cuda()])), fp16.bits(want))
