@@ -203,16 +203,18 @@ int mpt_master_update(void* stream, size_t n, float* w32_dev, float* m32_dev,
  *   relu_fwd:  h[i]  = max(y[i], 0)
  *   relu_bwd:  dy[i] = y[i] > 0 ? dh[i] : 0
  *   softmax_xent_scaled: p = softmax(logits[b,:]);
- *       loss_dev[0] = mean_b -log p[b,label_b]            (FP32; nullable)
+ *       row_loss_dev[b] = -log p[b,label_b]                (FP32[B]; nullable unless loss_dev is given)
+ *       loss_dev[0] = mean_b row_loss_dev[b]               (FP32; nullable; summed in a fixed order)
  *       dlogits[b,c] = rne16( scale * (p[b,c] - [c==label_b]) / B )
  *     which applies Sec. 3.2's loss scale at the head of back-propagation.
- *     labels_dev: int32, each in [0, C).  C <= 4096.
+ *     labels_dev: int32, each in [0, C).  C <= 2^24.  Each row is read once and written once when C <= 65536
+ *     (16-byte accesses when both tensors are 16-byte aligned with C and the row strides multiples of 8).
  * ------------------------------------------------------------------------- */
 int mpt_relu_fwd(void* stream, size_t n, const uint16_t* y_dev, uint16_t* h_dev);
 int mpt_relu_bwd(void* stream, size_t n, const uint16_t* dh_dev, const uint16_t* y_dev, uint16_t* dy_dev);
 int mpt_softmax_xent_scaled(void* stream, int64_t B, int64_t C,
                             const uint16_t* logits_dev, int64_t ldl, const int32_t* labels_dev,
-                            float scale, float* loss_dev, uint16_t* dlogits_dev, int64_t ldd);
+                            float scale, float* loss_dev, float* row_loss_dev, uint16_t* dlogits_dev, int64_t ldd);
 
 /* ------------------------------------------------------------------------- *
  * Batch normalisation over an FP16 tensor x[P, C], channels contiguous, row

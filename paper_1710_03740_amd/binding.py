@@ -52,7 +52,7 @@ SIGNATURES = {
     "mpt_master_update": (c_i, [c_vp, c_sz, c_vp, c_vp, c_vp, c_i, c_vp, c_f, c_vp, c_f, c_f, c_vp]),
     "mpt_relu_fwd": (c_i, [c_vp, c_sz, c_vp, c_vp]),
     "mpt_relu_bwd": (c_i, [c_vp, c_sz, c_vp, c_vp, c_vp]),
-    "mpt_softmax_xent_scaled": (c_i, [c_vp, c_i64, c_i64, c_vp, c_i64, c_vp, c_f, c_vp, c_vp, c_i64]),
+    "mpt_softmax_xent_scaled": (c_i, [c_vp, c_i64, c_i64, c_vp, c_i64, c_vp, c_f, c_vp, c_vp, c_vp, c_i64]),
     "mpt_bn_workspace_bytes": (c_sz, [c_i64, c_i64]),
     "mpt_bn_stats": (c_i, [c_vp, c_i64, c_i64, c_vp, c_i64, c_vp, c_vp, c_vp, c_sz]),
     "mpt_bn_apply": (c_i, [c_vp, c_i64, c_i64, c_vp, c_i64, c_vp, c_vp, c_vp, c_vp, c_f, c_i, c_vp, c_i64]),
@@ -234,11 +234,11 @@ def mpt_relu_bwd(dh, y, dy):
     _check("mpt_relu_bwd", lib().mpt_relu_bwd(_stream(), y.numel(), _p(dh), _p(y), _p(dy)))
 
 
-def mpt_softmax_xent_scaled(logits, labels, scale, dlogits, loss=None):
-    _dev(logits, labels, dlogits, loss)
+def mpt_softmax_xent_scaled(logits, labels, scale, dlogits, loss=None, row_loss=None):
+    _dev(logits, labels, dlogits, loss, row_loss)
     B, C = logits.shape
     _check("mpt_softmax_xent_scaled", lib().mpt_softmax_xent_scaled(_stream(), B, C, _p(logits), logits.stride(0), _p(labels),
-                                                                    scale, _p(loss), _p(dlogits), dlogits.stride(0)))
+                                                                    scale, _p(loss), _p(row_loss), _p(dlogits), dlogits.stride(0)))
 
 
 # ---------------------------------------------------------------- batch normalisation (x viewed as [P, C])

@@ -280,53 +280,171 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
-// One wavefront per row: FP16 logits in, FP32 max / sum / probabilities, FP16 scaled gradient out.
-__global__ __launch_bounds__(kThreads) void k_softmax_xent_grad(
+// Softmax cross-entropy with the loss scale folded into the gradient: FP16 logits in, FP32 max / sum / probabilities,
+// FP16 scaled gradient out, FP32 loss of the row out.  A row is held in registers between its single read and its
+// single write (4 bytes of traffic per element): WAVES wavefronts per row, NCH 16-byte chunks per lane, so a row of
+// up to WAVES*64*8*NCH classes (65536 at most; the row stays packed in FP16 and the exponential is evaluated twice).
+// Exponentials use the hardware 2^x (about 1 ulp of FP32, far inside one FP16 step).
+template <int WAVES, int NCH, bool VEC>
+__global__ __launch_bounds__((WAVES * 64 > kThreads ? WAVES * 64 : kThreads)) void k_softmax_xent_rows(
     int64_t B, int64_t C, const uint16_t* __restrict__ logits, int64_t ldl, const int32_t* __restrict__ labels,
-    float factor, uint16_t* __restrict__ dlogits, int64_t ldd) {
-  const int lane = threadIdx.x & 63;
-  const int64_t row = (int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
-  if (row >= B) return;
-  const _Float16* z = reinterpret_cast<const _Float16*>(logits) + row * ldl;
+    float factor, uint16_t* __restrict__ dlogits, int64_t ldd, float* __restrict__ row_loss) {
+  constexpr int NT = WAVES * 64 > kThreads ? WAVES * 64 : kThreads;   // threads per workgroup
+  constexpr int T = 64 * WAVES;                                        // threads per row
+  __shared__ float red[NT / 64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int rslot = wave / WAVES, tr = threadIdx.x - rslot * T;
+  const int64_t row = (int64_t)blockIdx.x * (NT / T) + rslot;
+  const bool live = row < B;
+  const _Float16* z = reinterpret_cast<const _Float16*>(logits) + (live ? row : 0) * ldl;
+  h8 q[NCH];                                                           // the row stays packed; padding is -inf
   float mx = -INFINITY;
-  for (int64_t c = lane; c < C; c += 64) mx = fmaxf(mx, (float)z[c]);
-  mx = wave_max(mx);
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    const int64_t c0 = ((int64_t)i * T + tr) * 8;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) q[i][e] = (_Float16)(-INFINITY);
+    if constexpr (VEC) {
+      if (live && c0 < C) q[i] = *reinterpret_cast<const h8*>(z + c0);
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        if (live && c0 + e < C) q[i][e] = z[c0 + e];
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) mx = fmaxf(mx, (float)q[i][e]);
+  }
+  auto across = [&](float x, bool is_max) {                // over the row's wavefronts, fixed order
+    x = is_max ? wave_max(x) : wave_sum(x);
+    if constexpr (WAVES > 1) {
+      __syncthreads();
+      if (lane == 0) red[wave] = x;
+      __syncthreads();
+      float t = red[rslot * WAVES];
+#pragma unroll
+      for (int w = 1; w < WAVES; ++w) t = is_max ? fmaxf(t, red[rslot * WAVES + w]) : __fadd_rn(t, red[rslot * WAVES + w]);
+      x = t;
+    }
+    return x;
+  };
+  mx = across(mx, true);
+  constexpr float kLog2e = 1.44269504088896340736f;
+  auto ex = [&](_Float16 h) { return __builtin_amdgcn_exp2f(__fmul_rn(__fsub_rn((float)h, mx), kLog2e)); };   // exp(-inf) = 0 for the padding
   float sum = 0.f;
-  for (int64_t c = lane; c < C; c += 64) sum = __fadd_rn(sum, expf(__fsub_rn((float)z[c], mx)));
-  sum = wave_sum(sum);
+#pragma unroll
+  for (int i = 0; i < NCH; ++i)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) sum = __fadd_rn(sum, ex(q[i][e]));
+  sum = across(sum, false);
+  if (!live) return;
   const int32_t lab = labels[row];
+  const float inv = div_rn(1.0f, sum);
   _Float16* d = reinterpret_cast<_Float16*>(dlogits) + row * ldd;
-  for (int64_t c = lane; c < C; c += 64) {
-    const float p = div_rn(expf(__fsub_rn((float)z[c], mx)), sum);
-    d[c] = (_Float16)__fmul_rn(__fsub_rn(p, c == lab ? 1.0f : 0.0f), factor);
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    const int64_t c0 = ((int64_t)i * T + tr) * 8;
+    h8 o;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float p = __fmul_rn(ex(q[i][e]), inv);
+      o[e] = (_Float16)__fmul_rn(__fsub_rn(p, (c0 + e == lab) ? 1.0f : 0.0f), factor);
+    }
+    if constexpr (VEC) {
+      if (c0 < C) *reinterpret_cast<h8*>(d + c0) = o;
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        if (c0 + e < C) d[c0 + e] = o[e];
+    }
+  }
+  if (row_loss != nullptr && tr == 0) {
+    // -log p[label] = log(sum) - (z[label] - max)
+    row_loss[row] = __fsub_rn(logf(sum), __fsub_rn((float)z[lab], mx));
   }
 }
 
-// Mean loss, one block, rows visited in a fixed order so the sum is reproducible.
-__global__ __launch_bounds__(kThreads) void k_softmax_xent_loss(
+// Rows too long to hold in registers: one workgroup of 1024 threads per row, three passes over the row (the
+// re-reads come from cache), 16-byte accesses when the row allows.
+template <bool VEC>
+__global__ __launch_bounds__(1024) void k_softmax_xent_long(
     int64_t B, int64_t C, const uint16_t* __restrict__ logits, int64_t ldl, const int32_t* __restrict__ labels,
-    float* __restrict__ loss) {
-  __shared__ float part[kThreads / 64];
+    float factor, uint16_t* __restrict__ dlogits, int64_t ldd, float* __restrict__ row_loss) {
+  constexpr int NT = 1024, W = VEC ? 8 : 1;
+  __shared__ float red[NT / 64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t row = blockIdx.x;
+  const _Float16* z = reinterpret_cast<const _Float16*>(logits) + row * ldl;
+  auto across = [&](float x, bool is_max) {
+    x = is_max ? wave_max(x) : wave_sum(x);
+    __syncthreads();
+    if (lane == 0) red[wave] = x;
+    __syncthreads();
+    float t = red[0];
+    for (int w = 1; w < NT / 64; ++w) t = is_max ? fmaxf(t, red[w]) : __fadd_rn(t, red[w]);
+    return t;
+  };
+  auto fetch = [&](int64_t c, float (&v)[W]) {
+    if constexpr (VEC) {
+      const h8 q = *reinterpret_cast<const h8*>(z + c);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = (float)q[e];
+    } else {
+      v[0] = (float)z[c];
+    }
+  };
+  float mx = -INFINITY;
+  for (int64_t c = (int64_t)threadIdx.x * W; c < C; c += (int64_t)NT * W) {
+    float v[W];
+    fetch(c, v);
+#pragma unroll
+    for (int e = 0; e < W; ++e) mx = fmaxf(mx, v[e]);
+  }
+  mx = across(mx, true);
+  constexpr float kLog2e = 1.44269504088896340736f;
+  float sum = 0.f;
+  for (int64_t c = (int64_t)threadIdx.x * W; c < C; c += (int64_t)NT * W) {
+    float v[W];
+    fetch(c, v);
+#pragma unroll
+    for (int e = 0; e < W; ++e) sum = __fadd_rn(sum, __builtin_amdgcn_exp2f(__fmul_rn(__fsub_rn(v[e], mx), kLog2e)));
+  }
+  sum = across(sum, false);
+  const int32_t lab = labels[row];
+  const float inv = div_rn(1.0f, sum);
+  _Float16* d = reinterpret_cast<_Float16*>(dlogits) + row * ldd;
+  for (int64_t c = (int64_t)threadIdx.x * W; c < C; c += (int64_t)NT * W) {
+    float v[W];
+    fetch(c, v);
+    _Float16 o[W];
+#pragma unroll
+    for (int e = 0; e < W; ++e) {
+      const float p = __fmul_rn(__builtin_amdgcn_exp2f(__fmul_rn(__fsub_rn(v[e], mx), kLog2e)), inv);
+      o[e] = (_Float16)__fmul_rn(__fsub_rn(p, c + e == lab ? 1.0f : 0.0f), factor);
+    }
+    if constexpr (VEC) {
+      h8 q;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) q[e] = o[e];
+      *reinterpret_cast<h8*>(d + c) = q;
+    } else {
+      d[c] = o[0];
+    }
+  }
+  if (row_loss != nullptr && threadIdx.x == 0) row_loss[row] = __fsub_rn(logf(sum), __fsub_rn((float)z[lab], mx));
+}
+
+// Mean of the row losses: one workgroup, each thread a strided share in row order, then a fixed-order sum (reproducible).
+__global__ __launch_bounds__(kThreads) void k_loss_mean(int64_t B, const float* __restrict__ row_loss, float* __restrict__ loss) {
+  __shared__ float part[kThreads];
   float acc = 0.f;
-  for (int64_t row = wave; row < B; row += kThreads / 64) {
-    const _Float16* z = reinterpret_cast<const _Float16*>(logits) + row * ldl;
-    float mx = -INFINITY;
-    for (int64_t c = lane; c < C; c += 64) mx = fmaxf(mx, (float)z[c]);
-    mx = wave_max(mx);
-    float sum = 0.f;
-    for (int64_t c = lane; c < C; c += 64) sum = __fadd_rn(sum, expf(__fsub_rn((float)z[c], mx)));
-    sum = wave_sum(sum);
-    const float zl = (float)z[labels[row]];
-    acc = __fadd_rn(acc, __fsub_rn(logf(sum), __fsub_rn(zl, mx)));
-  }
-  if (lane == 0) part[wave] = acc;
+  for (int64_t r = threadIdx.x; r < B; r += kThreads) acc = __fadd_rn(acc, row_loss[r]);
+  part[threadIdx.x] = acc;
   __syncthreads();
-  if (threadIdx.x == 0) {
-    float t = 0.f;
-    for (int i = 0; i < kThreads / 64; ++i) t = __fadd_rn(t, part[i]);
-    loss[0] = div_rn(t, (float)B);
+  for (int w = kThreads / 2; w > 0; w >>= 1) {
+    if ((int)threadIdx.x < w) part[threadIdx.x] = __fadd_rn(part[threadIdx.x], part[threadIdx.x + w]);
+    __syncthreads();
   }
+  if (threadIdx.x == 0) loss[0] = div_rn(part[0], (float)B);
 }
 
 // Grid size for a streaming pass over `units` thread-trips.
@@ -454,19 +572,37 @@ extern "C" int mpt_relu_bwd(void* stream, size_t n, const uint16_t* dh, const ui
 }
 
 extern "C" int mpt_softmax_xent_scaled(void* stream, int64_t B, int64_t C, const uint16_t* logits, int64_t ldl,
-                                       const int32_t* labels, float scale, float* loss, uint16_t* dlogits, int64_t ldd) {
-  if (logits == nullptr || labels == nullptr || dlogits == nullptr) return MPT_ERR_NULL;
-  if (B < 1 || C < 1 || C > 4096 || B > 0x7FFFFFFF || ldl < C || ldd < C) return MPT_ERR_SHAPE;
+                                       const int32_t* labels, float scale, float* loss, float* row_loss, uint16_t* dlogits, int64_t ldd) {
+  if (logits == nullptr || labels == nullptr || dlogits == nullptr || (loss != nullptr && row_loss == nullptr)) return MPT_ERR_NULL;
+  if (B < 1 || C < 1 || C > (1 << 24) || B > 0x7FFFFFFF || ldl < C || ldd < C) return MPT_ERR_SHAPE;
   if (!mpt_finite(scale) || !(scale > 0.f)) return MPT_ERR_ARG;
-  if (!mpt_aligned(logits, 2) || !mpt_aligned(dlogits, 2) || !mpt_aligned(labels, 4) || (loss && !mpt_aligned(loss, 4)))
+  if (!mpt_aligned(logits, 2) || !mpt_aligned(dlogits, 2) || !mpt_aligned(labels, 4) || (loss && !mpt_aligned(loss, 4)) ||
+      (row_loss && !mpt_aligned(row_loss, 4)))
     return MPT_ERR_ALIGN;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const float factor = scale / (float)B;
-  const unsigned grid = (unsigned)((B + kThreads / 64 - 1) / (kThreads / 64));
-  hipLaunchKernelGGL(k_softmax_xent_grad, dim3(grid), dim3(kThreads), 0, s, B, C, logits, ldl, labels, factor, dlogits, ldd);
+  const bool vec = mpt_aligned(logits, 16) && mpt_aligned(dlogits, 16) && (ldl % 8) == 0 && (ldd % 8) == 0 && (C % 8) == 0;
+#define MPT_SM_LAUNCH(WAVES, NCH)                                                                                                   \
+  do {                                                                                                                              \
+    constexpr unsigned nt = WAVES * 64 > kThreads ? WAVES * 64 : kThreads;                                                          \
+    const unsigned rows = nt / (64 * WAVES);                                                                                        \
+    const unsigned grid = (unsigned)((B + rows - 1) / rows);                                                                        \
+    if (vec) hipLaunchKernelGGL((k_softmax_xent_rows<WAVES, NCH, true>), dim3(grid), dim3(nt), 0, s, B, C, logits, ldl, labels,     \
+                                factor, dlogits, ldd, row_loss);                                                                    \
+    else hipLaunchKernelGGL((k_softmax_xent_rows<WAVES, NCH, false>), dim3(grid), dim3(nt), 0, s, B, C, logits, ldl, labels,        \
+                            factor, dlogits, ldd, row_loss);                                                                        \
+  } while (0)
+  if (C <= 512) MPT_SM_LAUNCH(1, 1);
+  else if (C <= 2048) MPT_SM_LAUNCH(1, 4);
+  else if (C <= 8192) MPT_SM_LAUNCH(4, 4);
+  else if (C <= 32768) MPT_SM_LAUNCH(16, 4);
+  else if (C <= 65536) MPT_SM_LAUNCH(16, 8);
+  else if (vec) hipLaunchKernelGGL(k_softmax_xent_long<true>, dim3((unsigned)B), dim3(1024), 0, s, B, C, logits, ldl, labels, factor, dlogits, ldd, row_loss);
+  else hipLaunchKernelGGL(k_softmax_xent_long<false>, dim3((unsigned)B), dim3(1024), 0, s, B, C, logits, ldl, labels, factor, dlogits, ldd, row_loss);
+#undef MPT_SM_LAUNCH
   MPT_LAUNCH_CHECK();
   if (loss != nullptr) {
-    hipLaunchKernelGGL(k_softmax_xent_loss, dim3(1), dim3(kThreads), 0, s, B, C, logits, ldl, labels, loss);
+    hipLaunchKernelGGL(k_loss_mean, dim3(1), dim3(kThreads), 0, s, B, row_loss, loss);
     MPT_LAUNCH_CHECK();
   }
   return MPT_OK;

@@ -112,8 +112,9 @@ def test_argument_errors_before_any_launch(L):
     assert L.mpt_loss_scale_update_dev(Z, Z, P) == -1
     assert L.mpt_relu_fwd(Z, 8, Z, P) == -1
     assert L.mpt_relu_bwd(Z, 8, P, P, Z) == -1
-    assert L.mpt_softmax_xent_scaled(Z, 4, 5000, P, 5000, P, 1.0, Z, P, 5000) == -2
-    assert L.mpt_softmax_xent_scaled(Z, 4, 10, P, 10, P, 0.0, Z, P, 10) == -5
+    assert L.mpt_softmax_xent_scaled(Z, 4, 5000, P, 4999, P, 1.0, Z, Z, P, 5000) == -2
+    assert L.mpt_softmax_xent_scaled(Z, 4, 10, P, 10, P, 0.0, Z, Z, P, 10) == -5
+    assert L.mpt_softmax_xent_scaled(Z, 4, 10, P, 10, P, 1.0, P, Z, P, 10) == -1      # a mean loss needs the per-row buffer
 
 
 def test_missing_library_is_an_error(monkeypatch):

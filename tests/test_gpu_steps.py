@@ -32,15 +32,30 @@ def test_relu_and_softmax_glue():
     h2 = _empty16(10008)
     mpt.mpt_relu_fwd(dev16(y)[1:], h2[2:10008])
     assert np.array_equal(fp16.bits(host16(h2)[2:]), fp16.bits(loss.relu_fwd(y[1:])))
-    for B, C, S in ((256, 10, 1024.0), (33, 1000, 128.0), (5, 4096, 1.0)):
+    for B, C, S in ((256, 10, 1024.0), (33, 1000, 128.0), (5, 4096, 1.0), (7, 512, 8.0), (9, 2048, 8.0), (6, 8192, 64.0),
+                    (3, 32768, 64.0), (3, 40000, 64.0), (2, 65536, 64.0), (2, 131072, 64.0), (2, 70001, 64.0), (5, 1001, 16.0), (4, 8191, 16.0), (130, 24, 2.0)):
         z = (rng.standard_normal((B, C)) * 3).astype(np.float16)
         lab = rng.integers(0, C, B).astype(np.int32)
+        lab[0], lab[-1] = 0, C - 1
         L, d = loss.softmax_xent_scaled(z, lab, S)
-        d_d, d_L = _empty16(B, C), torch.zeros(1, dtype=torch.float32, device="cuda")
-        mpt.mpt_softmax_xent_scaled(dev16(z), dev(lab), S, d_d, d_L)
+        d_d, d_L, d_R = _empty16(B, C), torch.zeros(1, dtype=torch.float32, device="cuda"), torch.zeros(B, dtype=torch.float32, device="cuda")
+        mpt.mpt_softmax_xent_scaled(dev16(z), dev(lab), S, d_d, d_L, d_R)
         dist = fp16.ulpdist16(fp16.bits(host16(d_d)), fp16.bits(d))
         assert dist.max() <= 1 and (dist > 0).mean() < 0.02, (B, C, dist.max(), (dist > 0).mean())
         assert abs(float(d_L.item()) - L) < 2e-6 * max(1.0, abs(L))
+        z64 = z.astype(np.float64); zs = z64 - z64.max(axis=1, keepdims=True)
+        rows = np.log(np.exp(zs).sum(axis=1)) - zs[np.arange(B), lab]                  # -log p[label], the plain definition
+        assert np.allclose(host(d_R), rows, rtol=2e-6, atol=2e-6)
+    # the gradient alone (no loss requested) needs no row buffer; a strided view takes the element-wise path
+    B, C = 9, 520
+    z = (rng.standard_normal((B, C)) * 3).astype(np.float16); lab = rng.integers(0, C, B).astype(np.int32)
+    _, d = loss.softmax_xent_scaled(z, lab, 4.0)
+    zb = torch.zeros((B, C + 3), dtype=torch.float16, device="cuda"); zb[:, 1:C + 1] = dev16(z)
+    db = torch.full((B, C + 3), 9.0, dtype=torch.float16, device="cuda")
+    mpt.mpt_softmax_xent_scaled(zb[:, 1:C + 1], dev(lab), 4.0, db[:, 1:C + 1])
+    out = host16(db)
+    assert fp16.ulpdist16(fp16.bits(np.ascontiguousarray(out[:, 1:C + 1])), fp16.bits(d)).max() <= 1
+    assert (out[:, 0] == 9.0).all() and (out[:, C + 1:] == 9.0).all()
 
 
 def test_cfg1_mlp_step_teacher_forced():
@@ -60,8 +75,8 @@ def test_cfg1_mlp_step_teacher_forced():
     assert np.array_equal(fp16.bits(host16(h1)), fp16.bits(o["h1"]))
     logits = _empty16(256, 10); mpt.mpt_gemm_fwd(dev16(o["h1"]), w2, logits)          # N = 10: element-wise loader path
     chk(logits, o["logits"], o["h1"], c["w2_16"], "fwd", "fwd2")
-    dlog, L = _empty16(256, 10), torch.zeros(1, dtype=torch.float32, device="cuda")
-    mpt.mpt_softmax_xent_scaled(dev16(o["logits"]), dev(c["labels"]), S, dlog, L)
+    dlog, L, R = _empty16(256, 10), torch.zeros(1, dtype=torch.float32, device="cuda"), torch.zeros(256, dtype=torch.float32, device="cuda")
+    mpt.mpt_softmax_xent_scaled(dev16(o["logits"]), dev(c["labels"]), S, dlog, L, R)
     dist = fp16.ulpdist16(fp16.bits(host16(dlog)), fp16.bits(o["dlogits"]))
     assert dist.max() <= 1 and abs(float(L.item()) - o["loss"]) < 1e-5
     flag = torch.zeros(1, dtype=torch.int32, device="cuda")
@@ -93,13 +108,14 @@ def test_cfg1_mlp_free_running_device_only():
     S, inv, lr = c["scale"], 1.0 / c["scale"], 0.05
     flag = torch.zeros(1, dtype=torch.int32, device="cuda")
     L = torch.zeros(1, dtype=torch.float32, device="cuda")
+    R = torch.zeros(256, dtype=torch.float32, device="cuda")
     y1, h1, logits, dlog = _empty16(256, 1024), _empty16(256, 1024), _empty16(256, 10), _empty16(256, 10)
     dw2, dh1, dy1, dw1 = _empty16(1024, 10), _empty16(256, 1024), _empty16(256, 1024), _empty16(1024, 1024)
     ow = (c["w1_32"], c["w2_32"], c["w1_16"], c["w2_16"])
     losses, olosses = [], []
     for _ in range(3):
         mpt.mpt_gemm_fwd(x, w1, y1); mpt.mpt_relu_fwd(y1, h1); mpt.mpt_gemm_fwd(h1, w2, logits)
-        mpt.mpt_softmax_xent_scaled(logits, lab, S, dlog, L)
+        mpt.mpt_softmax_xent_scaled(logits, lab, S, dlog, L, R)
         mpt.mpt_gemm_wgrad(h1, dlog, dw2, flag=flag); mpt.mpt_gemm_dgrad(dlog, w2, dh1)
         mpt.mpt_relu_bwd(dh1, y1, dy1); mpt.mpt_gemm_wgrad(x, dy1, dw1, flag=flag)
         mpt.mpt_master_update(w1_32, None, dw1, w1, inv, lr, 0.0, flag)
