@@ -34,7 +34,7 @@ def test_scale_rule():
     assert gradstats.suggest_scale_log2(1.0) == 15            # 32768 <= 65504 < 65536
     assert gradstats.suggest_scale_log2(65504.0) == 0
     assert gradstats.suggest_scale_log2(2.0 ** -24) == 39
-    assert gradstats.suggest_scale_log2(1.999) == 14 and gradstats.suggest_scale_log2(0.999) == 16
+    assert gradstats.suggest_scale_log2(2.0) == 14 and gradstats.suggest_scale_log2(1.999) == 15 and gradstats.suggest_scale_log2(0.999) == 16
     assert gradstats.suggest_scale_log2(0.0) is None
     for a in (3.1e-5, 0.37, 12.0, 40000.0):
         k = gradstats.suggest_scale_log2(a)
