@@ -217,6 +217,69 @@ int mpt_softmax_xent_scaled(void* stream, int64_t B, int64_t C,
                             float scale, float* loss_dev, float* row_loss_dev, uint16_t* dlogits_dev, int64_t ldd);
 
 /* ------------------------------------------------------------------------- *
+ * Other optimizers in the same fused pass (Sec. 4 trains with momentum SGD,
+ * Nesterov SGD, Adagrad and Adam; Sec. 3.1 keeps weights and with them the
+ * optimizer state in FP32; Sec. 3.2: the gradient is unscaled before anything
+ * else touches it, so weight decay and every other hyper-parameter is the
+ * same as in FP32 training).  The paper prints no update rule; the customary
+ * ones are used, each a fixed sequence of individually rounded FP32
+ * operations, (*) (+) (-) (/) sqrt:
+ *     g = float(grad) (*) inv_S        [if weight_decay != 0:  g = g (+) (weight_decay (*) w)]
+ *   MOMENTUM  m' = (mu (*) m) (+) g               w' = w (-) (lr (*) m')
+ *   NESTEROV  m' = (mu (*) m) (+) g               w' = w (-) (lr (*) (g (+) (mu (*) m')))
+ *   ADAGRAD   h' = h (+) (g (*) g)                w' = w (-) ((lr (*) g) (/) (sqrt(h') (+) eps))
+ *   ADAM      m' = (beta1 (*) m) (+) (one_minus_beta1 (*) g)
+ *             v' = (beta2 (*) v) (+) (one_minus_beta2 (*) (g (*) g))
+ *             w' = w (-) ((lr (*) (m' (/) bias_corr1)) (/) (sqrt(v' (/) bias_corr2) (+) eps))
+ *     w16' = rne16(w')
+ * state1 is m / h / m, state2 is Adam's v (ignored otherwise, may be NULL).
+ * `momentum` holds mu, or beta1 for Adam; one_minus_beta* and bias_corr*
+ * (1 - beta^t for the 1-based step t) are supplied by the caller already
+ * rounded to FP32.  hp is a HOST pointer, read before the call returns.
+ * inv_scale / scaler_dev / flag_dev as in mpt_master_update: a nonzero flag
+ * makes the call a no-op, state included.  All arrays are device memory of n
+ * elements owned by the caller; pairs of elements are moved together when
+ * the FP32 arrays are 8-byte and the FP16 arrays 4-byte aligned, else one at
+ * a time.  Traffic per element with an FP16 gradient: 20 B (28 B for Adam).
+ * Errors: NULL, ARG (unknown kind, non-finite or negative hyper-parameter,
+ * bias correction not > 0), ALIGN.
+ * ------------------------------------------------------------------------- */
+typedef enum mpt_opt_kind { MPT_OPT_MOMENTUM = 0, MPT_OPT_NESTEROV = 1, MPT_OPT_ADAGRAD = 2, MPT_OPT_ADAM = 3 } mpt_opt_kind;
+typedef struct mpt_opt_params {
+  float lr;
+  float momentum;
+  float beta2;
+  float eps;
+  float weight_decay;
+  float one_minus_beta1, one_minus_beta2;
+  float bias_corr1, bias_corr2;
+} mpt_opt_params;
+int mpt_optimizer_update(void* stream, size_t n, int kind, const mpt_opt_params* hp_host,
+                         float* w32_dev, float* state1_dev, float* state2_dev,
+                         const void* grad_dev, int grad_is_fp32, uint16_t* w16_dev,
+                         float inv_scale, const mpt_scaler* scaler_dev, const uint32_t* flag_dev);
+
+/* ------------------------------------------------------------------------- *
+ * Gradient statistics (Sec. 3.2: exponent histograms of the gradients show
+ * what FP16 would lose, and a constant loss scale is chosen so that
+ * scale * max|g| stays below 65504).  Over the stored FP16 values:
+ *   hist_dev[0]            zeros (+0, -0)
+ *   hist_dev[1 + e + 24]   finite non-zero values with floor(log2 |g|) = e, e = -24 .. 15
+ *   hist_dev[41]           Inf and NaN
+ *   absmax_bits_dev[0]     bit pattern (sign cleared) of the largest finite magnitude, 0 if none
+ * hist_dev: uint64[42], absmax_bits_dev: uint32, device memory.  accumulate = 0
+ * clears both first; accumulate != 0 adds to what they hold (several buffers,
+ * one histogram).  Counts are integers, so the result does not depend on the
+ * order of evaluation.  mpt_suggest_loss_scale_log2 (host, pure C) returns k
+ * with 2^k the largest power of two such that 2^k * max <= 65504, clamped to
+ * [-24, 40]; max is given as the FP16 bit pattern; 0 yields `if_zero`.
+ * ------------------------------------------------------------------------- */
+#define MPT_GRAD_STATS_BINS 42
+int mpt_grad_stats(void* stream, const uint16_t* grad_dev, size_t n, int accumulate,
+                   uint64_t* hist_dev, uint32_t* absmax_bits_dev);
+int mpt_suggest_loss_scale_log2(uint32_t absmax_bits, int if_zero);
+
+/* ------------------------------------------------------------------------- *
  * Batch normalisation over an FP16 tensor x[P, C], channels contiguous, row
  * stride ldx >= C elements (an NHWC activation with P = N*H*W).  Sec. 3.3: the
  * statistics are large reductions and are accumulated wide; the layer reads

@@ -30,6 +30,13 @@ class mpt_scaler(ctypes.Structure):
                 ("min_scale", c_f), ("max_scale", c_f)]
 
 
+class mpt_opt_params(ctypes.Structure):
+    _fields_ = [("lr", c_f), ("momentum", c_f), ("beta2", c_f), ("eps", c_f), ("weight_decay", c_f),
+                ("one_minus_beta1", c_f), ("one_minus_beta2", c_f), ("bias_corr1", c_f), ("bias_corr2", c_f)]
+
+
+OPT_KINDS = {"momentum": 0, "nesterov": 1, "adagrad": 2, "adam": 3}
+
 _GEMM = [c_vp, c_i64, c_i64, c_i64, c_vp, c_i64, c_vp, c_i64, c_vp, c_i64, c_vp, c_sz]
 _CONV = [c_vp, c_i64, c_i64, c_i64, c_i64, c_i64, c_vp, c_vp, c_vp, c_vp, c_sz]
 SIGNATURES = {
@@ -53,6 +60,9 @@ SIGNATURES = {
     "mpt_relu_fwd": (c_i, [c_vp, c_sz, c_vp, c_vp]),
     "mpt_relu_bwd": (c_i, [c_vp, c_sz, c_vp, c_vp, c_vp]),
     "mpt_softmax_xent_scaled": (c_i, [c_vp, c_i64, c_i64, c_vp, c_i64, c_vp, c_f, c_vp, c_vp, c_vp, c_i64]),
+    "mpt_optimizer_update": (c_i, [c_vp, c_sz, c_i, c_vp, c_vp, c_vp, c_vp, c_vp, c_i, c_vp, c_f, c_vp, c_vp]),
+    "mpt_grad_stats": (c_i, [c_vp, c_vp, c_sz, c_i, c_vp, c_vp]),
+    "mpt_suggest_loss_scale_log2": (c_i, [ctypes.c_uint32, c_i]),
     "mpt_bn_workspace_bytes": (c_sz, [c_i64, c_i64]),
     "mpt_bn_stats": (c_i, [c_vp, c_i64, c_i64, c_vp, c_i64, c_vp, c_vp, c_vp, c_sz]),
     "mpt_bn_apply": (c_i, [c_vp, c_i64, c_i64, c_vp, c_i64, c_vp, c_vp, c_vp, c_vp, c_f, c_i, c_vp, c_i64]),
@@ -195,6 +205,24 @@ def mpt_master_update(w32, m32, grad, w16, inv_scale, lr, momentum, flag=None, s
     _check("mpt_master_update", lib().mpt_master_update(_stream(), w32.numel(), _p(w32), _p(m32), _p(grad),
                                                         1 if grad.dtype == torch.float32 else 0, _p(w16),
                                                         inv_scale, _p(scaler_dev), lr, momentum, _p(flag)))
+
+
+def mpt_optimizer_update(kind, hp, w32, state1, state2, grad, w16, inv_scale, flag=None, scaler_dev=None):
+    """kind: a key of OPT_KINDS; hp: an mpt_opt_params (host struct)."""
+    _dev(w32, state1, state2, grad, w16, flag, scaler_dev)
+    _check("mpt_optimizer_update", lib().mpt_optimizer_update(_stream(), w32.numel(), OPT_KINDS[kind], ctypes.byref(hp), _p(w32), _p(state1),
+                                                              _p(state2), _p(grad), 1 if grad.dtype == torch.float32 else 0, _p(w16),
+                                                              inv_scale, _p(scaler_dev), _p(flag)))
+
+
+def mpt_grad_stats(grad, hist, absmax_bits, accumulate=False):
+    """hist: int64[42] device tensor; absmax_bits: int32[1] device tensor."""
+    _dev(grad, hist, absmax_bits)
+    _check("mpt_grad_stats", lib().mpt_grad_stats(_stream(), _p(grad), grad.numel(), 1 if accumulate else 0, _p(hist), _p(absmax_bits)))
+
+
+def mpt_suggest_loss_scale_log2(absmax_bits, if_zero=0):
+    return lib().mpt_suggest_loss_scale_log2(int(absmax_bits) & 0xFFFFFFFF, if_zero)
 
 
 def mpt_scaler_init(scale, growth_interval):

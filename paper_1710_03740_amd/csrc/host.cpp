@@ -16,7 +16,7 @@ extern "C" const char* mpt_status_string(int status) {
   }
 }
 
-extern "C" int mpt_version(void) { return 102; }
+extern "C" int mpt_version(void) { return 103; }
 
 extern "C" int mpt_scaler_init(mpt_scaler* s, float scale, int32_t growth_interval) {
   if (s == nullptr) return MPT_ERR_NULL;
@@ -46,4 +46,23 @@ extern "C" int mpt_loss_scale_update(mpt_scaler* s, int overflow) {
   }
   s->inv_scale = 1.0f / s->scale;
   return MPT_OK;
+}
+
+// Largest power of two 2^k with 2^k * max <= 65504 (paper Sec. 3.2), from the FP16 bit pattern of max.
+// Exact integer arithmetic: max = m * 2^q with integer m < 2^11, and 65504 = 2047 * 2^5.
+extern "C" int mpt_suggest_loss_scale_log2(uint32_t absmax_bits, int if_zero) {
+  const uint32_t mag = absmax_bits & 0x7FFFu;
+  if (mag == 0u || mag >= 0x7C00u) return if_zero;
+  const uint32_t ef = mag >> 10, mant = mag & 0x3FFu;
+  const int64_t m = ef ? (int64_t)(1024 + mant) : (int64_t)mant;       // value = m * 2^q
+  const int q = ef ? (int)ef - 25 : -24;
+  // 2^k * m * 2^q <= 2047 * 2^5  <=>  m * 2^sh <= 2047 with sh = k + q - 5  (m < 2^11)
+  for (int k = 40; k >= -24; --k) {
+    const int sh = k + q - 5;
+    bool ok;
+    if (sh >= 0) ok = sh <= 11 && (m << sh) <= 2047;
+    else ok = -sh >= 11 || m <= ((int64_t)2047 << -sh);
+    if (ok) return k;
+  }
+  return -24;
 }

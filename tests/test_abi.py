@@ -99,6 +99,17 @@ def test_argument_errors_before_any_launch(L):
     assert L.mpt_bn_bwd_reduce(Z, 1000, 64, P, 64, Z, 64, P, P, 1e-5, P, P, P, need) == -1
     assert L.mpt_bn_bwd_apply(Z, 1000, 64, P, 64, P, 64, P, P, P, float("nan"), P, P, P, 64) == -5
     assert L.mpt_bn_bwd_apply(Z, 1000, 0, P, 64, P, 64, P, P, P, 1e-5, P, P, P, 64) == -2
+    hp = (ctypes.c_float * 9)(0.1, 0.9, 0.999, 1e-8, 0.0, 0.1, 0.001, 0.1, 0.001)
+    assert L.mpt_optimizer_update(Z, 8, 3, hp, P, P, Z, P, 0, P, 1.0, Z, Z) == -1          # Adam needs its second moment
+    assert L.mpt_optimizer_update(Z, 8, 9, hp, P, P, P, P, 0, P, 1.0, Z, Z) == -5
+    assert L.mpt_optimizer_update(Z, 8, 1, Z, P, P, P, P, 0, P, 1.0, Z, Z) == -1
+    assert L.mpt_optimizer_update(Z, 8, 2, hp, P, odd, P, P, 0, P, 1.0, Z, Z) == -3
+    assert L.mpt_optimizer_update(Z, 8, 0, hp, P, P, P, P, 0, P, 0.0, Z, Z) == -5
+    bad = (ctypes.c_float * 9)(0.1, 0.9, 0.999, 1e-8, 0.0, 0.1, 0.001, 0.0, 0.001)
+    assert L.mpt_optimizer_update(Z, 8, 3, bad, P, P, P, P, 0, P, 1.0, Z, Z) == -5          # bias correction must be > 0
+    assert L.mpt_optimizer_update(Z, 0, 3, Z, Z, Z, Z, Z, 0, Z, 1.0, Z, Z) == 0
+    assert L.mpt_grad_stats(Z, P, 8, 0, Z, P) == -1
+    assert L.mpt_grad_stats(Z, odd, 8, 0, P, P) == -3
     assert L.mpt_unscale_check(Z, Z, 0, 8, 1.0, Z, P) == -1
     assert L.mpt_unscale_check(Z, P, 0, 8, 0.0, Z, P) == -5
     assert L.mpt_unscale_check(Z, P, 0, 8, float("inf"), Z, P) == -5
@@ -123,3 +134,17 @@ def test_missing_library_is_an_error(monkeypatch):
     monkeypatch.setattr(binding, "LIB_PATH", "/nonexistent/libmpt.so")
     with pytest.raises(RuntimeError, match="no fallback"):
         binding.lib()
+
+
+def test_suggested_scale_matches_the_oracle_for_every_fp16_magnitude(L):
+    """Host-only function: checked exhaustively against the oracle's rule (largest 2^k with 2^k * max <= 65504)."""
+    import numpy as np
+    from oracle import gradstats
+    L.mpt_suggest_loss_scale_log2.restype = ctypes.c_int
+    L.mpt_suggest_loss_scale_log2.argtypes = [ctypes.c_uint32, ctypes.c_int]
+    vals = np.arange(1, 0x7C00, dtype=np.uint16).view(np.float16).astype(np.float64)
+    for bits in list(range(1, 0x7C00, 37)) + [1, 0x3FF, 0x400, 0x3C00, 0x7BFF]:
+        k = gradstats.suggest_scale_log2(float(vals[bits - 1]))
+        assert L.mpt_suggest_loss_scale_log2(bits, -99) == max(-24, min(40, k)), bits
+    assert L.mpt_suggest_loss_scale_log2(0, -99) == -99 and L.mpt_suggest_loss_scale_log2(0x7C00, 7) == 7
+    assert L.mpt_suggest_loss_scale_log2(0x8000 | 0x3C00, 0) == 15          # the sign bit is ignored: |-1.0|
