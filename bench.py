@@ -32,12 +32,113 @@ GEMM_TRAFFIC_BYTES = 235.4e6      # 201.8 MB read + 33.6 MB written per 4096^3 l
 UPDATE_TRAFFIC_BYTES = 2320.0e6   # 1160 MB read + 1160 MB written per 116M-element launch
 
 
+def measure_next(torch, mpt, np, dev, with_cpu):
+    """Kernels beyond the headline path, each timed alone on resident inputs against the HBM (or MFMA) roofline, with
+    the CPU oracle timed on a bounded sample of the same input.  Returns a list of dicts."""
+    rows = []
+
+    def timeit(fn, reps=10, warm=3):
+        for _ in range(warm):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e-3
+
+    def row(name, workload, bytes_alg, sec, cpu=None):
+        gbs = bytes_alg / sec / 1e9
+        rows.append({"kernel": name, "workload": workload, "bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(gbs / HBM_PEAK_GBS, 4), "avg_launch_us": round(sec * 1e6, 1), "cpu_oracle": cpu})
+
+    def cpu_time(fn, sample_bytes, sample):
+        if not with_cpu:
+            return None
+        t0 = time.perf_counter()
+        fn()
+        dt = time.perf_counter() - t0
+        return {"value": round(sample_bytes / dt / 1e9, 3), "unit": "GB/s", "kind": "oracle", "sample": sample + "; %.2f s wall" % dt}
+
+    from oracle import norm as onorm, loss as oloss, optim as ooptim, gradstats as ostats
+    # ---- batch normalisation on a 411 MB activation (256 x 56 x 56 positions, 256 channels)
+    P, C = 256 * 56 * 56, 256
+    x = (torch.randn(P, C, device=dev) * 0.7 + 0.2).half()
+    dy = (torch.randn(P, C, device=dev) * 2.0 ** -7).half()
+    y = torch.empty_like(x)
+    mean, var = torch.empty(C, device=dev), torch.empty(C, device=dev)
+    gamma, beta = torch.ones(C, device=dev), torch.zeros(C, device=dev)
+    dg, db = torch.empty(C, device=dev), torch.empty(C, device=dev)
+    ws = torch.empty(max(mpt.mpt_bn_workspace_bytes(P, C), 16) // 8, dtype=torch.float64, device=dev)
+    wl = "x[%d, %d] FP16 (%.0f MB)" % (P, C, P * C * 2 / 1e6)
+    n = P * C
+    ps = 20000                                                           # rows of the CPU sample
+    xs = x[:ps].cpu().numpy(); dys = dy[:ps].cpu().numpy()
+    t = timeit(lambda: mpt.mpt_bn_stats(x, mean, var, ws))
+    row("bn_stats (k_bn_partial + k_bn_finalize)", wl, 2 * n, t, cpu_time(lambda: onorm.bn_stats(xs), 2 * ps * C, "first %d rows" % ps))
+    m32, v32 = mean.cpu().numpy(), var.cpu().numpy()
+    g32, b32 = gamma.cpu().numpy(), beta.cpu().numpy()
+    t = timeit(lambda: mpt.mpt_bn_apply(x, mean, var, gamma, beta, 1e-5, y, relu=True))
+    row("bn_apply (k_bn_apply, with ReLU)", wl, 4 * n, t, cpu_time(lambda: onorm.bn_apply(xs, m32, v32, g32, b32, 1e-5, relu=True), 4 * ps * C, "first %d rows" % ps))
+    t = timeit(lambda: mpt.mpt_bn_bwd_reduce(x, dy, mean, var, 1e-5, dg, db, ws))
+    row("bn_bwd_reduce (k_bn_partial + k_bn_finalize)", wl, 4 * n, t, cpu_time(lambda: onorm.bn_bwd_reduce(xs, dys, m32, v32, 1e-5), 4 * ps * C, "first %d rows" % ps))
+    dg32, db32 = dg.cpu().numpy(), db.cpu().numpy()
+    t = timeit(lambda: mpt.mpt_bn_bwd_apply(x, dy, mean, var, gamma, 1e-5, dg, db, y))
+    row("bn_bwd_apply (k_bn_bwd_apply)", wl, 6 * n, t, cpu_time(lambda: onorm.bn_bwd_apply(xs, dys, m32, v32, g32, 1e-5, dg32, db32), 6 * ps * C, "first %d rows" % ps))
+    del x, dy, y, ws
+    # ---- softmax cross-entropy with the loss scale: 5120 rows (256 sequences x 20 steps) of 32768 classes
+    B, Cc = 5120, 32768
+    z = (torch.randn(B, Cc, device=dev) * 3).half()
+    d = torch.empty_like(z)
+    lab = torch.randint(0, Cc, (B,), device=dev, dtype=torch.int32)
+    L, R = torch.zeros(1, device=dev), torch.zeros(B, device=dev)
+    t = timeit(lambda: mpt.mpt_softmax_xent_scaled(z, lab, 128.0, d, L, R))
+    zs, ls = z[:64].cpu().numpy(), lab[:64].cpu().numpy()
+    row("softmax_xent_scaled (k_softmax_xent_rows, 16 wavefronts per row)", "logits[%d, %d] FP16 (%.0f MB) -> scaled gradient" % (B, Cc, B * Cc * 2 / 1e6),
+        4 * B * Cc, t, cpu_time(lambda: oloss.softmax_xent_scaled(zs, ls, 128.0), 4 * 64 * Cc, "first 64 rows"))
+    del z, d
+    # ---- Adam on the 116M-element flat buffer (28 B/element), and the gradient statistics pass (2 B/element)
+    nf = N_FLAT
+    MiB2 = 1 << 21
+    sizes = [nf * 4, nf * 4, nf * 4, nf * 2, nf * 2]
+    offs, o = [], 0
+    for sz in sizes:
+        offs.append(o)
+        o += (sz + MiB2 - 1) // MiB2 * MiB2
+    pool = torch.empty(o, dtype=torch.uint8, device=dev)
+    w = pool[offs[0]:offs[0] + sizes[0]].view(torch.float32)
+    a = pool[offs[1]:offs[1] + sizes[1]].view(torch.float32)
+    b = pool[offs[2]:offs[2] + sizes[2]].view(torch.float32)
+    g = pool[offs[3]:offs[3] + sizes[3]].view(torch.float16)
+    h = pool[offs[4]:offs[4] + sizes[4]].view(torch.float16)
+    w.uniform_(-0.05, 0.05); a.zero_(); b.fill_(1e-4); g.copy_(torch.randn(nf, device=dev) * 64); h.copy_(w)
+    op = ooptim.adam_params(1e-3, 0.9, 0.999, 1e-8, 10)
+    hp = mpt.mpt_opt_params(op.lr, op.momentum, op.beta2, op.eps, op.weight_decay, op.one_minus_beta1, op.one_minus_beta2, op.bias_corr1, op.bias_corr2)
+    ns = 4_000_000
+    ws_, as_, bs_, gs_ = w[:ns].cpu().numpy(), a[:ns].cpu().numpy(), b[:ns].cpu().numpy(), g[:ns].cpu().numpy()
+    t = timeit(lambda: mpt.mpt_optimizer_update("adam", hp, w, a, b, g, h, 2.0 ** -16, None))
+    row("optimizer_update Adam (k_optimizer_update)", "%d elements, FP16 gradient, 28 B/element" % nf, 28 * nf, t,
+        cpu_time(lambda: ooptim.optimizer_update("adam", ws_, as_, bs_, gs_, 2.0 ** -16, op, 0), 28 * ns, "first %d elements" % ns))
+    hpn = mpt.mpt_opt_params(1e-3, 0.9, 0.0, 0.0, 0.0, 0.0, 0.0, 1.0, 1.0)
+    t = timeit(lambda: mpt.mpt_optimizer_update("nesterov", hpn, w, a, None, g, h, 2.0 ** -16, None))
+    row("optimizer_update Nesterov (k_optimizer_update)", "%d elements, FP16 gradient, 20 B/element" % nf, 20 * nf, t)
+    hist = torch.zeros(42, dtype=torch.int64, device=dev)
+    am = torch.zeros(1, dtype=torch.int32, device=dev)
+    t = timeit(lambda: mpt.mpt_grad_stats(g, hist, am))
+    row("grad_stats (k_grad_stats)", "%d FP16 gradients -> 42-bin exponent histogram + max magnitude" % nf, 2 * nf, t,
+        cpu_time(lambda: (ostats.exponent_histogram(gs_), ostats.absmax(gs_)), 2 * ns, "first %d elements" % ns))
+    del pool, w, a, b, g, h
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-next", action="store_true", help="skip the kernels beyond the headline path (batch norm, softmax, other optimizers, statistics)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy, so a counter run of this command holds a kernel of known traffic")
     args = ap.parse_args()
@@ -165,6 +266,8 @@ def main():
                        "unscale_check_GBs": round(2.0 * N_FLAT / (chk_ms * 1e-3) / 1e9, 1)}
     del w, m, g, h, pool
 
+    next_rows = None if args.no_next else measure_next(torch, mpt, np, dev, not args.no_cpu_baseline)
+
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import gemm as ogemm
@@ -190,7 +293,7 @@ def main():
                       "loss_scale": 8192, "master_update_elements": n * n},
            "pct_of_fp16_peak": round(100 * value / MFMA_F16_PEAK_TFLOPS, 2),
            "master_update_pct_of_hbm_peak": round(100 * upd_gbs / HBM_PEAK_GBS, 2),
-           "roofline": roofline, "roofline_update": roofline_update, "cpu_baseline": cpu}
+           "roofline": roofline, "roofline_update": roofline_update, "roofline_next": next_rows, "cpu_baseline": cpu}
     print(json.dumps(out))
 
 
