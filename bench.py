@@ -129,6 +129,47 @@ def measure_next(torch, mpt, np, dev, with_cpu):
     row("grad_stats (k_grad_stats)", "%d FP16 gradients -> 42-bin exponent histogram + max magnitude" % nf, 2 * nf, t,
         cpu_time(lambda: (ostats.exponent_histogram(gs_), ostats.absmax(gs_)), 2 * ns, "first %d elements" % ns))
     del pool, w, a, b, g, h
+    # ---- LSTM cell (pointwise part) at the time-batched language-model shape: 5120 rows x 8192 cells
+    from oracle import lstm as olstm
+    Bc, Hc = 5120, 8192
+    gx = torch.randn(Bc, 4 * Hc, device=dev).half(); gr = torch.randn(Bc, 4 * Hc, device=dev).half()
+    cp = torch.randn(Bc, Hc, device=dev).half()
+    act, cc, hh = torch.empty_like(gx), torch.empty_like(cp), torch.empty_like(cp)
+    dh, dcn = (torch.randn(Bc, Hc, device=dev) * 0.01).half(), (torch.randn(Bc, Hc, device=dev) * 0.01).half()
+    da, dcp = torch.empty_like(gx), torch.empty_like(cp)
+    rs = 64
+    gxs, grs, cps = gx[:rs].cpu().numpy(), gr[:rs].cpu().numpy(), cp[:rs].cpu().numpy()
+    t = timeit(lambda: mpt.mpt_lstm_cell_fwd(gx, gr, None, cp, act, cc, hh))
+    row("lstm_cell_fwd (k_lstm_cell_fwd)", "%d rows x %d cells, 30 B/cell" % (Bc, Hc), 30 * Bc * Hc, t,
+        cpu_time(lambda: olstm.lstm_cell_fwd(gxs, grs, None, cps), 30 * rs * Hc, "first %d rows" % rs))
+    acts, ccs, dhs, dcns = act[:rs].cpu().numpy(), cc[:rs].cpu().numpy(), dh[:rs].cpu().numpy(), dcn[:rs].cpu().numpy()
+    t = timeit(lambda: mpt.mpt_lstm_cell_bwd(dh, dcn, act, cc, cp, da, dcp))
+    row("lstm_cell_bwd (k_lstm_cell_bwd)", "%d rows x %d cells, 22 B/cell" % (Bc, Hc), 22 * Bc * Hc, t,
+        cpu_time(lambda: olstm.lstm_cell_bwd(dhs, dcns, acts, ccs, cps), 22 * rs * Hc, "first %d rows" % rs))
+    del gx, gr, act, da
+    # ---- free-running projected LSTM layer, forward, 20 steps of batch 256 (1024 -> 8192 cells -> 1024), no host round trips
+    T, B2, I, H2, R2 = 20, 256, 1024, 8192, 1024
+    x = torch.randn(T * B2, I, device=dev).half()
+    Wx = (torch.randn(I, 4 * H2, device=dev) * 0.03).half(); Wr = (torch.randn(R2, 4 * H2, device=dev) * 0.03).half()
+    Wp = (torch.randn(H2, R2, device=dev) * 0.01).half()
+    gxa = torch.empty(T * B2, 4 * H2, device=dev, dtype=torch.float16)
+    grr, ac = torch.empty(B2, 4 * H2, device=dev, dtype=torch.float16), torch.empty(B2, 4 * H2, device=dev, dtype=torch.float16)
+    c2, h2 = torch.zeros(B2, H2, device=dev, dtype=torch.float16), torch.empty(B2, H2, device=dev, dtype=torch.float16)
+    r2 = torch.zeros(B2, R2, device=dev, dtype=torch.float16)
+    wsp = torch.empty(max(mpt.mpt_gemm_workspace_bytes(0, B2, R2, H2), 16) // 4, dtype=torch.float32, device=dev)
+
+    def layer():
+        mpt.mpt_gemm_fwd(x, Wx, gxa)
+        for ts in range(T):
+            mpt.mpt_gemm_fwd(r2, Wr, grr)
+            mpt.mpt_lstm_cell_fwd(gxa[ts * B2:(ts + 1) * B2], grr, None, c2, ac, c2, h2)
+            mpt.mpt_gemm_fwd(h2, Wp, r2, wsp)
+    t = timeit(layer, reps=5, warm=2)
+    fl = 2.0 * T * B2 * (I * 4 * H2 + R2 * 4 * H2 + H2 * R2)
+    rows.append({"kernel": "free-running LSTM layer forward (time-batched input GEMM + per step: recurrent GEMM, cell, projection GEMM)",
+                 "workload": "T=20, batch 256, 1024 -> 8192 cells -> 1024", "bound": "mfma", "achieved": round(fl / t / 1e12, 1),
+                 "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(fl / t / 1e12 / MFMA_F16_PEAK_TFLOPS, 4),
+                 "avg_launch_us": round(t * 1e6, 1), "us_per_step": round(t * 1e6 / T, 1), "cpu_oracle": None})
     return rows
 
 

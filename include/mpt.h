@@ -320,6 +320,38 @@ int mpt_bn_bwd_apply(void* stream, int64_t P, int64_t C, const uint16_t* x_dev, 
                      const float* gamma_dev, float eps, const float* dgamma_dev, const float* dbeta_dev,
                      uint16_t* dx_dev, int64_t lddx);
 
+/* ------------------------------------------------------------------------- *
+ * Pointwise part of an LSTM cell (Sec. 3.3 "point-wise operations"; the
+ * recurrent layers of Sec. 4): FP16 tensors, FP32 math.  The products that
+ * feed it (time-batched x W_x, per-step r W_r, projection h W_p) are
+ * mpt_gemm_fwd calls.  Gate order (i, f, g, o) along the 4H axis; the paper
+ * prints no cell equations, the customary ones are used:
+ *   a = gx + gr (+ bias);  i,f,o = sigmoid(a_i, a_f, a_o);  g = tanh(a_g)
+ *   c = f * c_prev + i * g;   h = o * tanh(c)              (tanh of the unrounded c)
+ *   stores act = rne16(i,f,g,o) [B,4H], c [B,H], h [B,H]
+ * backward, from the stored act, c, c_prev, the gradient dh of h and the
+ * state gradient dc_next carried from the next step (NULL = 0):
+ *   tc = tanh(c);  dc = dh*o*(1 - tc^2) + dc_next
+ *   da = ( dc*g*i(1-i), dc*c_prev*f(1-f), dc*i*(1-g^2), dh*tc*o(1-o) )   dc_prev = dc * f
+ * gr and bias (FP32[4H]) may be NULL.  c may alias c_prev and dc_prev may
+ * alias dc_next (each element is read and written by the same thread);
+ * otherwise outputs must not overlap inputs.  Row strides are in elements.
+ * 16-byte accesses when H % 8 == 0 and every tensor is 16-byte aligned with
+ * a stride that is a multiple of 8; else element-wise, same results.
+ * Results agree with an FP64 evaluation to within one FP16 step (hardware
+ * exponential and reciprocal, library tanh); they are not specified bit for bit.
+ * Errors: NULL, SHAPE (B, H < 1, stride too small), ALIGN.
+ * ------------------------------------------------------------------------- */
+int mpt_lstm_cell_fwd(void* stream, int64_t B, int64_t H,
+                      const uint16_t* gx_dev, int64_t ldgx, const uint16_t* gr_dev, int64_t ldgr, const float* bias_dev,
+                      const uint16_t* c_prev_dev, int64_t ldcp,
+                      uint16_t* act_dev, int64_t ldact, uint16_t* c_dev, int64_t ldc, uint16_t* h_dev, int64_t ldh);
+int mpt_lstm_cell_bwd(void* stream, int64_t B, int64_t H,
+                      const uint16_t* dh_dev, int64_t lddh, const uint16_t* dc_next_dev, int64_t lddcn,
+                      const uint16_t* act_dev, int64_t ldact, const uint16_t* c_dev, int64_t ldc,
+                      const uint16_t* c_prev_dev, int64_t ldcp,
+                      uint16_t* da_dev, int64_t ldda, uint16_t* dc_prev_dev, int64_t lddcp);
+
 #ifdef __cplusplus
 }
 #endif

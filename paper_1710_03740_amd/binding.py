@@ -63,6 +63,8 @@ SIGNATURES = {
     "mpt_optimizer_update": (c_i, [c_vp, c_sz, c_i, c_vp, c_vp, c_vp, c_vp, c_vp, c_i, c_vp, c_f, c_vp, c_vp]),
     "mpt_grad_stats": (c_i, [c_vp, c_vp, c_sz, c_i, c_vp, c_vp]),
     "mpt_suggest_loss_scale_log2": (c_i, [ctypes.c_uint32, c_i]),
+    "mpt_lstm_cell_fwd": (c_i, [c_vp, c_i64, c_i64, c_vp, c_i64, c_vp, c_i64, c_vp, c_vp, c_i64, c_vp, c_i64, c_vp, c_i64, c_vp, c_i64]),
+    "mpt_lstm_cell_bwd": (c_i, [c_vp, c_i64, c_i64, c_vp, c_i64, c_vp, c_i64, c_vp, c_i64, c_vp, c_i64, c_vp, c_i64, c_vp, c_i64, c_vp, c_i64]),
     "mpt_bn_workspace_bytes": (c_sz, [c_i64, c_i64]),
     "mpt_bn_stats": (c_i, [c_vp, c_i64, c_i64, c_vp, c_i64, c_vp, c_vp, c_vp, c_sz]),
     "mpt_bn_apply": (c_i, [c_vp, c_i64, c_i64, c_vp, c_i64, c_vp, c_vp, c_vp, c_vp, c_f, c_i, c_vp, c_i64]),
@@ -301,3 +303,22 @@ def mpt_bn_bwd_apply(x, dy, mean, var, gamma, eps, dgamma, dbeta, dx):
     P, C = x.shape
     _check("mpt_bn_bwd_apply", lib().mpt_bn_bwd_apply(_stream(), P, C, _p(x), x.stride(0), _p(dy), dy.stride(0), _p(mean), _p(var),
                                                       _p(gamma), eps, _p(dgamma), _p(dbeta), _p(dx), dx.stride(0)))
+
+
+# ---------------------------------------------------------------- LSTM cell (pointwise part)
+def _ld(t):
+    return 0 if t is None else t.stride(0)
+
+
+def mpt_lstm_cell_fwd(gx, gr, bias, c_prev, act, c, h):
+    _dev(gx, gr, bias, c_prev, act, c, h)
+    B, H = c_prev.shape
+    _check("mpt_lstm_cell_fwd", lib().mpt_lstm_cell_fwd(_stream(), B, H, _p(gx), _ld(gx), _p(gr), _ld(gr), _p(bias), _p(c_prev), _ld(c_prev),
+                                                        _p(act), _ld(act), _p(c), _ld(c), _p(h), _ld(h)))
+
+
+def mpt_lstm_cell_bwd(dh, dc_next, act, c, c_prev, da, dc_prev):
+    _dev(dh, dc_next, act, c, c_prev, da, dc_prev)
+    B, H = c.shape
+    _check("mpt_lstm_cell_bwd", lib().mpt_lstm_cell_bwd(_stream(), B, H, _p(dh), _ld(dh), _p(dc_next), _ld(dc_next), _p(act), _ld(act), _p(c), _ld(c),
+                                                        _p(c_prev), _ld(c_prev), _p(da), _ld(da), _p(dc_prev), _ld(dc_prev)))

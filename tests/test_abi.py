@@ -148,3 +148,20 @@ def test_suggested_scale_matches_the_oracle_for_every_fp16_magnitude(L):
         assert L.mpt_suggest_loss_scale_log2(bits, -99) == max(-24, min(40, k)), bits
     assert L.mpt_suggest_loss_scale_log2(0, -99) == -99 and L.mpt_suggest_loss_scale_log2(0x7C00, 7) == 7
     assert L.mpt_suggest_loss_scale_log2(0x8000 | 0x3C00, 0) == 15          # the sign bit is ignored: |-1.0|
+
+
+def test_lstm_cell_argument_errors(L):
+    P, Z, odd = ctypes.c_void_p(0x1000), ctypes.c_void_p(0), ctypes.c_void_p(0x1001)
+    i64 = ctypes.c_int64
+    f = L.mpt_lstm_cell_fwd
+    f.restype = ctypes.c_int
+    f.argtypes = [ctypes.c_void_p, i64, i64] + [ctypes.c_void_p, i64, ctypes.c_void_p, i64, ctypes.c_void_p, ctypes.c_void_p, i64] + [ctypes.c_void_p, i64] * 3
+    assert f(Z, 4, 8, Z, 32, P, 32, Z, P, 8, P, 32, P, 8, P, 8) == -1
+    assert f(Z, 4, 8, P, 31, P, 32, Z, P, 8, P, 32, P, 8, P, 8) == -2
+    assert f(Z, 0, 8, P, 32, P, 32, Z, P, 8, P, 32, P, 8, P, 8) == -2
+    assert f(Z, 4, 8, P, 32, odd, 32, Z, P, 8, P, 32, P, 8, P, 8) == -3
+    b = L.mpt_lstm_cell_bwd
+    b.restype = ctypes.c_int
+    b.argtypes = [ctypes.c_void_p, i64, i64] + [ctypes.c_void_p, i64] * 7
+    assert b(Z, 4, 8, Z, 8, Z, 0, P, 32, P, 8, P, 8, P, 32, P, 8) == -1
+    assert b(Z, 4, 8, P, 8, Z, 0, P, 32, P, 8, P, 8, P, 16, P, 8) == -2
