@@ -463,7 +463,7 @@ __device__ __forceinline__ uint2v lds_read_tr_b64(uint32_t addr) {
 // index l%16 and reduction indices 8*(l/16) .. +7.  Per-lane byte offsets inside an operand's stage are fixed for the
 // whole kernel: RC fragments need one (a 16-byte chunk), OC fragments two (reduction rows +0..3 and +4..7, one
 // transposing read each).
-template <bool RC>
+template <bool RC, int BO = 256>
 struct FragAddr {
   uint32_t off[RC ? 1 : 2];
   __device__ __forceinline__ void init(int outer0, int lane) {
@@ -477,7 +477,7 @@ struct FragAddr {
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
         const int r = ((lane >> 4) << 3) + 4 * h + ((lane & 15) >> 2);
-        off[h] = r * 512 + ((unit ^ oc_key(r)) << 5) + sub;
+        off[h] = r * (BO * 2) + ((unit ^ (oc_key(r) & (BO / 16 - 1))) << 5) + sub;
       }
     }
   }
@@ -663,23 +663,26 @@ __global__ __launch_bounds__(512) void k_gemm_dma(DmaMat A, DmaMat B, Problem pb
 // wavefront per SIMD nothing else covers a stall, so everything is software-pipelined inside the wavefront:
 // a stage is 8 steps (one A block against the 8 B blocks); step a requests A block a+2 (wrapping into the next stage),
 // steps 4-7 also request the next stage's B blocks, and every step issues one of the wavefront's 8 LDS-direct loads.
-template <bool RC>
+template <bool RC, int BO = 256>
 struct DmaOperand4 {
-  const uint16_t* p[4];     // this lane's source for its four 1 KiB blocks of stage 0
+  static constexpr int NB = BO / 64;   // 1 KiB blocks per wavefront per stage (the operand stage is BO x 32 halves)
+  const uint16_t* p[NB];    // this lane's source for its blocks of stage 0
   int64_t step;             // elements to advance per stage
   __device__ __forceinline__ void init(const DmaMat& m, int o0, int r0, int wave, int lane) {
     if constexpr (RC) {
-      const int row = wave * 64 + (lane >> 2);                       // blocks 4w .. 4w+3 hold 16 rows each
+      const int row = wave * (BO / 4) + (lane >> 2);                 // blocks NB*w .. hold 16 rows each
       const int chunk = (lane & 3) ^ ((row >> 1) & 3);               // same for row + 16k
 #pragma unroll
-      for (int k = 0; k < 4; ++k) p[k] = m.base + (int64_t)(o0 + row + 16 * k) * m.ld + r0 + chunk * 8;
+      for (int k = 0; k < NB; ++k) p[k] = m.base + (int64_t)(o0 + row + 16 * k) * m.ld + r0 + chunk * 8;
       step = 32;
     } else {
-      const int pc = lane & 31;
+      constexpr int RPB = 512 / BO;                                  // reduction rows per 1 KiB block (rows of BO*2 bytes)
+      constexpr int LPR = 64 / RPB;                                  // lanes per reduction row
+      const int pc = lane % LPR;
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const int row = wave * 8 + 2 * k + (lane >> 5);              // blocks 4w .. 4w+3 hold 2 reduction rows each
-        const int c = 2 * ((pc >> 1) ^ oc_key(row)) + (pc & 1);
+      for (int k = 0; k < NB; ++k) {
+        const int row = (wave * NB + k) * RPB + lane / LPR;
+        const int c = 2 * ((pc >> 1) ^ (oc_key(row) & (BO / 16 - 1))) + (pc & 1);
         p[k] = m.base + (int64_t)(r0 + row) * m.ld + o0 + c * 8;
       }
       step = 32 * m.ld;
@@ -710,93 +713,130 @@ __device__ __forceinline__ void wait_frags9(half8& f, half8 (&g)[8]) {
                : "memory");
 }
 
-template <bool A_RC, bool B_RC>
+template <bool A_RC, bool B_RC, int BM>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_gemm_dma4(DmaMat A, DmaMat B, Problem pb, Epilogue ep) {
-  constexpr int NSTAGE = 4, AHEAD = 3, OPERAND = 256 * 64, STAGE = 2 * OPERAND;
+  // BM = 256: tile 256 x 256, 128 x 128 per wavefront.  BM = 128: tile 128 x 256, 64 x 128 per wavefront, for problems
+  // with too few 256-row tiles to occupy the chip (batch-256 recurrent and gate products).
+  static_assert(BM == 256 || BM == 128, "tile rows");
+  constexpr int NA = BM / 32;                      // A blocks per wavefront = steps per stage
+  constexpr int HALF = NA / 2;                     // the barrier sits before step HALF
+  constexpr int LA = BM / 64, LB = 4;              // LDS-direct loads per wavefront per stage: A blocks, B blocks
+  constexpr int NBQ = 8 / HALF;                    // B fragments requested per late step
+  constexpr int LBQ = LB / HALF;                   // B loads issued per early step
+  constexpr int NSTAGE = 4, AHEAD = 3, A_BYTES = BM * 64, B_BYTES = 256 * 64, STAGE = A_BYTES + B_BYTES;
   constexpr int RA1 = A_RC ? 1 : 2, RB1 = B_RC ? 1 : 2;               // LDS read instructions per fragment
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   const int t = threadIdx.x, lane = t & 63, wave = __builtin_amdgcn_readfirstlane(t >> 6);
   const int wm = wave >> 1, wn = wave & 1;
   int ti, tj, sp;
   tile_of(pb, blockIdx.x, ti, tj, sp);
-  const int i0 = ti * 256, j0 = tj * 256;
+  const int i0 = ti * BM, j0 = tj * 256;
   const int st_total = pb.R / 32;
   const int st_begin = sp * pb.ktiles_per_split * 2;
-  const int nst = min(pb.ktiles_per_split * 2, st_total - st_begin);   // stages this workgroup reduces over (>= 1)
+  const int nst = min(pb.ktiles_per_split * 2, st_total - st_begin);   // stages this workgroup reduces over (even, >= 2)
 
-  float4v acc[8][8];
+  float4v acc[NA][8];
 #pragma unroll
-  for (int a = 0; a < 8; ++a)
+  for (int a = 0; a < NA; ++a)
 #pragma unroll
     for (int b = 0; b < 8; ++b)
 #pragma unroll
       for (int v = 0; v < 4; ++v) acc[a][b][v] = 0.f;
 
-  DmaOperand4<A_RC> da;
-  DmaOperand4<B_RC> db;
+  DmaOperand4<A_RC, BM> da;
+  DmaOperand4<B_RC, 256> db;
   da.init(A, i0, st_begin * 32, wave, lane);
   db.init(B, j0, st_begin * 32, wave, lane);
-  const int blk = wave * 4096;                                         // this wavefront's four 1 KiB blocks inside an operand stage
-  // load q (0-3: A blocks, 4-7: B blocks) of stage s; past the end: refetch the last slice into a free slot
+  // load q (0 .. LA-1: A blocks, then the B blocks) of stage s; past the end: refetch the last slice into a free slot
   auto issue1 = [&](int s, auto qc) {
     constexpr int q = decltype(qc)::value;
     const int sc = min(s, nst - 1);
     char* st = lds + (s % NSTAGE) * STAGE;
-    if constexpr (q < 4) da.template issue<q>(sc, st + blk);
-    else db.template issue<q - 4>(sc, st + OPERAND + blk);
+    if constexpr (q < LA) da.template issue<q>(sc, st + wave * (LA * 1024));
+    else db.template issue<q - LA>(sc, st + A_BYTES + wave * (LB * 1024));
   };
-  FragAddr<A_RC> aa[8];
-  FragAddr<B_RC> ab[8];
+  FragAddr<A_RC, BM> aa[NA];
+  FragAddr<B_RC, 256> ab[8];
 #pragma unroll
-  for (int a = 0; a < 8; ++a) aa[a].init(wm * 128 + a * 16, lane);
+  for (int a = 0; a < NA; ++a) aa[a].init(wm * (BM / 2) + a * 16, lane);
 #pragma unroll
   for (int b = 0; b < 8; ++b) ab[b].init(wn * 128 + b * 16, lane);
   const uint32_t lds0 = lds_offset(lds);
-  half8 fa[8], fb[2][8];                                               // A blocks of the running stage(s); B blocks, double buffered
+  half8 fa[NA], fb[2][8];                                              // A blocks of the running stage(s); B blocks, double buffered
   auto stage_base = [&](int s) { return lds0 + (uint32_t)((s % NSTAGE) * STAGE); };
+  auto issue_all = [&](int s, auto lo, auto hi) {                      // loads lo .. hi-1 of stage s
+    constexpr int L = decltype(lo)::value, Hh = decltype(hi)::value;
+    if constexpr (L + 0 < Hh) issue1(s, std::integral_constant<int, L + 0>{});
+    if constexpr (L + 1 < Hh) issue1(s, std::integral_constant<int, L + 1>{});
+    if constexpr (L + 2 < Hh) issue1(s, std::integral_constant<int, L + 2>{});
+    if constexpr (L + 3 < Hh) issue1(s, std::integral_constant<int, L + 3>{});
+    if constexpr (L + 4 < Hh) issue1(s, std::integral_constant<int, L + 4>{});
+    if constexpr (L + 5 < Hh) issue1(s, std::integral_constant<int, L + 5>{});
+    if constexpr (L + 6 < Hh) issue1(s, std::integral_constant<int, L + 6>{});
+    if constexpr (L + 7 < Hh) issue1(s, std::integral_constant<int, L + 7>{});
+  };
 
-  // prologue: stages 0 and 1 whole, and the A half of stage 2 (the first steps of stage 0 add its B half)
-#define MPT_ISSUE(s, q) issue1((s), std::integral_constant<int, (q)>{})
-  MPT_ISSUE(0, 0); MPT_ISSUE(0, 1); MPT_ISSUE(0, 2); MPT_ISSUE(0, 3); MPT_ISSUE(0, 4); MPT_ISSUE(0, 5); MPT_ISSUE(0, 6); MPT_ISSUE(0, 7);
-  MPT_ISSUE(1, 0); MPT_ISSUE(1, 1); MPT_ISSUE(1, 2); MPT_ISSUE(1, 3); MPT_ISSUE(1, 4); MPT_ISSUE(1, 5); MPT_ISSUE(1, 6); MPT_ISSUE(1, 7);
-  MPT_ISSUE(2, 0); MPT_ISSUE(2, 1); MPT_ISSUE(2, 2); MPT_ISSUE(2, 3);
-  asm volatile("s_waitcnt vmcnt(4)\n\ts_barrier" ::: "memory");        // stages 0 and 1 have landed everywhere
+  // prologue: stages 0 and 1 whole, and the A part of stage 2 (the early steps of stage 0 add its B part)
+  issue_all(0, std::integral_constant<int, 0>{}, std::integral_constant<int, LA + LB>{});
+  issue_all(1, std::integral_constant<int, 0>{}, std::integral_constant<int, LA + LB>{});
+  issue_all(2, std::integral_constant<int, 0>{}, std::integral_constant<int, LA>{});
+  asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(LA) : "memory");     // stages 0 and 1 have landed everywhere
 #pragma unroll
-  for (int b = 0; b < 8; ++b) fb[0][b] = ab[b].read(stage_base(0) + OPERAND);
+  for (int b = 0; b < 8; ++b) fb[0][b] = ab[b].read(stage_base(0) + A_BYTES);
   fa[0] = aa[0].read(stage_base(0));
   fa[1] = aa[1].read(stage_base(0));
 
-  // One step: requests, wait for this step's operands, 8 MFMAs with one LDS-direct load in their middle.
+  // One step: requests, wait for this step's operands, 8 MFMAs with the step's LDS-direct loads among them.
   // LDS reads complete in order, so "A block a has arrived" is "at most W reads issued after it are outstanding";
   // A block a was the last request of step a-2, hence W = reads of steps a-1 and a.  Step 0 also needs the whole
-  // B buffer, whose last request precedes the A requests of steps 7 and 0.
+  // B buffer, whose last request precedes the A requests of the last step and of step 0.
   auto step = [&](int s, auto ac, half8 (&fb_cur)[8], half8 (&fb_nxt)[8]) {
     constexpr int a = decltype(ac)::value;
-    if constexpr (a == 4) {
+    if constexpr (a == HALF) {
       // Stage s+1 is about to be read and the slot of stage s-1 about to be refilled: every wavefront's loads of
-      // stage s+1 must have landed (only the 8 loads of stage s+2 may be in flight) and every wavefront must be
+      // stage s+1 must have landed (only the loads of stage s+2 may be in flight) and every wavefront must be
       // past stage s-1, all of whose reads were consumed by MFMAs already issued.
-      asm volatile("s_waitcnt vmcnt(8)\n\ts_barrier" ::: "memory");
+      asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(LA + LB) : "memory");
     }
-    if constexpr (a >= 4) {
-      fb_nxt[2 * (a - 4)] = ab[2 * (a - 4)].read(stage_base(s + 1) + OPERAND);
-      fb_nxt[2 * (a - 4) + 1] = ab[2 * (a - 4) + 1].read(stage_base(s + 1) + OPERAND);
+    if constexpr (a >= HALF) {
+#pragma unroll
+      for (int k = 0; k < NBQ; ++k) fb_nxt[NBQ * (a - HALF) + k] = ab[NBQ * (a - HALF) + k].read(stage_base(s + 1) + A_BYTES);
     }
-    constexpr int na = (a + 2) & 7;
-    fa[na] = aa[na].read(stage_base(s + ((a + 2) >> 3)));              // steps 6, 7 read the next stage (published at step 4)
+    constexpr int na = (a + 2) % NA;
+    fa[na] = aa[na].read(stage_base(s + (a + 2) / NA));                // the last two steps read the next stage (published at step HALF)
     __builtin_amdgcn_sched_barrier(0);
-    constexpr int W = a < 4 ? 2 * RA1 : (a == 4 ? 2 * RA1 + 2 * RB1 : 2 * RA1 + 4 * RB1);
+    constexpr int N_PREV = RA1 + ((a - 1 >= HALF) ? NBQ * RB1 : 0);    // reads of step a-1 (for a >= 1)
+    constexpr int N_THIS = RA1 + ((a >= HALF) ? NBQ * RB1 : 0);
+    constexpr int W = a == 0 ? 2 * RA1 : N_PREV + N_THIS;
     if constexpr (a == 0) wait_frags9<W>(fa[0], fb_cur);
     else wait_frag1<W>(fa[a]);
 #pragma unroll
     for (int b = 0; b < 8; ++b) {   // operands swapped: each lane ends up with 4 consecutive output columns of one row
       mfma_acc(acc[a][b], fb_cur[b], fa[a]);
-      if (b == 3) {
-        __builtin_amdgcn_sched_barrier(0);
-        // steps 4-7 start stage s+3 (A blocks) into the slot just vacated; steps 0-3 finish stage s+2 (B blocks)
-        if constexpr (a >= 4) issue1(s + AHEAD, std::integral_constant<int, a - 4>{});
-        else issue1(s + AHEAD - 1, std::integral_constant<int, a + 4>{});
-        __builtin_amdgcn_sched_barrier(0);
+      // late steps start stage s+3 (one A block each) into the slot just vacated; early steps finish stage s+2 (B blocks)
+      if constexpr (a >= HALF) {
+        if (b == 3) {
+          __builtin_amdgcn_sched_barrier(0);
+          issue1(s + AHEAD, std::integral_constant<int, a - HALF>{});
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      } else if constexpr (LBQ == 1) {
+        if (b == 3) {
+          __builtin_amdgcn_sched_barrier(0);
+          issue1(s + AHEAD - 1, std::integral_constant<int, LA + a>{});
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      } else {
+        if (b == 1) {
+          __builtin_amdgcn_sched_barrier(0);
+          issue1(s + AHEAD - 1, std::integral_constant<int, LA + 2 * a>{});
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        if (b == 5) {
+          __builtin_amdgcn_sched_barrier(0);
+          issue1(s + AHEAD - 1, std::integral_constant<int, LA + 2 * a + 1>{});
+          __builtin_amdgcn_sched_barrier(0);
+        }
       }
     }
     __builtin_amdgcn_sched_barrier(0);
@@ -806,12 +846,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     step(s, std::integral_constant<int, 1>{}, fb_cur, fb_nxt);
     step(s, std::integral_constant<int, 2>{}, fb_cur, fb_nxt);
     step(s, std::integral_constant<int, 3>{}, fb_cur, fb_nxt);
-    step(s, std::integral_constant<int, 4>{}, fb_cur, fb_nxt);
-    step(s, std::integral_constant<int, 5>{}, fb_cur, fb_nxt);
-    step(s, std::integral_constant<int, 6>{}, fb_cur, fb_nxt);
-    step(s, std::integral_constant<int, 7>{}, fb_cur, fb_nxt);
+    if constexpr (NA == 8) {
+      step(s, std::integral_constant<int, 4 % NA>{}, fb_cur, fb_nxt);
+      step(s, std::integral_constant<int, 5 % NA>{}, fb_cur, fb_nxt);
+      step(s, std::integral_constant<int, 6 % NA>{}, fb_cur, fb_nxt);
+      step(s, std::integral_constant<int, 7 % NA>{}, fb_cur, fb_nxt);
+    }
   };
-#undef MPT_ISSUE
   // nst is even: the reduction length is a multiple of 64 and splits are cut at multiples of 64
   for (int s = 0; s < nst; s += 2) {
     one_stage(s, fb[0], fb[1]);
@@ -823,17 +864,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 
   // ---- epilogue (whole tiles, FP16 store with optional Inf/NaN vote; the host sends only unsplit problems with a
   // 16-byte aligned output and ld % 8 == 0 here).
-  // acc[a][b][e]: row i = 16a + lane%16, column j = 16b + 4*(lane/16) + e of the wavefront's 128 x 128 block.
+  // acc[a][b][e]: row i = 16a + lane%16, column j = 16b + 4*(lane/16) + e of the wavefront's (BM/2) x 128 block.
   bool bad = false;
   {
     // FP16 store through LDS, so that global stores are whole 256-byte row segments instead of 32-byte pieces:
-    // each wavefront rounds its block to FP16 into its own 32 KiB of the (now idle) ring as [128 rows][256 B],
+    // each wavefront rounds its block to FP16 into its own part of the (now idle) ring as [BM/2 rows][256 B],
     // 16-byte unit u of row r kept at unit u ^ (r & 15), then streams it out 16 bytes per lane, 16 lanes per row.
     __syncthreads();                                                   // every wavefront is done reading the ring
-    char* mine = lds + wave * 32768;
+    char* mine = lds + wave * (BM / 2 * 256);
     const int li = lane & 15, lg = lane >> 4;
 #pragma unroll
-    for (int a = 0; a < 8; ++a)
+    for (int a = 0; a < NA; ++a)
 #pragma unroll
       for (int b = 0; b < 8; ++b) {
         asm volatile("" : "+a"(acc[a][b]) : : "memory");              // keeps the copy out of the accumulation registers here, one block at a time
@@ -842,9 +883,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         for (int e = 0; e < 4; ++e) h[e] = (_Float16)acc[a][b][e];
         *reinterpret_cast<half4*>(mine + (a * 16 + li) * 256 + (((2 * b + (lg >> 1)) ^ li) << 4) + (lg & 1) * 8) = h;
       }
-    uint16_t* out = reinterpret_cast<uint16_t*>(ep.out) + (int64_t)(i0 + wm * 128) * ep.ld + j0 + wn * 128 + li * 8;
+    uint16_t* out = reinterpret_cast<uint16_t*>(ep.out) + (int64_t)(i0 + wm * (BM / 2)) * ep.ld + j0 + wn * 128 + li * 8;
 #pragma unroll 8
-    for (int it = 0; it < 32; ++it) {
+    for (int it = 0; it < BM / 8; ++it) {
       const int r = it * 4 + lg;
       uint4v q = *reinterpret_cast<const uint4v*>(mine + r * 256 + ((li ^ (r & 15)) << 4));
       if (ep.act == 1) {
@@ -852,7 +893,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         for (int e = 0; e < 4; ++e)
           q[e] &= (half_bits_positive(q[e]) ? 0x0000FFFFu : 0u) | (half_bits_positive(q[e] >> 16) ? 0xFFFF0000u : 0u);
       } else if (ep.act == 2) {                                        // the host sends only 16-byte aligned masks with ldmask % 8 == 0 here
-        const uint4v m = *reinterpret_cast<const uint4v*>(ep.mask + (int64_t)(i0 + wm * 128 + r) * ep.ldmask + j0 + wn * 128 + li * 8);
+        const uint4v m = *reinterpret_cast<const uint4v*>(ep.mask + (int64_t)(i0 + wm * (BM / 2) + r) * ep.ldmask + j0 + wn * 128 + li * 8);
 #pragma unroll
         for (int e = 0; e < 4; ++e)
           q[e] &= (half_bits_positive(m[e]) ? 0x0000FFFFu : 0u) | (half_bits_positive(m[e] >> 16) ? 0xFFFF0000u : 0u);
@@ -978,7 +1019,7 @@ bool try_launch_dma(hipStream_t s, const AView& A, const BView& B, bool aligned,
     static const int nstage = mpt_env_int("MPT_GEMM_STAGES", 4);          // 4 or 5 ring slots of 32 KiB (tuning only)
     auto k4 = k_gemm_dma<DmaKind<AView>::rc, DmaKind<BView>::rc, 4>;
     auto k5 = k_gemm_dma<DmaKind<AView>::rc, DmaKind<BView>::rc, 5>;
-    auto kw4 = k_gemm_dma4<DmaKind<AView>::rc, DmaKind<BView>::rc>;
+    auto kw4 = k_gemm_dma4<DmaKind<AView>::rc, DmaKind<BView>::rc, 256>;
     static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(k4), hipFuncAttributeMaxDynamicSharedMemorySize, 4 * 32768),
                         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k5), hipFuncAttributeMaxDynamicSharedMemorySize, 5 * 32768),
                         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kw4), hipFuncAttributeMaxDynamicSharedMemorySize, 4 * 32768), true);
@@ -999,17 +1040,43 @@ bool try_launch_dma(hipStream_t s, const AView& A, const BView& B, bool aligned,
   }
 }
 
+// Problems with few 256-row tiles but many 128 x 256 ones (a batch-256 product against a wide weight matrix): one
+// unsplit launch of the 128-row variant of the one-wavefront-per-SIMD kernel fills the chip where 256 x 256 tiles
+// leave half of it idle; a workspace, if given, is not needed then.
+template <class AView, class BView>
+bool try_launch_dma128(hipStream_t s, const AView& A, const BView& B, bool aligned, int I, int J, int R, const Epilogue& ep, int& status) {
+  if constexpr (DmaKind<AView>::ok && DmaKind<BView>::ok) {
+    static const bool enabled = mpt_env_int("MPT_GEMM_STREAMED", 1) != 0 && mpt_env_int("MPT_GEMM_WAVES", 4) == 4 &&
+                                mpt_env_int("MPT_GEMM_TILE128", 1) != 0;
+    if (!enabled || !aligned || (I % 128) || (J % 256) || (R % 64) || ep.mode != 0) return false;
+    if ((ep.ld % 8) || !mpt_aligned(ep.out, 16) || (ep.act == 2 && ((ep.ldmask % 8) || !mpt_aligned(ep.mask, 16)))) return false;
+    const int64_t t256 = ((int64_t)(I + 255) / 256) * (J / 256), t128 = (int64_t)(I / 128) * (J / 256);
+    if (t256 >= kCUs * 3 / 4 || t128 < kCUs * 3 / 8) return false;
+    auto k = k_gemm_dma4<DmaKind<AView>::rc, DmaKind<BView>::rc, 128>;
+    constexpr int lds = 4 * (128 + 256) * 64;
+    static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, lds), true);
+    (void)once;
+    Problem pb{I, J, R, I / 128, J / 256, 1, R / 64};
+    hipLaunchKernelGGL(k, dim3((unsigned)t128), dim3(256), lds, s, DmaMat{A.base, A.ld}, DmaMat{B.base, B.ld}, pb, ep);
+    status = hipGetLastError() == hipSuccess ? MPT_OK : MPT_ERR_HIP;
+    return true;
+  } else {
+    return false;
+  }
+}
+
 // Run one contraction: single pass, or split partials + ordered reduction.
 template <class AView, class BView>
 int run(hipStream_t s, const AView& A, const BView& B, bool a_aligned, bool b_aligned, int I, int J, int R, Epilogue ep, void* ws, size_t ws_bytes) {
   const bool aligned = a_aligned && b_aligned;
   const Plan pl = make_plan(I, J, R, ws != nullptr);
   if (ws != nullptr && ws_bytes < plan_ws_bytes(pl, I, J)) return MPT_ERR_WORKSPACE;
+  int st = MPT_OK;
+  if (try_launch_dma128(s, A, B, aligned, I, J, R, ep, st)) return st;
   Epilogue first = ep;
   if (pl.splits > 1) {
     first.out = ws; first.ld = J; first.mode = 3; first.flag = nullptr;
   }
-  int st = MPT_OK;
   if (!try_launch_dma(s, A, B, aligned, pl, I, J, R, first, st))
     st = a_aligned ? (b_aligned ? launch_tiles<AView, BView, true, true>(s, A, B, pl, I, J, R, first)
                                 : launch_tiles<AView, BView, true, false>(s, A, B, pl, I, J, R, first))

@@ -259,3 +259,41 @@ def test_relu_folded_whole_tile_kernels():
         got = host16(dX)
         gemm_check(got, dx, sa, s, "dgrad_relu mask pad %d" % pad)
         assert not got[mask <= 0].any()
+
+
+def test_outputs_with_few_rows_and_many_columns():
+    """384 x 16384 outputs (three 128-row tiles by 64 column tiles): the 128-row whole-tile kernel, in all three
+    passes, with the folded ReLU forms and the overflow vote."""
+    I, J = 384, 16384
+    rng = np.random.default_rng(21)
+    for K in (64, 192):
+        X = rng.standard_normal((I, K)).astype(np.float16)
+        W = (rng.standard_normal((K, J)) * 0.05).astype(np.float16)
+        y, sa, s = gemm.gemm_fwd(X, W, full=True)
+        gemm_check(run_fwd(X, W), y, sa, s, "fwd K %d" % K)
+        dY = (np.exp2(rng.uniform(-20, -3, (I, K))) * rng.choice([-1, 1], (I, K))).astype(np.float16)
+        Wd = (rng.standard_normal((J, K)) * 0.05).astype(np.float16)
+        dx, sa, s = gemm.gemm_dgrad(dY, Wd, full=True)
+        gemm_check(run_dgrad(dY, Wd), dx, sa, s, "dgrad K %d" % K)
+        Xw = rng.standard_normal((K, I)).astype(np.float16)
+        dYw = (np.exp2(rng.uniform(-20, -3, (K, J))) * rng.choice([-1, 1], (K, J))).astype(np.float16)
+        dw, sa, s = gemm.gemm_wgrad(Xw, dYw, full=True)
+        gemm_check(run_wgrad(Xw, dYw), dw, sa, s, "wgrad K %d" % K)
+    H = torch.full((I, J), float("nan"), dtype=torch.float16, device="cuda")
+    mpt.mpt_gemm_fwd_relu(dev16(X), dev16(W), H)
+    h, sa, s = gemm.gemm_fwd_relu(X, W, full=True)
+    gemm_check(host16(H), h, sa, s, "fwd_relu")
+    mask = np.maximum(rng.standard_normal((I, J)), 0).astype(np.float16)
+    dX = torch.full((I, J), float("nan"), dtype=torch.float16, device="cuda")
+    mpt.mpt_gemm_dgrad_relu(dev16(dY), dev16(Wd), dev16(mask), dX)
+    dx, sa, s = gemm.gemm_dgrad_relu(dY, Wd, mask, full=True)
+    got = host16(dX)
+    gemm_check(got, dx, sa, s, "dgrad_relu")
+    assert not got[mask <= 0].any()
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    Xo = np.full((64, I), 2.0 ** -3, dtype=np.float16); dYo = np.full((64, J), 2.0 ** -3, dtype=np.float16)
+    run_wgrad(Xo, dYo, flag=flag)
+    assert int(flag.item()) == 0
+    Xo[:, I - 1] = 300.0; dYo[:, J - 1] = 300.0
+    dW = run_wgrad(Xo, dYo, flag=flag)
+    assert fp16.bits(dW)[I - 1, J - 1] == 0x7C00 and int(flag.item()) == 1
