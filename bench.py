@@ -27,8 +27,8 @@ HBM_PEAK_GBS = 8000.0             # MI355X HBM3E peak
 N_SQUARE = 4096
 N_FLAT = 116_000_000
 # HBM traffic per GEMM launch (bytes) from rocprofv3 FETCH_SIZE/WRITE_SIZE counter runs, scaled by the
-# same counters on a copy kernel of known size; see profiles/k_gemm_dma_and_update_hbm_traffic.md.
-GEMM_TRAFFIC_BYTES = 235.4e6      # 201.8 MB read + 33.6 MB written per 4096^3 launch
+# same counters on a copy kernel of known size; see profiles/k_gemm_dma4_and_update_hbm_traffic.md.
+GEMM_TRAFFIC_BYTES = 235.3e6      # 201.7 MB read + 33.6 MB written per 4096^3 launch
 UPDATE_TRAFFIC_BYTES = 2320.0e6   # 1160 MB read + 1160 MB written per 116M-element launch
 
 
