@@ -288,7 +288,7 @@ __device__ __forceinline__ float wave_sum(float v) {
 template <int WAVES, int NCH, bool VEC>
 __global__ __launch_bounds__((WAVES * 64 > kThreads ? WAVES * 64 : kThreads)) void k_softmax_xent_rows(
     int64_t B, int64_t C, const uint16_t* __restrict__ logits, int64_t ldl, const int32_t* __restrict__ labels,
-    float factor, uint16_t* __restrict__ dlogits, int64_t ldd, float* __restrict__ row_loss) {
+    float factor, uint16_t* __restrict__ dlogits, int64_t ldd, float* __restrict__ row_loss, bool stream) {
   constexpr int NT = WAVES * 64 > kThreads ? WAVES * 64 : kThreads;   // threads per workgroup
   constexpr int T = 64 * WAVES;                                        // threads per row
   __shared__ float red[NT / 64];
@@ -305,7 +305,7 @@ __global__ __launch_bounds__((WAVES * 64 > kThreads ? WAVES * 64 : kThreads)) vo
 #pragma unroll
     for (int e = 0; e < 8; ++e) q[i][e] = (_Float16)(-INFINITY);
     if constexpr (VEC) {
-      if (live && c0 < C) q[i] = *reinterpret_cast<const h8*>(z + c0);
+      if (live && c0 < C) q[i] = stream ? __builtin_nontemporal_load(reinterpret_cast<const h8*>(z + c0)) : *reinterpret_cast<const h8*>(z + c0);
     } else {
 #pragma unroll
       for (int e = 0; e < 8; ++e)
@@ -330,11 +330,19 @@ __global__ __launch_bounds__((WAVES * 64 > kThreads ? WAVES * 64 : kThreads)) vo
   mx = across(mx, true);
   constexpr float kLog2e = 1.44269504088896340736f;
   auto ex = [&](_Float16 h) { return __builtin_amdgcn_exp2f(__fmul_rn(__fsub_rn((float)h, mx), kLog2e)); };   // exp(-inf) = 0 for the padding
+  // With few chunks per lane the exponentials are kept in registers for the output pass (the kernel is close to
+  // ALU-bound: two evaluations per element cost a quarter of its instructions); with many they are recomputed.
+  constexpr bool KEEP = NCH <= 4;
+  float ev[KEEP ? NCH : 1][8];
   float sum = 0.f;
 #pragma unroll
   for (int i = 0; i < NCH; ++i)
 #pragma unroll
-    for (int e = 0; e < 8; ++e) sum = __fadd_rn(sum, ex(q[i][e]));
+    for (int e = 0; e < 8; ++e) {
+      const float x = ex(q[i][e]);
+      if constexpr (KEEP) ev[i][e] = x;
+      sum = __fadd_rn(sum, x);
+    }
   sum = across(sum, false);
   if (!live) return;
   const int32_t lab = labels[row];
@@ -346,11 +354,17 @@ __global__ __launch_bounds__((WAVES * 64 > kThreads ? WAVES * 64 : kThreads)) vo
     h8 o;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      const float p = __fmul_rn(ex(q[i][e]), inv);
+      float x;
+      if constexpr (KEEP) x = ev[i][e];
+      else x = ex(q[i][e]);
+      const float p = __fmul_rn(x, inv);
       o[e] = (_Float16)__fmul_rn(__fsub_rn(p, (c0 + e == lab) ? 1.0f : 0.0f), factor);
     }
     if constexpr (VEC) {
-      if (c0 < C) *reinterpret_cast<h8*>(d + c0) = o;
+      if (c0 < C) {
+        if (stream) __builtin_nontemporal_store(o, reinterpret_cast<h8*>(d + c0));
+        else *reinterpret_cast<h8*>(d + c0) = o;
+      }
     } else {
 #pragma unroll
       for (int e = 0; e < 8; ++e)
@@ -582,20 +596,21 @@ extern "C" int mpt_softmax_xent_scaled(void* stream, int64_t B, int64_t C, const
   hipStream_t s = static_cast<hipStream_t>(stream);
   const float factor = scale / (float)B;
   const bool vec = mpt_aligned(logits, 16) && mpt_aligned(dlogits, 16) && (ldl % 8) == 0 && (ldd % 8) == 0 && (C % 8) == 0;
+  const bool nontemporal = B * C * 2 > (192LL << 20);   // beyond the memory-side cache
 #define MPT_SM_LAUNCH(WAVES, NCH)                                                                                                   \
   do {                                                                                                                              \
     constexpr unsigned nt = WAVES * 64 > kThreads ? WAVES * 64 : kThreads;                                                          \
     const unsigned rows = nt / (64 * WAVES);                                                                                        \
     const unsigned grid = (unsigned)((B + rows - 1) / rows);                                                                        \
     if (vec) hipLaunchKernelGGL((k_softmax_xent_rows<WAVES, NCH, true>), dim3(grid), dim3(nt), 0, s, B, C, logits, ldl, labels,     \
-                                factor, dlogits, ldd, row_loss);                                                                    \
+                                factor, dlogits, ldd, row_loss, nontemporal);                                                       \
     else hipLaunchKernelGGL((k_softmax_xent_rows<WAVES, NCH, false>), dim3(grid), dim3(nt), 0, s, B, C, logits, ldl, labels,        \
-                            factor, dlogits, ldd, row_loss);                                                                        \
+                            factor, dlogits, ldd, row_loss, nontemporal);                                                           \
   } while (0)
   if (C <= 512) MPT_SM_LAUNCH(1, 1);
   else if (C <= 2048) MPT_SM_LAUNCH(1, 4);
   else if (C <= 8192) MPT_SM_LAUNCH(4, 4);
-  else if (C <= 32768) MPT_SM_LAUNCH(16, 4);
+  else if (C <= 32768) MPT_SM_LAUNCH(16, 4);      // measured: 16 wavefronts x 4 chunks 5.0 TB/s, 4 x 16 4.4 TB/s
   else if (C <= 65536) MPT_SM_LAUNCH(16, 8);
   else if (vec) hipLaunchKernelGGL(k_softmax_xent_long<true>, dim3((unsigned)B), dim3(1024), 0, s, B, C, logits, ldl, labels, factor, dlogits, ldd, row_loss);
   else hipLaunchKernelGGL(k_softmax_xent_long<false>, dim3((unsigned)B), dim3(1024), 0, s, B, C, logits, ldl, labels, factor, dlogits, ldd, row_loss);
