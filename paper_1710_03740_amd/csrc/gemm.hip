@@ -2,8 +2,15 @@
 // (paper Sec. 3.3), for the three passes of a layer (Sec. 3.1 / Fig. 1) and for
 // the 3x3 convolution as an implicit GEMM.  gfx950 only.
 //
-// One kernel template computes C[i,j] = sum_r A(i,r) * B(r,j) on a BM x BN tile
-// per workgroup with v_mfma_f32_32x32x16_f16.  Operands differ only in how a
+// Three kernels compute C[i,j] = sum_r A(i,r) * B(r,j):
+//   k_gemm       the general one: any shape, alignment and operand view (plain matrices, gathered image windows,
+//                filter slices), FP16 / FP32 / accumulating stores, split partials;
+//   k_gemm_dma4  whole 256 x 256 (or 128 x 256) tiles of aligned plain matrices with an FP16 store: operands
+//                streamed global -> LDS, one wavefront per SIMD;
+//   k_gemm_dma   the same streaming with two wavefronts per SIMD, for split partials and odd output strides.
+// k_gemm_dma4 is the one the square 4096^3 workload runs on.
+//
+// k_gemm works on a BM x BN tile per workgroup with v_mfma_f32_32x32x16_f16.  Operands differ only in how a
 // tile is fetched:
 //   * "RC" operands are contiguous along the reduction index r: a thread fetches
 //     16-byte chunks of 8 r-values and stores them to LDS unchanged;
@@ -389,7 +396,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void k_gemm(AView A, BV
 }
 
 // ---------------------------------------------------------------- streamed variant for whole 256x256 tiles of plain matrices
-// Same contraction, same tile and MFMA, but operand slices go global -> LDS with the LDS-direct load
+// Same contraction and tile on v_mfma_f32_16x16x32_f16 blocks, but operand slices go global -> LDS with the LDS-direct load
 // (global_load_lds_dwordx4: no staging registers), through a ring of four 32 KiB stages of reduction depth 32,
 // three of them in flight.  The two wavefronts that share a SIMD run half a stage apart (wavefronts 4-7 take the
 // per-stage barrier in the middle of their stage), so one of them always has MFMAs to issue while the other sits
@@ -663,6 +670,7 @@ __global__ __launch_bounds__(512) void k_gemm_dma(DmaMat A, DmaMat B, Problem pb
 // wavefront per SIMD nothing else covers a stall, so everything is software-pipelined inside the wavefront:
 // a stage is 8 steps (one A block against the 8 B blocks); step a requests A block a+2 (wrapping into the next stage),
 // steps 4-7 also request the next stage's B blocks, and every step issues one of the wavefront's 8 LDS-direct loads.
+// The kernel is also instantiated for a 128-row tile (64 x 128 per wavefront, 4 steps per stage).
 template <bool RC, int BO = 256>
 struct DmaOperand4 {
   static constexpr int NB = BO / 64;   // 1 KiB blocks per wavefront per stage (the operand stage is BO x 32 halves)
