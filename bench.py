@@ -230,14 +230,17 @@ def main():
     gemm_events = []
 
     def step(record):
+        # record = 1: one event pair around the three GEMMs (inside the timed region: the dominant kernel's average launch
+        # duration); record = 2: an event after every GEMM (per-pass breakdown, taken after the timed region, since every
+        # event costs the queue a few microseconds)
         if record:
             ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
             ev[0].record()
         mpt.mpt_gemm_fwd(X, W16, Y)
-        if record:
+        if record == 2:
             ev[1].record()
         mpt.mpt_gemm_dgrad(G, W16, dX)
-        if record:
+        if record == 2:
             ev[2].record()
         mpt.mpt_gemm_wgrad(X, G, dW)
         if record:
@@ -255,13 +258,13 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    preheat(torch, lambda: step(False), args.preheat_ms)
+    preheat(torch, lambda: step(0), args.preheat_ms)
     for _ in range(args.warmup):
-        step(False)
+        step(0)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step(True)
+        step(1)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
@@ -269,14 +272,19 @@ def main():
     value = flops_step / (ms_per_step * 1e-3) / 1e12
 
     # dominant kernel: average GEMM launch duration from the HIP events recorded inside the timed region
-    durs = [ev[i].elapsed_time(ev[i + 1]) for ev in gemm_events for i in range(3)]
-    gemm_ms = sum(durs) / len(durs)
+    gemm_ms = sum(ev[0].elapsed_time(ev[3]) for ev in gemm_events) / (3 * len(gemm_events))
     achieved = 2.0 * n ** 3 / (gemm_ms * 1e-3) / 1e12
+    timed_events = len(gemm_events)
+    for _ in range(20):                                  # per-pass breakdown, outside the timed region
+        step(2)
+    torch.cuda.synchronize()
+    per_pass = {k: round(1e3 * sum(ev[i].elapsed_time(ev[i + 1]) for ev in gemm_events[timed_events:]) / 20, 2)
+                for i, k in enumerate(("fwd", "dgrad", "wgrad"))}
     roofline = {"bound": "mfma", "achieved": round(achieved, 1), "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / MFMA_F16_PEAK_TFLOPS, 4), "traffic": GEMM_TRAFFIC_BYTES,
-                "kernel": "k_gemm_dma4: streamed 256x256 tile, 4 wavefronts x 128x128 of 16x16x32 MFMA blocks, K=32 stages (avg of fwd, dgrad, wgrad)", "avg_launch_us": round(gemm_ms * 1e3, 2),
-                "per_pass_us": {k: round(1e3 * sum(ev[i].elapsed_time(ev[i + 1]) for ev in gemm_events) / len(gemm_events), 2)
-                                for i, k in enumerate(("fwd", "dgrad", "wgrad"))}}
+                "kernel": "k_gemm_dma4: streamed 256x256 tile, 4 wavefronts x 128x128 of 16x16x32 MFMA blocks, K=32 stages (avg of fwd, dgrad, wgrad)",
+                "avg_launch_us": round(gemm_ms * 1e3, 2),
+                "per_pass_us_with_event_overhead": per_pass}
 
     # the other half of the metric: fused master update on the 116M-parameter flat buffer
     del X, G, Y, dX, dW, W32, M32
