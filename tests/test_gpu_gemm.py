@@ -297,3 +297,46 @@ def test_outputs_with_few_rows_and_many_columns():
     Xo[:, I - 1] = 300.0; dYo[:, J - 1] = 300.0
     dW = run_wgrad(Xo, dYo, flag=flag)
     assert fp16.bits(dW)[I - 1, J - 1] == 0x7C00 and int(flag.item()) == 1
+
+
+def test_random_shapes_strides_and_offsets():
+    """A seeded sweep over shapes, leading dimensions and base offsets (every loader and store path of the general
+    kernel, with and without the split workspace), each pass against the oracle."""
+    rng = np.random.default_rng(2024)
+    for case in range(24):
+        M, N, K = (int(v) for v in rng.integers(1, 400, 3))
+        if case % 6 == 0:
+            M, N, K = M * 2 + 256, N + 256, (K // 8 + 1) * 8
+        px, pw, py = (int(v) for v in rng.integers(0, 12, 3))
+        ox, ow, oy = (int(v) for v in rng.integers(0, 5, 3))
+        if case % 3 == 0:
+            px = pw = py = ox = ow = oy = 0                     # contiguous, aligned
+        X = rng.standard_normal((M, K)).astype(np.float16)
+        W = (rng.standard_normal((K, N)) * 0.1).astype(np.float16)
+        dY = (np.exp2(rng.uniform(-18, -2, (M, N))) * rng.choice([-1, 1], (M, N))).astype(np.float16)
+        split = bool(case % 2)
+
+        def view(a, pad, off):
+            buf = torch.zeros((a.shape[0], a.shape[1] + pad + off), dtype=torch.float16, device="cuda")
+            buf[:, off:off + a.shape[1]] = dev16(a)
+            return buf[:, off:off + a.shape[1]]
+
+        def out(rows, cols, pad, off):
+            buf = torch.full((rows, cols + pad + off), 3.0, dtype=torch.float16, device="cuda")
+            return buf, buf[:, off:off + cols]
+
+        label = "case %d M=%d N=%d K=%d pads %s offs %s split %s" % (case, M, N, K, (px, pw, py), (ox, ow, oy), split)
+        yb, yv = out(M, N, py, oy)
+        mpt.mpt_gemm_fwd(view(X, px, ox), view(W, pw, ow), yv, _ws(0, M, N, K) if split else None)
+        y, sa, s = gemm.gemm_fwd(X, W, full=True)
+        got = host16(yb)
+        gemm_check(np.ascontiguousarray(got[:, oy:oy + N]), y, sa, s, "fwd " + label)
+        assert (got[:, :oy] == 3.0).all() and (got[:, oy + N:] == 3.0).all(), label
+        xb, xv = out(M, K, px, ox)
+        mpt.mpt_gemm_dgrad(view(dY, py, oy), view(W, pw, ow), xv, _ws(1, M, N, K) if split else None)
+        dx, sa, s = gemm.gemm_dgrad(dY, W, full=True)
+        gemm_check(np.ascontiguousarray(host16(xb)[:, ox:ox + K]), dx, sa, s, "dgrad " + label)
+        wb, wv = out(K, N, pw, ow)
+        mpt.mpt_gemm_wgrad(view(X, px, ox), view(dY, py, oy), wv, ws=_ws(2, M, N, K) if split else None)
+        dw, sa, s = gemm.gemm_wgrad(X, dY, full=True)
+        gemm_check(np.ascontiguousarray(host16(wb)[:, ow:ow + N]), dw, sa, s, "wgrad " + label)
