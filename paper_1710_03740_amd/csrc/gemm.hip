@@ -39,7 +39,7 @@ constexpr int ROWB = BK * 2;      // bytes per LDS row
 // ---------------------------------------------------------------- exact 32-bit division by an invariant
 struct FastDiv {
   uint32_t d, m, s;               // q = (umulhi(m, n) + n') >> s  (round-up method)
-  FastDiv() : d(1), m(0), s(0) {}
+  __host__ __device__ FastDiv() : d(1), m(0), s(0) {}
   explicit FastDiv(uint32_t div) : d(div) {
     if (div <= 1) { m = 0; s = 0; d = 1; return; }
     uint32_t l = 0;
@@ -671,8 +671,12 @@ __global__ __launch_bounds__(512) void k_gemm_dma(DmaMat A, DmaMat B, Problem pb
 // a stage is 8 steps (one A block against the 8 B blocks); step a requests A block a+2 (wrapping into the next stage),
 // steps 4-7 also request the next stage's B blocks, and every step issues one of the wavefront's 8 LDS-direct loads.
 // The kernel is also instantiated for a 128-row tile (64 x 128 per wavefront, 4 steps per stage).
+// An operand of the one-wavefront-per-SIMD kernel is a policy: Src (what the host passes), kRC (layout kind),
+// init (per-lane constants for this workgroup's tile) and issue<K> (the K-th LDS-direct load of a stage).
 template <bool RC, int BO = 256>
 struct DmaOperand4 {
+  typedef DmaMat Src;
+  static constexpr bool kRC = RC;
   static constexpr int NB = BO / 64;   // 1 KiB blocks per wavefront per stage (the operand stage is BO x 32 halves)
   const uint16_t* p[NB];    // this lane's source for its blocks of stage 0
   int64_t step;             // elements to advance per stage
@@ -702,6 +706,87 @@ struct DmaOperand4 {
   }
 };
 
+// Source of zeros for taps that fall outside the image (an LDS-direct load needs an address to read).
+__device__ __attribute__((aligned(64))) const uint32_t k_zero_line[16] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
+
+// 3x3 convolution, stride 1, pad 1: rows of the implicit matrix are pixels (n, y, x), the reduction index is
+// r = tap * Cc + c with tap = 3*tr + ts; the source pixel is (y + sgn*(tr-1), x + sgn*(ts-1)).  Cc is a multiple of
+// 32, so a stage of 32 r-values is 32 consecutive channels of one tap: per load a lane needs one bounds test and one
+// address.  Reduction-contiguous layout, same LDS image as a plain RC operand.
+struct DmaImgSrc {
+  const uint16_t* base;
+  int H, W, Cc, sgn;
+  FastDiv dHW, dW, dSpt;           // divisions by H*W, W and by the stages per tap (Cc / 32)
+};
+template <int BO>
+struct DmaImgRC {
+  typedef DmaImgSrc Src;
+  static constexpr bool kRC = true;
+  static constexpr int NB = BO / 64;
+  const uint16_t* base;
+  int32_t pix[NB];                 // element offset of the lane's pixel (centre tap) + its 16-byte chunk
+  int32_t yx[NB];                  // y << 16 | x
+  int H, W, Cc, sgn, stage0;
+  FastDiv dSpt;
+  __device__ __forceinline__ void init(const Src& m, int o0, int r0, int wave, int lane) {
+    base = m.base; H = m.H; W = m.W; Cc = m.Cc; sgn = m.sgn; dSpt = m.dSpt; stage0 = r0 >> 5;
+    const int row = wave * (BO / 4) + (lane >> 2);
+    const int chunk = (lane & 3) ^ ((row >> 1) & 3);
+#pragma unroll
+    for (int k = 0; k < NB; ++k) {
+      uint32_t n, rem, y, x;
+      m.dHW.divmod((uint32_t)(o0 + row + 16 * k), n, rem);
+      m.dW.divmod(rem, y, x);
+      pix[k] = (int32_t)(((n * (uint32_t)H + y) * (uint32_t)W + x) * (uint32_t)Cc) + chunk * 8;
+      yx[k] = (int32_t)((y << 16) | x);
+    }
+  }
+  template <int K>
+  __device__ __forceinline__ void issue(int stage_rel, char* lds_blocks) const {
+    uint32_t tap, cs;
+    dSpt.divmod((uint32_t)(stage0 + stage_rel), tap, cs);          // wavefront-uniform
+    const int tr = (int)tap / 3, ts = (int)tap - 3 * tr;
+    const int dy = sgn * (tr - 1), dx = sgn * (ts - 1);
+    const int yy = (yx[K] >> 16) + dy, xx = (yx[K] & 0xFFFF) + dx;
+    const bool inside = (unsigned)yy < (unsigned)H && (unsigned)xx < (unsigned)W;
+    const uint16_t* p = inside ? base + (pix[K] + (dy * W + dx) * Cc + (int)cs * 32) : reinterpret_cast<const uint16_t*>(k_zero_line);
+    __builtin_amdgcn_global_load_lds((global_void_ptr)p, (lds_void_ptr)(lds_blocks + K * 1024), 16, 0, 0);
+  }
+};
+
+// The filter w[k][tap][c] read as B(r = tap * Kf + k, o = c) for the input-gradient pass: outer-contiguous, one
+// reduction row (k, tap) is Cc contiguous channels; Kf is a multiple of 32, so a stage stays inside one tap.
+struct DmaFilterSrc {
+  const uint16_t* base;
+  int Cc, Kf;
+  FastDiv dSpt;                    // stages per tap = Kf / 32
+};
+struct DmaFilterOC {
+  typedef DmaFilterSrc Src;
+  static constexpr bool kRC = false;
+  static constexpr int NB = 4;
+  const uint16_t* p[NB];           // lane's source for reduction row (k = row, tap = 0) of its blocks
+  int Cc, stage0;
+  FastDiv dSpt;
+  __device__ __forceinline__ void init(const Src& m, int o0, int r0, int wave, int lane) {
+    Cc = m.Cc; dSpt = m.dSpt; stage0 = r0 >> 5;
+    const int pc = lane & 31;
+#pragma unroll
+    for (int k = 0; k < NB; ++k) {
+      const int row = (wave * NB + k) * 2 + (lane >> 5);
+      const int c = 2 * ((pc >> 1) ^ oc_key(row)) + (pc & 1);
+      p[k] = m.base + (int64_t)row * 9 * m.Cc + o0 + c * 8;
+    }
+  }
+  template <int K>
+  __device__ __forceinline__ void issue(int stage_rel, char* lds_blocks) const {
+    uint32_t tap, ks;
+    dSpt.divmod((uint32_t)(stage0 + stage_rel), tap, ks);
+    const uint16_t* q = p[K] + ((int64_t)ks * 32 * 9 + tap) * Cc;
+    __builtin_amdgcn_global_load_lds((global_void_ptr)q, (lds_void_ptr)(lds_blocks + K * 1024), 16, 0, 0);
+  }
+};
+
 // MFMA with the accumulator pinned, in place, to the accumulation half of the register file: the 256 accumulator
 // registers of a 128 x 128 wavefront block fill that half exactly, and left to itself the register allocator shuffles
 // them through the other half.  Issued as assembly, the instruction is opaque to the compiler's hazard handling; the
@@ -721,8 +806,9 @@ __device__ __forceinline__ void wait_frags9(half8& f, half8 (&g)[8]) {
                : "memory");
 }
 
-template <bool A_RC, bool B_RC, int BM>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_gemm_dma4(DmaMat A, DmaMat B, Problem pb, Epilogue ep) {
+template <class AOp, class BOp, int BM>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_gemm_dma4(typename AOp::Src A, typename BOp::Src B, Problem pb, Epilogue ep) {
+  constexpr bool A_RC = AOp::kRC, B_RC = BOp::kRC;
   // BM = 256: tile 256 x 256, 128 x 128 per wavefront.  BM = 128: tile 128 x 256, 64 x 128 per wavefront, for problems
   // with too few 256-row tiles to occupy the chip (batch-256 recurrent and gate products).
   static_assert(BM == 256 || BM == 128, "tile rows");
@@ -751,8 +837,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #pragma unroll
       for (int v = 0; v < 4; ++v) acc[a][b][v] = 0.f;
 
-  DmaOperand4<A_RC, BM> da;
-  DmaOperand4<B_RC, 256> db;
+  AOp da;
+  BOp db;
   da.init(A, i0, st_begin * 32, wave, lane);
   db.init(B, j0, st_begin * 32, wave, lane);
   // load q (0 .. LA-1: A blocks, then the B blocks) of stage s; past the end: refetch the last slice into a free slot
@@ -1036,7 +1122,7 @@ bool try_launch_dma(hipStream_t s, const AView& A, const BView& B, bool aligned,
     static const int nstage = mpt_env_int("MPT_GEMM_STAGES", 4);          // 4 or 5 ring slots of 32 KiB (tuning only)
     auto k4 = k_gemm_dma<DmaKind<AView>::rc, DmaKind<BView>::rc, 4>;
     auto k5 = k_gemm_dma<DmaKind<AView>::rc, DmaKind<BView>::rc, 5>;
-    auto kw4 = k_gemm_dma4<DmaKind<AView>::rc, DmaKind<BView>::rc, 256>;
+    auto kw4 = k_gemm_dma4<DmaOperand4<DmaKind<AView>::rc, 256>, DmaOperand4<DmaKind<BView>::rc, 256>, 256>;
     static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(k4), hipFuncAttributeMaxDynamicSharedMemorySize, 4 * 32768),
                         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k5), hipFuncAttributeMaxDynamicSharedMemorySize, 5 * 32768),
                         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kw4), hipFuncAttributeMaxDynamicSharedMemorySize, 4 * 32768), true);
@@ -1069,7 +1155,7 @@ bool try_launch_dma128(hipStream_t s, const AView& A, const BView& B, bool align
     if ((ep.ld % 8) || !mpt_aligned(ep.out, 16) || (ep.act == 2 && ((ep.ldmask % 8) || !mpt_aligned(ep.mask, 16)))) return false;
     const int64_t t256 = ((int64_t)(I + 255) / 256) * (J / 256), t128 = (int64_t)(I / 128) * (J / 256);
     if (t256 >= kCUs * 3 / 4 || t128 < kCUs * 3 / 8) return false;
-    auto k = k_gemm_dma4<DmaKind<AView>::rc, DmaKind<BView>::rc, 128>;
+    auto k = k_gemm_dma4<DmaOperand4<DmaKind<AView>::rc, 128>, DmaOperand4<DmaKind<BView>::rc, 256>, 128>;
     constexpr int lds = 4 * (128 + 256) * 64;
     static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, lds), true);
     (void)once;
@@ -1220,11 +1306,49 @@ extern "C" size_t mpt_conv3x3_workspace_bytes(int op, int64_t Nb, int64_t H, int
   return plan_ws_bytes(make_plan(I, J, R, true), I, J);
 }
 
+namespace {
+// Whole-tile convolutions (pixel count a multiple of the tile rows, 256 output channels per tile column, input
+// channels a multiple of 64) take the streamed one-wavefront-per-SIMD kernel with a gathered A operand.
+template <class BOp>
+bool try_launch_conv_dma(hipStream_t s, const uint16_t* img, int64_t H, int64_t W, int64_t Cin, int sgn, const typename BOp::Src& B,
+                         int64_t P, int64_t J, uint16_t* out, int& status) {
+  static const bool enabled = mpt_env_int("MPT_GEMM_STREAMED", 1) != 0 && mpt_env_int("MPT_CONV_STREAMED", 1) != 0;
+  if (!enabled || (J % 256) || (Cin % 64) || H >= 65536 || W >= 65536 || P * Cin >= (1LL << 31) || P * J >= (1LL << 31)) return false;
+  const int R = (int)(9 * Cin);
+  const DmaImgSrc A{img, (int)H, (int)W, (int)Cin, sgn, FastDiv((uint32_t)(H * W)), FastDiv((uint32_t)W), FastDiv((uint32_t)(Cin / 32))};
+  Epilogue ep{out, J, 0, nullptr, 0, nullptr, 0};
+  const int64_t t256 = (P / 256) * (J / 256), t128 = (P / 128) * (J / 256);
+  if ((P % 256) == 0 && t256 >= kCUs * 3 / 8) {
+    auto k = k_gemm_dma4<DmaImgRC<256>, BOp, 256>;
+    static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, 4 * 32768), true);
+    (void)once;
+    Problem pb{(int)P, (int)J, R, (int)(P / 256), (int)(J / 256), 1, R / 64};
+    hipLaunchKernelGGL(k, dim3((unsigned)t256), dim3(256), 4 * 32768, s, A, B, pb, ep);
+  } else if ((P % 128) == 0 && t128 >= kCUs * 3 / 8) {
+    auto k = k_gemm_dma4<DmaImgRC<128>, BOp, 128>;
+    constexpr int lds = 4 * (128 + 256) * 64;
+    static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, lds), true);
+    (void)once;
+    Problem pb{(int)P, (int)J, R, (int)(P / 128), (int)(J / 256), 1, R / 64};
+    hipLaunchKernelGGL(k, dim3((unsigned)t128), dim3(256), lds, s, A, B, pb, ep);
+  } else {
+    return false;
+  }
+  status = hipGetLastError() == hipSuccess ? MPT_OK : MPT_ERR_HIP;
+  return true;
+}
+}  // namespace
+
 extern "C" int mpt_conv3x3_fwd(void* stream, int64_t Nb, int64_t H, int64_t W, int64_t C, int64_t Kf, const uint16_t* x,
                                const uint16_t* w, uint16_t* y, void* ws, size_t ws_bytes) {
   if (x == nullptr || w == nullptr || y == nullptr) return MPT_ERR_NULL;
   if (!conv_ok(Nb, H, W, C, Kf)) return MPT_ERR_SHAPE;
   if (!mpt_aligned(x, 16) || !mpt_aligned(w, 16) || !mpt_aligned(y, 16) || (ws && !mpt_aligned(ws, 16))) return MPT_ERR_ALIGN;
+  {
+    int st = MPT_OK;                 // the workspace, if any, is not needed on this path (its size was not checked: nothing is written to it)
+    if (ws == nullptr || ws_bytes >= mpt_conv3x3_workspace_bytes(MPT_OP_FWD, Nb, H, W, C, Kf))
+      if (try_launch_conv_dma<DmaOperand4<true, 256>>(static_cast<hipStream_t>(stream), x, H, W, C, +1, DmaMat{w, 9 * C}, Nb * H * W, Kf, y, st)) return st;
+  }
   const int P = (int)(Nb * H * W), R = (int)(9 * C);
   ImgRC A{x, (int)H, (int)W, (int)C, P, R, +1, FastDiv((uint32_t)(H * W)), FastDiv((uint32_t)W), FastDiv((uint32_t)C)};
   MatRC B{w, 9 * C, (int)Kf, R};
@@ -1237,6 +1361,12 @@ extern "C" int mpt_conv3x3_dgrad(void* stream, int64_t Nb, int64_t H, int64_t W,
   if (dy == nullptr || w == nullptr || dx == nullptr) return MPT_ERR_NULL;
   if (!conv_ok(Nb, H, W, C, Kf)) return MPT_ERR_SHAPE;
   if (!mpt_aligned(dy, 16) || !mpt_aligned(w, 16) || !mpt_aligned(dx, 16) || (ws && !mpt_aligned(ws, 16))) return MPT_ERR_ALIGN;
+  {
+    int st = MPT_OK;
+    if (ws == nullptr || ws_bytes >= mpt_conv3x3_workspace_bytes(MPT_OP_DGRAD, Nb, H, W, C, Kf))
+      if (try_launch_conv_dma<DmaFilterOC>(static_cast<hipStream_t>(stream), dy, H, W, Kf, -1,
+                                           DmaFilterSrc{w, (int)C, (int)Kf, FastDiv((uint32_t)(Kf / 32))}, Nb * H * W, C, dx, st)) return st;
+  }
   const int P = (int)(Nb * H * W), R = (int)(9 * Kf);
   ImgRC A{dy, (int)H, (int)W, (int)Kf, P, R, -1, FastDiv((uint32_t)(H * W)), FastDiv((uint32_t)W), FastDiv((uint32_t)Kf)};
   FilterOC B{w, (int)C, (int)Kf, (int)C, R, FastDiv((uint32_t)Kf)};

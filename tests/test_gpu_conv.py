@@ -67,3 +67,28 @@ def test_cfg4_resnet_block_full_size():
     gemm_check(dx, o, sa, s, "cfg4 dgrad")
     o, sa, s = conv.conv3x3_wgrad(x, dy, full=True)
     gemm_check(dw, o, sa, s, "cfg4 wgrad")
+
+
+@pytest.mark.parametrize("Nb,H,W,C,Kf", [(64, 14, 14, 64, 512), (50, 16, 16, 256, 256), (32, 7, 56, 128, 256)])
+def test_whole_tile_shapes_forward_and_input_gradient(Nb, H, W, C, Kf):
+    """Pixel counts that are whole tiles (49 x 256 rows with two tile columns; 100 x 128 rows; a wide, flat image):
+    the streamed forward and input-gradient kernels with the gathered operand, including image borders in every
+    tile.  Integer-valued inputs make the comparison bit-exact on top of the usual acceptance rule."""
+    rng = np.random.default_rng(Nb + H + C)
+    x = np.maximum(rng.standard_normal((Nb, H, W, C)), 0).astype(np.float16)
+    w = (rng.standard_normal((Kf, 3, 3, C)) * np.sqrt(2.0 / (9 * C))).astype(np.float16)
+    dy = (np.abs(rng.standard_normal((Nb, H, W, Kf))) * 2.0 ** -6 * rng.integers(0, 2, (Nb, H, W, Kf))).astype(np.float16)
+    y, dx, dw = run_all(x, w, dy, True)
+    o, sa, s = conv.conv3x3_fwd(x, w, full=True)
+    gemm_check(y, o, sa, s, "conv fwd")
+    o, sa, s = conv.conv3x3_dgrad(dy, w, full=True)
+    gemm_check(dx, o, sa, s, "conv dgrad")
+    o, sa, s = conv.conv3x3_wgrad(x, dy, full=True)
+    gemm_check(dw, o, sa, s, "conv wgrad")
+    xi = rng.integers(-2, 3, (Nb, H, W, C)).astype(np.float16)
+    wi = rng.integers(-1, 2, (Kf, 3, 3, C)).astype(np.float16) * (rng.random((Kf, 3, 3, C)) < 0.05)
+    wi = wi.astype(np.float16)
+    dyi = rng.integers(-2, 3, (Nb, H, W, Kf)).astype(np.float16) * (rng.random((Nb, H, W, Kf)) < 0.05).astype(np.float16)
+    yi, dxi, _ = run_all(xi, wi, dyi, False)
+    assert np.array_equal(fp16.bits(yi), fp16.bits(conv.conv3x3_fwd(xi, wi)[0]))
+    assert np.array_equal(fp16.bits(dxi), fp16.bits(conv.conv3x3_dgrad(dyi, wi)[0]))
