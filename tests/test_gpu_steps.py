@@ -182,3 +182,65 @@ def test_cfg3_wgrad_over_timesteps():
     assert int(flag.item()) == 0
     assert np.array_equal(host(d_w).view(np.uint32), wn.view(np.uint32))
     assert np.array_equal(fp16.bits(host16(d_h)), fp16.bits(hn))
+
+
+def test_conv_batchnorm_relu_block_teacher_forced():
+    """A residual-network style block on the device: 3x3 convolution -> batch-norm statistics -> normalise + ReLU,
+    then its backward pass (ReLU mask, batch-norm reductions and input gradient, convolution gradients).  Every stage is
+    fed the oracle's FP16 tensors for the stage before (bit-identical inputs) and compared at that stage's own bar."""
+    from oracle import conv, norm
+    rng = np.random.default_rng(31)
+    Nb, H, W, C, Kf = 16, 14, 14, 64, 256                       # 3136 pixels: whole 128-row tiles for the convolution
+    S = 256.0
+    x = np.maximum(rng.standard_normal((Nb, H, W, C)), 0).astype(np.float16)
+    w = (rng.standard_normal((Kf, 3, 3, C)) * np.sqrt(2.0 / (9 * C))).astype(np.float16)
+    gamma = rng.uniform(0.5, 1.5, Kf).astype(np.float32); beta = rng.uniform(-0.5, 0.5, Kf).astype(np.float32)
+    dz = (rng.standard_normal((Nb, H, W, Kf)) * 2.0 ** -9 * S).astype(np.float16)          # upstream gradient, loss-scaled
+    P = Nb * H * W
+    # ---- forward
+    y_o, sa, s = conv.conv3x3_fwd(x, w, full=True)
+    y = _empty16(Nb, H, W, Kf); mpt.mpt_conv3x3_fwd(dev16(x), dev16(w), y)
+    gemm_check(host16(y), y_o, sa, s, "block conv fwd")
+    y2 = y_o.reshape(P, Kf)
+    mean = torch.empty(Kf, dtype=torch.float32, device="cuda"); var = torch.empty_like(mean)
+    ws = torch.empty(max(mpt.mpt_bn_workspace_bytes(P, Kf), 16) // 8, dtype=torch.float64, device="cuda")
+    mpt.mpt_bn_stats(dev16(y2), mean, var, ws)
+    m_o, v_o = norm.bn_stats(y2)
+    assert np.allclose(host(mean), m_o, rtol=1e-5, atol=1e-6) and np.allclose(host(var), v_o, rtol=1e-4, atol=1e-8)
+    m32, v32 = m_o.astype(np.float32), v_o.astype(np.float32)
+    z = _empty16(P, Kf); mpt.mpt_bn_apply(dev16(y2), dev(m32), dev(v32), dev(gamma), dev(beta), 1e-5, z, relu=True)
+    z_o = norm.bn_apply(y2, m32, v32, gamma, beta, 1e-5, relu=True)
+    assert np.array_equal(fp16.bits(host16(z)), fp16.bits(z_o))
+    # ---- backward
+    dz2 = dz.reshape(P, Kf)
+    da = _empty16(P, Kf); mpt.mpt_relu_bwd(dev16(dz2), dev16(z_o), da)                       # z > 0 exactly where the pre-activation was
+    da_o = loss.relu_bwd(dz2, z_o)
+    assert np.array_equal(fp16.bits(host16(da)), fp16.bits(da_o))
+    dg = torch.empty(Kf, dtype=torch.float32, device="cuda"); db = torch.empty_like(dg)
+    mpt.mpt_bn_bwd_reduce(dev16(y2), dev16(da_o), dev(m32), dev(v32), 1e-5, dg, db, ws)
+    dg_o, db_o = norm.bn_bwd_reduce(y2, da_o, m32, v32, 1e-5)
+    scale_g = np.abs(da_o.astype(np.float64)).sum(axis=0) * 8                                # |xhat| stays below ~8 here
+    assert (np.abs(host(dg) - dg_o) <= 20 * 2.0 ** -24 * scale_g + 1e-12).all()
+    assert (np.abs(host(db) - db_o) <= 20 * 2.0 ** -24 * np.abs(da_o.astype(np.float64)).sum(axis=0) + 1e-12).all()
+    dg32, db32 = dg_o.astype(np.float32), db_o.astype(np.float32)
+    dy = _empty16(P, Kf); mpt.mpt_bn_bwd_apply(dev16(y2), dev16(da_o), dev(m32), dev(v32), dev(gamma), 1e-5, dev(dg32), dev(db32), dy)
+    dy_o = norm.bn_bwd_apply(y2, da_o, m32, v32, gamma, 1e-5, dg32, db32)
+    assert np.array_equal(fp16.bits(host16(dy)), fp16.bits(dy_o))
+    dy4 = dy_o.reshape(Nb, H, W, Kf)
+    dx = _empty16(Nb, H, W, C); mpt.mpt_conv3x3_dgrad(dev16(dy4), dev16(w), dx)
+    o, sa, s = conv.conv3x3_dgrad(dy4, w, full=True)
+    gemm_check(host16(dx), o, sa, s, "block conv dgrad")
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    dw = _empty16(Kf, 3, 3, C)
+    b = mpt.mpt_conv3x3_workspace_bytes(2, Nb, H, W, C, Kf)
+    wsw = torch.empty(max(b, 16) // 4, dtype=torch.float32, device="cuda") if b else None
+    mpt.mpt_conv3x3_wgrad(dev16(x), dev16(dy4), dw, flag, wsw)
+    o, sa, s = conv.conv3x3_wgrad(x, dy4, full=True)
+    gemm_check(host16(dw), o, sa, s, "block conv wgrad")
+    assert int(flag.item()) == 0
+    # the scaled weight gradient goes through the usual unscale + update
+    wm = w.astype(np.float32).reshape(-1); mom = np.zeros_like(wm)
+    rw, rm, rh = update.master_update(wm, mom, o.reshape(-1), 1.0 / S, 0.01, 0.9, 0)
+    d_w, d_m, d_h = dev(wm.copy()), dev(mom.copy()), dev16(w.reshape(-1).copy())
+    mpt.mpt_master_update(d_w, d_m, dev16(o.reshape(-1)), d_h, 1.0 / S, 0.01, 0.9, flag)
+    assert np.array_equal(host(d_w).view(np.uint32), rw.view(np.uint32)) and np.array_equal(fp16.bits(host16(d_h)), fp16.bits(rh))
