@@ -207,7 +207,7 @@ int mpt_master_update(void* stream, size_t n, float* w32_dev, float* m32_dev,
  *       loss_dev[0] = mean_b row_loss_dev[b]               (FP32; nullable; summed in a fixed order)
  *       dlogits[b,c] = rne16( scale * (p[b,c] - [c==label_b]) / B )
  *     which applies Sec. 3.2's loss scale at the head of back-propagation.
- *     labels_dev: int32, each in [0, C).  C <= 2^24.  Each row is read once and written once when C <= 65536
+ *     labels_dev: int32, each in [0, C) (a value outside is clamped into the range).  C <= 2^24.  Each row is read once and written once when C <= 65536
  *     (16-byte accesses when both tensors are 16-byte aligned with C and the row strides multiples of 8).
  * ------------------------------------------------------------------------- */
 int mpt_relu_fwd(void* stream, size_t n, const uint16_t* y_dev, uint16_t* h_dev);

@@ -345,7 +345,7 @@ __global__ __launch_bounds__((WAVES * 64 > kThreads ? WAVES * 64 : kThreads)) vo
     }
   sum = across(sum, false);
   if (!live) return;
-  const int32_t lab = labels[row];
+  const int32_t lab = min(max(labels[row], 0), (int32_t)(C - 1));      // a label outside [0, C) is the caller's error; it must not become a wild read
   const float inv = div_rn(1.0f, sum);
   _Float16* d = reinterpret_cast<_Float16*>(dlogits) + row * ldd;
 #pragma unroll
@@ -423,7 +423,7 @@ __global__ __launch_bounds__(1024) void k_softmax_xent_long(
     for (int e = 0; e < W; ++e) sum = __fadd_rn(sum, __builtin_amdgcn_exp2f(__fmul_rn(__fsub_rn(v[e], mx), kLog2e)));
   }
   sum = across(sum, false);
-  const int32_t lab = labels[row];
+  const int32_t lab = min(max(labels[row], 0), (int32_t)(C - 1));      // a label outside [0, C) is the caller's error; it must not become a wild read
   const float inv = div_rn(1.0f, sum);
   _Float16* d = reinterpret_cast<_Float16*>(dlogits) + row * ldd;
   for (int64_t c = (int64_t)threadIdx.x * W; c < C; c += (int64_t)NT * W) {
