@@ -184,6 +184,124 @@ def measure_next(torch, mpt, np, dev, with_cpu):
     return rows
 
 
+def measure_configs(torch, mpt, np, dev, workloads):
+    """The other synthetic configurations (MLP step, projected-LSTM layer GEMMs, 3x3 convolution block, dynamic-scale
+    flat update), each pass preheated and timed alone on resident inputs.  Returns a list of dicts."""
+    rows = []
+
+    def timeit(fn, reps=20, warm=3):
+        preheat(torch, fn, 40.0)
+        for _ in range(warm):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e-3
+
+    def mfma_row(cfg, name, flops, sec):
+        tf = flops / sec / 1e12
+        rows.append({"config": cfg, "pass": name, "bound": "mfma", "achieved": round(tf, 1), "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(tf / MFMA_F16_PEAK_TFLOPS, 4), "us": round(sec * 1e6, 1)})
+
+    def d16(a):
+        return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).to(dev).view(torch.float16)
+
+    def e16(*shape):
+        return torch.empty(shape, dtype=torch.float16, device=dev)
+
+    def wsp(*byte_counts):
+        return torch.empty(max(max(byte_counts), 16) // 4, dtype=torch.float32, device=dev)
+
+    def log_uniform(shape, lo, hi, scale):
+        mag = torch.exp2(torch.empty(shape, device=dev).uniform_(lo, hi)) * scale
+        return (mag * (torch.randint(0, 2, shape, device=dev) * 2 - 1)).half()
+
+    # ---- cfg 1: the whole 2-layer MLP step, device only (13 launches; latency bound)
+    c = workloads.mlp()
+    x, lab = d16(c["x"]), torch.from_numpy(c["labels"]).to(dev)
+    w1_32, w2_32 = torch.from_numpy(c["w1_32"].copy()).to(dev), torch.from_numpy(c["w2_32"].copy()).to(dev)
+    w1, w2 = d16(c["w1_16"]), d16(c["w2_16"])
+    S, inv, lr = c["scale"], 1.0 / c["scale"], c["lr"]
+    flag = torch.zeros(1, dtype=torch.int32, device=dev)
+    L, R = torch.zeros(1, device=dev), torch.zeros(256, device=dev)
+    y1, h1, logits, dlog = e16(256, 1024), e16(256, 1024), e16(256, 10), e16(256, 10)
+    dw2, dh1, dy1, dw1 = e16(1024, 10), e16(256, 1024), e16(256, 1024), e16(1024, 1024)
+
+    def mlp_step():
+        mpt.mpt_gemm_fwd_relu(x, w1, h1); mpt.mpt_gemm_fwd(h1, w2, logits)
+        mpt.mpt_softmax_xent_scaled(logits, lab, S, dlog, L, R)
+        mpt.mpt_gemm_wgrad(h1, dlog, dw2, flag=flag); mpt.mpt_gemm_dgrad_relu(dlog, w2, h1, dy1)
+        mpt.mpt_gemm_wgrad(x, dy1, dw1, flag=flag)
+        mpt.mpt_master_update(w1_32, None, dw1, w1, inv, lr, 0.0, flag)
+        mpt.mpt_master_update(w2_32, None, dw2, w2, inv, lr, 0.0, flag)
+    t = timeit(mlp_step, reps=50)
+    fl = 3 * 2.0 * 256 * (1024 * 1024 + 1024 * 10)
+    mfma_row("cfg1 MLP 256x1024 -> 1024 -> 10", "whole step: 2 fwd (ReLU folded), loss, 2 wgrad (+Inf/NaN vote), dgrad (mask folded), 2 master updates; 8 launches", fl, t)
+    del x, w1, w2, w1_32, w2_32
+
+    # ---- cfg 3: projected-LSTM layer products at batch 256 (per timestep), and the time-batched weight gradient
+    Bt, T, DK, G4, HC, RP = 256, 20, 2048, 4 * 8192, 8192, 1024
+    Wg = torch.empty(DK, G4, device=dev).uniform_(-0.05, 0.05).half()
+    Wp = torch.empty(HC, RP, device=dev).uniform_(-0.05, 0.05).half()
+    xh = torch.randn(T * Bt, DK, device=dev).half()
+    hh = torch.randn(Bt, HC, device=dev).clamp_(-0.999, 0.999).half()
+    dga = log_uniform((T * Bt, G4), -30.0, -5.0, 128.0)
+    dr = log_uniform((Bt, RP), -30.0, -5.0, 128.0)
+    ws = wsp(mpt.mpt_gemm_workspace_bytes(0, Bt, G4, DK), mpt.mpt_gemm_workspace_bytes(1, Bt, G4, DK), mpt.mpt_gemm_workspace_bytes(2, Bt, G4, DK),
+             mpt.mpt_gemm_workspace_bytes(0, Bt, RP, HC), mpt.mpt_gemm_workspace_bytes(1, Bt, RP, HC), mpt.mpt_gemm_workspace_bytes(2, Bt, RP, HC),
+             mpt.mpt_gemm_workspace_bytes(2, T * Bt, G4, DK))
+    gates, dxh, dWg = e16(Bt, G4), e16(Bt, DK), e16(DK, G4)
+    proj, dh = e16(Bt, RP), e16(Bt, HC)
+    dWp32 = torch.zeros(HC, RP, dtype=torch.float32, device=dev)
+    name = "cfg3 LSTM-with-projection, batch 256"
+    fg, fp = 2.0 * Bt * DK * G4, 2.0 * Bt * HC * RP
+    mfma_row(name, "gate fwd 256 x 32768 x 2048", fg, timeit(lambda: mpt.mpt_gemm_fwd(xh[:Bt], Wg, gates, ws)))
+    mfma_row(name, "gate dgrad 256 x 2048 x 32768 (split reduction through the workspace)", fg, timeit(lambda: mpt.mpt_gemm_dgrad(dga[:Bt], Wg, dxh, ws)))
+    mfma_row(name, "gate wgrad per timestep 2048 x 32768 x 256", fg, timeit(lambda: mpt.mpt_gemm_wgrad(xh[:Bt], dga[:Bt], dWg, ws=ws)))
+    mfma_row(name, "gate wgrad, 20 timesteps in one contraction 2048 x 32768 x 5120", T * fg, timeit(lambda: mpt.mpt_gemm_wgrad(xh, dga, dWg, ws=ws), reps=5))
+    mfma_row(name, "projection fwd 256 x 1024 x 8192 (split)", fp, timeit(lambda: mpt.mpt_gemm_fwd(hh, Wp, proj, ws)))
+    mfma_row(name, "projection dgrad 256 x 8192 x 1024", fp, timeit(lambda: mpt.mpt_gemm_dgrad(dr, Wp, dh, ws)))
+    mfma_row(name, "projection wgrad per timestep, accumulated into an FP32 gradient 8192 x 1024 x 256", fp,
+             timeit(lambda: mpt.mpt_gemm_wgrad(hh, dr, dWp32, accumulate=True)))
+    del Wg, Wp, xh, hh, dga, dr, gates, dxh, dWg, proj, dh, dWp32, ws
+
+    # ---- cfg 4: 3x3 convolution block, NHWC 256 x 14 x 14 x 256 -> 256 channels (implicit GEMM 50176 x 256 x 2304)
+    c = workloads.conv_block()
+    x, w, dy = d16(c["x"]), d16(c["w"]), d16(c["dy"])
+    Nb, H, W_, C = c["x"].shape
+    Kf = c["w"].shape[0]
+    ws = wsp(*[mpt.mpt_conv3x3_workspace_bytes(op, Nb, H, W_, C, Kf) for op in (0, 1, 2)])
+    y, dx, dw = e16(Nb, H, W_, Kf), e16(Nb, H, W_, C), e16(Kf, 3, 3, C)
+    fl = 2.0 * Nb * H * W_ * Kf * 9 * C
+    name = "cfg4 conv 3x3 256x14x14x256 -> 256"
+    mfma_row(name, "fwd (streamed, gathered operand)", fl, timeit(lambda: mpt.mpt_conv3x3_fwd(x, w, y, ws)))
+    mfma_row(name, "dgrad (streamed, gathered operand, filter read outer-contiguous)", fl, timeit(lambda: mpt.mpt_conv3x3_dgrad(dy, w, dx, ws)))
+    mfma_row(name, "wgrad (general kernel, split reduction through the workspace)", fl, timeit(lambda: mpt.mpt_conv3x3_wgrad(x, dy, dw, ws=ws)))
+    del x, w, dy, y, dx, dw, ws
+
+    # ---- cfg 5: one dynamic-scale step on the 116M-element flat buffer: check, momentum update, scaler (device resident)
+    nf = N_FLAT
+    w32 = torch.empty(nf, device=dev).uniform_(-0.05, 0.05)
+    m32 = torch.zeros(nf, device=dev)
+    g16 = log_uniform((nf,), -28.0, -2.0, 65536.0)
+    h16 = w32.half()
+    scaler = mpt.scaler_to_device(mpt.mpt_scaler_init(65536.0, 1000))
+    flag.zero_()
+
+    def flat_step():
+        mpt.mpt_unscale_check(g16, 2.0 ** -16, flag)
+        mpt.mpt_master_update(w32, m32, g16, h16, 1.0, 1e-3, 0.9, flag, scaler_dev=scaler)
+        mpt.mpt_loss_scale_update_dev(scaler, flag)
+    t = timeit(flat_step, reps=20)
+    gbs = 22.0 * nf / t / 1e9
+    rows.append({"config": "cfg5 dynamic loss scaling + master update, 116M elements", "pass": "check (2 B/element) + momentum update (20 B/element) + scaler, 3 launches",
+                 "bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4), "us": round(t * 1e6, 1)})
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -194,6 +312,7 @@ def main():
                          "the first ~30 ms of sustained load, and a step here is only ~0.5 ms")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-next", action="store_true", help="skip the kernels beyond the headline path (batch norm, softmax, other optimizers, statistics)")
+    ap.add_argument("--no-configs", action="store_true", help="skip the per-pass figures of the other synthetic configurations")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy, so a counter run of this command holds a kernel of known traffic")
     args = ap.parse_args()
@@ -331,6 +450,8 @@ def main():
 
     next_rows = None if args.no_next else measure_next(torch, mpt, np, dev, not args.no_cpu_baseline)
 
+    config_rows = None if args.no_configs else measure_configs(torch, mpt, np, dev, workloads)
+
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import gemm as ogemm
@@ -357,7 +478,7 @@ def main():
                       "loss_scale": 8192, "master_update_elements": n * n},
            "pct_of_fp16_peak": round(100 * value / MFMA_F16_PEAK_TFLOPS, 2),
            "master_update_pct_of_hbm_peak": round(100 * upd_gbs / HBM_PEAK_GBS, 2),
-           "roofline": roofline, "roofline_update": roofline_update, "roofline_next": next_rows, "cpu_baseline": cpu}
+           "roofline": roofline, "roofline_update": roofline_update, "roofline_next": next_rows, "roofline_configs": config_rows, "cpu_baseline": cpu}
     print(json.dumps(out))
 
 

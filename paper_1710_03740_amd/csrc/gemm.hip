@@ -379,11 +379,25 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void k_gemm(AView A, BV
           }
         } else {
           float* o = reinterpret_cast<float*>(ep.out) + split_off + (int64_t)i * ep.ld + j;
-          for (int e = 0; e < nj; ++e) {
-            float v = x[e];
-            if (ep.mode == 2) v = __fadd_rn(o[e], v);
-            if (ep.flag && ep.mode != 3) bad |= (__float_as_uint(v) & 0x7F800000u) == 0x7F800000u;
-            o[e] = v;
+          if (nj == 4 && (reinterpret_cast<uintptr_t>(o) & 15) == 0) {     // 16 bytes per lane
+            float4v v = {x[0], x[1], x[2], x[3]};
+            if (ep.mode == 2) {
+              const float4v old = *reinterpret_cast<const float4v*>(o);
+#pragma unroll
+              for (int e = 0; e < 4; ++e) v[e] = __fadd_rn(old[e], v[e]);
+            }
+            if (ep.flag && ep.mode != 3) {
+#pragma unroll
+              for (int e = 0; e < 4; ++e) bad |= (__float_as_uint(v[e]) & 0x7F800000u) == 0x7F800000u;
+            }
+            *reinterpret_cast<float4v*>(o) = v;
+          } else {
+            for (int e = 0; e < nj; ++e) {
+              float v = x[e];
+              if (ep.mode == 2) v = __fadd_rn(o[e], v);
+              if (ep.flag && ep.mode != 3) bad |= (__float_as_uint(v) & 0x7F800000u) == 0x7F800000u;
+              o[e] = v;
+            }
           }
         }
       }
@@ -629,7 +643,7 @@ __global__ __launch_bounds__(512) void k_gemm_dma(DmaMat A, DmaMat B, Problem pb
   // drain the tail prefetches before LDS is released
   asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
 
-  // ---- epilogue (whole tiles): FP16 store with optional Inf/NaN vote, or FP32 split partial.
+  // ---- epilogue (whole tiles): FP16 store, FP32 store / accumulate (each with optional Inf/NaN vote), or FP32 split partial.
   // acc[a][b][e]: row i = 16a + lane%16, column j = 16b + 4*(lane/16) + e of the wavefront's 128 x 64 block.
   bool bad = false;
   const int64_t split_off = (ep.mode == 3) ? (int64_t)sp * pb.I * pb.J : 0;
@@ -652,12 +666,23 @@ __global__ __launch_bounds__(512) void k_gemm_dma(DmaMat A, DmaMat B, Problem pb
 #pragma unroll
           for (int e = 0; e < 4; ++e) o[e] = (uint16_t)(hb[e >> 1] >> ((e & 1) * 16));
         }
-      } else {
-        *reinterpret_cast<float4v*>(reinterpret_cast<float*>(ep.out) + split_off + (int64_t)i * ep.ld + j) = acc[a][b];
+      } else {                                                           // FP32 store, accumulate, or split partial: 16 bytes per lane
+        float* o = reinterpret_cast<float*>(ep.out) + split_off + (int64_t)i * ep.ld + j;
+        float4v v = acc[a][b];
+        if (ep.mode == 2) {
+          const float4v old = *reinterpret_cast<const float4v*>(o);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = __fadd_rn(old[e], v[e]);
+        }
+        if (ep.flag && ep.mode != 3) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) bad |= (__float_as_uint(v[e]) & 0x7F800000u) == 0x7F800000u;
+        }
+        *reinterpret_cast<float4v*>(o) = v;
       }
     }
   }
-  if (ep.flag != nullptr && ep.mode == 0) {
+  if (ep.flag != nullptr && ep.mode != 3) {
     const unsigned long long vote = __builtin_amdgcn_ballot_w64(bad);
     if (vote != 0ull && lane == 0) atomicOr(ep.flag, 1u);
   }
@@ -1112,8 +1137,8 @@ template <class AView, class BView>
 bool try_launch_dma(hipStream_t s, const AView& A, const BView& B, bool aligned, const Plan& pl, int I, int J, int R, const Epilogue& ep, int& status) {
   if constexpr (DmaKind<AView>::ok && DmaKind<BView>::ok) {
     static const bool enabled = mpt_env_int("MPT_GEMM_STREAMED", 1) != 0;
-    if (!enabled || !aligned || !pl.big || (I % 256) || (J % 256) || (R % 64) || (ep.mode != 0 && ep.mode != 3)) return false;
-    if (ep.mode == 3 && ((ep.ld % 4) || !mpt_aligned(ep.out, 16))) return false;
+    if (!enabled || !aligned || !pl.big || (I % 256) || (J % 256) || (R % 64)) return false;
+    if (ep.mode != 0 && ((ep.ld % 4) || !mpt_aligned(ep.out, 16))) return false;      // FP32 outputs go out 16 bytes per lane
     // FP16 stores of unsplit problems into 16-byte aligned rows take the one-wavefront-per-SIMD kernel (same speed at one
     // tile per CU, about 5 % faster over several); split partials and odd output strides take k_gemm_dma.
     static const int nwaves = mpt_env_int("MPT_GEMM_WAVES", 4);           // 8 forces k_gemm_dma (tuning only)

@@ -195,6 +195,43 @@ def test_wgrad_fp32_store_and_accumulate():
     assert int(flag.item()) == 1
 
 
+@pytest.mark.parametrize("K,N,B", [(512, 256, 128), (256, 768, 64), (1024, 512, 256), (4096, 2048, 64)])
+def test_wgrad_fp32_whole_tiles(K, N, B):
+    """FP32 store and accumulate with 16 bytes per lane: the general kernel on the small shapes, the streamed kernel's
+    FP32 epilogue on the last one (128 tiles of 256 x 256).  Integer data so that the sums are exact, then real data
+    against the oracle's allowance; the output is a column window of a wider buffer (row stride 8 floats longer than
+    the matrix), and a planted Inf raises the flag."""
+    rng = np.random.default_rng(K + N + B)
+    T = 3
+    Xi = rng.integers(-3, 4, (T, B, K)).astype(np.float16)
+    dYi = rng.integers(-3, 4, (T, B, N)).astype(np.float16)
+    buf = torch.full((K, N + 8), 7.0, dtype=torch.float32, device="cuda")
+    out = buf[:, 4:4 + N]                                                  # 16-byte aligned rows, ld = N + 8
+    want = np.zeros((K, N), dtype=np.int64)
+    for t in range(T):
+        mpt.mpt_gemm_wgrad(dev16(Xi[t]), dev16(dYi[t]), out, accumulate=(t > 0))
+        want += Xi[t].astype(np.int64).T @ dYi[t].astype(np.int64)
+    got = host(buf)
+    assert np.array_equal(got[:, 4:4 + N].astype(np.int64), want)
+    assert (got[:, :4] == 7.0).all() and (got[:, 4 + N:] == 7.0).all()     # nothing outside the window is touched
+    X = rng.standard_normal((T, B, K)).astype(np.float16)
+    dY = (rng.standard_normal((T, B, N)) * 2.0 ** -10).astype(np.float16)
+    d_acc = torch.zeros((K, N), dtype=torch.float32, device="cuda")
+    acc, sabs = None, 0.0
+    for t in range(T):
+        mpt.mpt_gemm_wgrad(dev16(X[t]), dev16(dY[t]), d_acc, accumulate=(t > 0))
+        acc, sa = gemm.gemm_wgrad(X[t], dY[t], out_fp32=True, acc32=acc)
+        sabs = sabs + sa
+    from gpu_util import C_ACC, U32
+    assert (np.abs(host(d_acc).astype(np.float64) - acc.astype(np.float64)) <= C_ACC * U32 * sabs).all()
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    mpt.mpt_gemm_wgrad(dev16(X[0]), dev16(dY[0]), d_acc, accumulate=True, flag=flag)
+    assert int(flag.item()) == 0
+    d_acc[K - 1, N - 1] = float("inf")
+    mpt.mpt_gemm_wgrad(dev16(X[0]), dev16(dY[0]), d_acc, accumulate=True, flag=flag)
+    assert int(flag.item()) == 1
+
+
 @pytest.mark.parametrize("scale", [1.0, 8192.0])
 def test_cfg2_square_4096(scale):
     """The benchmark shape, in the benchmarked launch configuration, whole output compared."""
