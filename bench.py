@@ -230,16 +230,18 @@ def measure_configs(torch, mpt, np, dev, workloads):
     y1, h1, logits, dlog = e16(256, 1024), e16(256, 1024), e16(256, 10), e16(256, 10)
     dw2, dh1, dy1, dw1 = e16(1024, 10), e16(256, 1024), e16(256, 1024), e16(1024, 1024)
 
+    ws1 = wsp(*[mpt.mpt_gemm_workspace_bytes(op, 256, n_, 1024) for op in (0, 1, 2) for n_ in (1024, 10)])
+
     def mlp_step():
-        mpt.mpt_gemm_fwd_relu(x, w1, h1); mpt.mpt_gemm_fwd(h1, w2, logits)
+        mpt.mpt_gemm_fwd_relu(x, w1, h1, ws1); mpt.mpt_gemm_fwd(h1, w2, logits, ws1)
         mpt.mpt_softmax_xent_scaled(logits, lab, S, dlog, L, R)
-        mpt.mpt_gemm_wgrad(h1, dlog, dw2, flag=flag); mpt.mpt_gemm_dgrad_relu(dlog, w2, h1, dy1)
-        mpt.mpt_gemm_wgrad(x, dy1, dw1, flag=flag)
+        mpt.mpt_gemm_wgrad(h1, dlog, dw2, flag=flag, ws=ws1); mpt.mpt_gemm_dgrad_relu(dlog, w2, h1, dy1, ws1)
+        mpt.mpt_gemm_wgrad(x, dy1, dw1, flag=flag, ws=ws1)
         mpt.mpt_master_update(w1_32, None, dw1, w1, inv, lr, 0.0, flag)
         mpt.mpt_master_update(w2_32, None, dw2, w2, inv, lr, 0.0, flag)
     t = timeit(mlp_step, reps=50)
     fl = 3 * 2.0 * 256 * (1024 * 1024 + 1024 * 10)
-    mfma_row("cfg1 MLP 256x1024 -> 1024 -> 10", "whole step: 2 fwd (ReLU folded), loss, 2 wgrad (+Inf/NaN vote), dgrad (mask folded), 2 master updates; 8 launches", fl, t)
+    mfma_row("cfg1 MLP 256x1024 -> 1024 -> 10", "whole step: 2 fwd (ReLU folded), loss, 2 wgrad (+Inf/NaN vote), dgrad (mask folded), 2 master updates; split reductions through one workspace", fl, t)
     del x, w1, w2, w1_32, w2_32
 
     # ---- cfg 3: projected-LSTM layer products at batch 256 (per timestep), and the time-batched weight gradient

@@ -1092,7 +1092,12 @@ Plan make_plan(int64_t I, int64_t J, int64_t R, bool allow_split) {
   int splits = 1;
   if (allow_split && tiles < kCUs) {
     splits = (int)(kCUs / tiles);
-    const int max_by_depth = kt / 8 > 0 ? kt / 8 : 1;                // keep >= 8 k-tiles per split
+    // keep >= 8 k-tiles per split; a short reduction (the latency-bound layers of a small network, one memory round
+    // trip per k-tile) may go down to 2 per split, up to 8 splits
+    int max_by_depth = kt / 8;
+    const int short_r = kt / 2 < 8 ? kt / 2 : 8;
+    if (max_by_depth < short_r) max_by_depth = short_r;
+    if (max_by_depth < 1) max_by_depth = 1;
     if (splits > max_by_depth) splits = max_by_depth;
     if (splits > 64) splits = 64;
   }
