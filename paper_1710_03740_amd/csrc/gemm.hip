@@ -694,7 +694,8 @@ __global__ __launch_bounds__(512) void k_gemm_dma(DmaMat A, DmaMat B, Problem pb
 // i.e. two thirds of the LDS read traffic, and only four wavefronts meet at the per-stage barrier.  With a single
 // wavefront per SIMD nothing else covers a stall, so everything is software-pipelined inside the wavefront:
 // a stage is 8 steps (one A block against the 8 B blocks); step a requests A block a+2 (wrapping into the next stage),
-// steps 4-7 also request the next stage's B blocks, and every step issues one of the wavefront's 8 LDS-direct loads.
+// the steps after the stage's barrier also request the next stage's B blocks, and every step issues one of the
+// wavefront's 8 LDS-direct loads (FragSched below says where in a step each request sits, and why).
 // The kernel is also instantiated for a 128-row tile (64 x 128 per wavefront, 4 steps per stage).
 // An operand of the one-wavefront-per-SIMD kernel is a policy: Src (what the host passes), kRC (layout kind),
 // init (per-lane constants for this workgroup's tile) and issue<K> (the K-th LDS-direct load of a stage).
@@ -812,6 +813,49 @@ struct DmaFilterOC {
   }
 };
 
+// Fragment-request schedule of the one-wavefront-per-SIMD kernel.  A stage is NA steps of 8 MFMAs; step a requests the
+// A block used two steps later and, in the late steps (a >= NA/2, after the stage's barrier), its share of the next
+// stage's 8 B blocks.  With a single wavefront per SIMD every instruction that is not an MFMA delays the next MFMA
+// unless it sits alone in the gap behind one (measured: 4 VALU operations bunched before a step cost 9 cycles, the
+// same 4 placed one per gap cost none; a bunched pair of LDS reads 10 cycles, spread 2-6), so the 256-row kernel
+// issues its requests one per gap: the A block behind MFMA 0, B blocks behind the odd MFMAs (3, 3, 2 of them in steps
+// 4, 5, 6, so that the last one is a whole step old when step 0 needs it), the LDS-direct load behind MFMA 6.
+template <int NA>
+struct FragSched {
+  static constexpr int kADist = 2;
+  static constexpr bool kSpread = NA == 8;
+  static constexpr int nb_at(int a) {               // B blocks requested in step a
+    if (NA == 4) return a >= 2 ? 4 : 0;
+    return (a == 4 || a == 5) ? 3 : (a == 6 ? 2 : 0);
+  }
+  static constexpr int nb_before(int a) { int n = 0; for (int j = 0; j < a; ++j) n += nb_at(j); return n; }
+  static constexpr int last_b_step() { int l = 0; for (int j = 0; j < NA; ++j) if (nb_at(j) > 0) l = j; return l; }
+  // LDS read instructions issued in step a (ra1 / rb1 instructions per A / B fragment)
+  static constexpr int reads(int a, int ra1, int rb1) { return ra1 + nb_at(((a % NA) + NA) % NA) * rb1; }
+  // Reads that may still be outstanding when step a's operands are needed (the LDS returns data in order): everything
+  // issued after the request of A block a; step 0 also needs the whole B buffer.
+  static constexpr int allowed(int a, int ra1, int rb1) {
+    if (kSpread) {                                  // requests follow the MFMAs: step a's own come after its wait
+      int w = nb_at((((a - kADist) % NA) + NA) % NA) * rb1;
+      for (int j = a - kADist + 1; j <= a - 1; ++j) w += reads(j, ra1, rb1);
+      if (a == 0) {
+        int wb = 0;
+        for (int j = last_b_step() + 1; j <= NA - 1; ++j) wb += reads(j, ra1, rb1);
+        if (wb < w) w = wb;
+      }
+      return w;
+    }
+    int w = 0;                                      // requests precede the step's wait; the B requests precede the A request
+    for (int j = a - kADist + 1; j <= a; ++j) w += reads(j, ra1, rb1);
+    if (a == 0) {
+      int wb = ra1;
+      for (int j = last_b_step() + 1; j <= NA; ++j) wb += reads(j, ra1, rb1);
+      if (wb < w) w = wb;
+    }
+    return w;
+  }
+};
+
 // MFMA with the accumulator pinned, in place, to the accumulation half of the register file: the 256 accumulator
 // registers of a 128 x 128 wavefront block fill that half exactly, and left to itself the register allocator shuffles
 // them through the other half.  Issued as assembly, the instruction is opaque to the compiler's hazard handling; the
@@ -840,8 +884,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   constexpr int NA = BM / 32;                      // A blocks per wavefront = steps per stage
   constexpr int HALF = NA / 2;                     // the barrier sits before step HALF
   constexpr int LA = BM / 64, LB = 4;              // LDS-direct loads per wavefront per stage: A blocks, B blocks
-  constexpr int NBQ = 8 / HALF;                    // B fragments requested per late step
   constexpr int LBQ = LB / HALF;                   // B loads issued per early step
+  typedef FragSched<NA> Sched;
+  constexpr int AD = Sched::kADist;
   constexpr int NSTAGE = 4, AHEAD = 3, A_BYTES = BM * 64, B_BYTES = 256 * 64, STAGE = A_BYTES + B_BYTES;
   constexpr int RA1 = A_RC ? 1 : 2, RB1 = B_RC ? 1 : 2;               // LDS read instructions per fragment
   extern __shared__ __attribute__((aligned(1024))) char lds[];
@@ -902,13 +947,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(LA) : "memory");     // stages 0 and 1 have landed everywhere
 #pragma unroll
   for (int b = 0; b < 8; ++b) fb[0][b] = ab[b].read(stage_base(0) + A_BYTES);
-  fa[0] = aa[0].read(stage_base(0));
-  fa[1] = aa[1].read(stage_base(0));
+#pragma unroll
+  for (int a = 0; a < AD; ++a) fa[a] = aa[a].read(stage_base(0));
 
   // One step: requests, wait for this step's operands, 8 MFMAs with the step's LDS-direct loads among them.
-  // LDS reads complete in order, so "A block a has arrived" is "at most W reads issued after it are outstanding";
-  // A block a was the last request of step a-2, hence W = reads of steps a-1 and a.  Step 0 also needs the whole
-  // B buffer, whose last request precedes the A requests of the last step and of step 0.
+  // LDS reads complete in order, so "A block a has arrived" is "at most W reads issued after it are outstanding"
+  // (FragSched::allowed).
   auto step = [&](int s, auto ac, half8 (&fb_cur)[8], half8 (&fb_nxt)[8]) {
     constexpr int a = decltype(ac)::value;
     if constexpr (a == HALF) {
@@ -917,41 +961,55 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       // past stage s-1, all of whose reads were consumed by MFMAs already issued.
       asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(LA + LB) : "memory");
     }
-    if constexpr (a >= HALF) {
+    constexpr int B0 = Sched::nb_before(a);
+    constexpr int na = (a + AD) % NA;
+    static_assert(Sched::nb_at(a) == 0 || a >= HALF, "the next stage is published by the barrier before step HALF");
+    constexpr bool SPREAD = Sched::kSpread;
+    if constexpr (!SPREAD) {
 #pragma unroll
-      for (int k = 0; k < NBQ; ++k) fb_nxt[NBQ * (a - HALF) + k] = ab[NBQ * (a - HALF) + k].read(stage_base(s + 1) + A_BYTES);
+      for (int k = 0; k < Sched::nb_at(a); ++k) fb_nxt[B0 + k] = ab[B0 + k].read(stage_base(s + 1) + A_BYTES);
+      fa[na] = aa[na].read(stage_base(s + (a + AD) / NA));             // the last AD steps read the next stage (published at step HALF)
     }
-    constexpr int na = (a + 2) % NA;
-    fa[na] = aa[na].read(stage_base(s + (a + 2) / NA));                // the last two steps read the next stage (published at step HALF)
     __builtin_amdgcn_sched_barrier(0);
-    constexpr int N_PREV = RA1 + ((a - 1 >= HALF) ? NBQ * RB1 : 0);    // reads of step a-1 (for a >= 1)
-    constexpr int N_THIS = RA1 + ((a >= HALF) ? NBQ * RB1 : 0);
-    constexpr int W = a == 0 ? 2 * RA1 : N_PREV + N_THIS;
+    constexpr int W = Sched::allowed(a, RA1, RB1);
     if constexpr (a == 0) wait_frags9<W>(fa[0], fb_cur);
     else wait_frag1<W>(fa[a]);
 #pragma unroll
     for (int b = 0; b < 8; ++b) {   // operands swapped: each lane ends up with 4 consecutive output columns of one row
       mfma_acc(acc[a][b], fb_cur[b], fa[a]);
+      if constexpr (SPREAD) {       // one request per gap between MFMAs: the A block after MFMA 0, B blocks after the odd ones
+        if (b == 0) {
+          __builtin_amdgcn_sched_barrier(0);
+          fa[na] = aa[na].read(stage_base(s + (a + AD) / NA));
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        if ((b & 1) && (b >> 1) < Sched::nb_at(a)) {
+          __builtin_amdgcn_sched_barrier(0);
+          fb_nxt[B0 + (b >> 1)] = ab[B0 + (b >> 1)].read(stage_base(s + 1) + A_BYTES);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
       // late steps start stage s+3 (one A block each) into the slot just vacated; early steps finish stage s+2 (B blocks)
+      constexpr int L1 = SPREAD ? 6 : 3, L2A = SPREAD ? 2 : 1, L2B = SPREAD ? 6 : 5;   // MFMAs followed by an LDS-direct load
       if constexpr (a >= HALF) {
-        if (b == 3) {
+        if (b == L1) {
           __builtin_amdgcn_sched_barrier(0);
           issue1(s + AHEAD, std::integral_constant<int, a - HALF>{});
           __builtin_amdgcn_sched_barrier(0);
         }
       } else if constexpr (LBQ == 1) {
-        if (b == 3) {
+        if (b == L1) {
           __builtin_amdgcn_sched_barrier(0);
           issue1(s + AHEAD - 1, std::integral_constant<int, LA + a>{});
           __builtin_amdgcn_sched_barrier(0);
         }
       } else {
-        if (b == 1) {
+        if (b == L2A) {
           __builtin_amdgcn_sched_barrier(0);
           issue1(s + AHEAD - 1, std::integral_constant<int, LA + 2 * a>{});
           __builtin_amdgcn_sched_barrier(0);
         }
-        if (b == 5) {
+        if (b == L2B) {
           __builtin_amdgcn_sched_barrier(0);
           issue1(s + AHEAD - 1, std::integral_constant<int, LA + 2 * a + 1>{});
           __builtin_amdgcn_sched_barrier(0);
