@@ -514,6 +514,53 @@ struct FragAddr {
   }
 };
 
+// The same fragment addressed without arithmetic in the loop: the lane's absolute LDS address inside the first slot of
+// each pair of ring slots sits in a register, and the slot within the pair and the operand's offset inside a stage go
+// into the read's immediate offset (16 bits: a pair of slots plus an operand offset stays below 64 KiB).
+template <int IMM>
+__device__ __forceinline__ half8 lds_read_b128_imm(uint32_t addr) {
+  static_assert(IMM >= 0 && IMM < 65536, "LDS immediate offset");
+  half8 v;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(IMM) : "memory");
+  return v;
+}
+template <int IMM>
+__device__ __forceinline__ uint2v lds_read_tr_b64_imm(uint32_t addr) {
+  static_assert(IMM >= 0 && IMM < 65536, "LDS immediate offset");
+  uint2v v;
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(IMM) : "memory");
+  return v;
+}
+template <bool RC, int BO = 256>
+struct FragAddr4 {
+  uint32_t at[2][RC ? 1 : 2];
+  __device__ __forceinline__ void init(int outer0, int lane, uint32_t lds0, uint32_t pair_bytes) {
+    FragAddr<RC, BO> f;
+    f.init(outer0, lane);
+#pragma unroll
+    for (int p = 0; p < 2; ++p)
+#pragma unroll
+      for (int h = 0; h < (RC ? 1 : 2); ++h) at[p][h] = lds0 + p * pair_bytes + f.off[h];
+  }
+  template <int PAIR, int IMM>
+  __device__ __forceinline__ half8 read() const {
+    if constexpr (RC) {
+      return lds_read_b128_imm<IMM>(at[PAIR][0]);
+    } else {
+      const uint2v lo = lds_read_tr_b64_imm<IMM>(at[PAIR][0]);
+      const uint2v hi = lds_read_tr_b64_imm<IMM>(at[PAIR][1]);
+      uint4v q = {lo[0], lo[1], hi[0], hi[1]};
+      return __builtin_bit_cast(half8, q);
+    }
+  }
+};
+
+// The compiler takes an inline-assembly LDS read to be complete when the statement ends.  A fragment that nothing
+// consumes afterwards (the prefetch past the last stage) would leave its registers free for reuse, for instance as the
+// address of the next LDS-direct load, while the data is still on its way and lands on top of the new value.  Passing
+// such fragments through this statement after the final wait keeps their registers reserved until then.
+__device__ __forceinline__ void keep_until_here(const half8& f) { asm volatile("" ::"v"(f)); }
+
 // Wait until at most NEWER LDS reads issued after these fragments are still outstanding (the LGKM counter is
 // in order and 4 bits wide); the fragments pass through the statement so that their consumers stay below it.
 template <int NEWER>
@@ -634,12 +681,13 @@ __global__ __launch_bounds__(512) void k_gemm_dma(DmaMat A, DmaMat B, Problem pb
     if (wave < 4) publish_end();
     __builtin_amdgcn_sched_barrier(0);
   };
-  int s = 0;
-  for (; s + 1 < nst; s += 2) {
+  // nst is even (the reduction length is a multiple of 64 and splits are cut at multiples of 64), so the loop is the
+  // only copy of the stage code: every prefetched fragment is consumed by the next trip, and none has a dead
+  // destination inside the loop (see keep_until_here).
+  for (int s = 0; s < nst; s += 2) {
     one_stage(s, fb[0]);
     one_stage(s + 1, fb[1]);
   }
-  if (s < nst) one_stage(s, fb[0]);
   // drain the tail prefetches before LDS is released
   asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
 
@@ -919,15 +967,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     if constexpr (q < LA) da.template issue<q>(sc, st + wave * (LA * 1024));
     else db.template issue<q - LA>(sc, st + A_BYTES + wave * (LB * 1024));
   };
-  FragAddr<A_RC, BM> aa[NA];
-  FragAddr<B_RC, 256> ab[8];
-#pragma unroll
-  for (int a = 0; a < NA; ++a) aa[a].init(wm * (BM / 2) + a * 16, lane);
-#pragma unroll
-  for (int b = 0; b < 8; ++b) ab[b].init(wn * 128 + b * 16, lane);
+  static_assert(STAGE + A_BYTES < 65536, "the second slot of a pair plus the B offset fits the LDS immediate");
   const uint32_t lds0 = lds_offset(lds);
+  FragAddr4<A_RC, BM> aa[NA];
+  FragAddr4<B_RC, 256> ab[8];
+#pragma unroll
+  for (int a = 0; a < NA; ++a) aa[a].init(wm * (BM / 2) + a * 16, lane, lds0, 2 * STAGE);
+#pragma unroll
+  for (int b = 0; b < 8; ++b) ab[b].init(wn * 128 + b * 16, lane, lds0, 2 * STAGE);
   half8 fa[NA], fb[2][8];                                              // A blocks of the running stage(s); B blocks, double buffered
-  auto stage_base = [&](int s) { return lds0 + (uint32_t)((s % NSTAGE) * STAGE); };
   auto issue_all = [&](int s, auto lo, auto hi) {                      // loads lo .. hi-1 of stage s
     constexpr int L = decltype(lo)::value, Hh = decltype(hi)::value;
     if constexpr (L + 0 < Hh) issue1(s, std::integral_constant<int, L + 0>{});
@@ -946,15 +994,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   issue_all(2, std::integral_constant<int, 0>{}, std::integral_constant<int, LA>{});
   asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(LA) : "memory");     // stages 0 and 1 have landed everywhere
 #pragma unroll
-  for (int b = 0; b < 8; ++b) fb[0][b] = ab[b].read(stage_base(0) + A_BYTES);
+  for (int b = 0; b < 8; ++b) fb[0][b] = ab[b].template read<0, A_BYTES>();
 #pragma unroll
-  for (int a = 0; a < AD; ++a) fa[a] = aa[a].read(stage_base(0));
+  for (int a = 0; a < AD; ++a) fa[a] = aa[a].template read<0, 0>();
 
   // One step: requests, wait for this step's operands, 8 MFMAs with the step's LDS-direct loads among them.
   // LDS reads complete in order, so "A block a has arrived" is "at most W reads issued after it are outstanding"
   // (FragSched::allowed).
-  auto step = [&](int s, auto ac, half8 (&fb_cur)[8], half8 (&fb_nxt)[8]) {
-    constexpr int a = decltype(ac)::value;
+  // The ring slot of stage s (s % 4) is a compile-time constant SLOT: the loop below is unrolled over the four slots.
+  auto step = [&](int s, auto slotc, auto ac, half8 (&fb_cur)[8], half8 (&fb_nxt)[8]) {
+    constexpr int a = decltype(ac)::value, SLOT = decltype(slotc)::value;
+    constexpr int SLOT_A = (SLOT + (a + Sched::kADist) / NA) % NSTAGE;  // slot of the A block requested in this step
+    constexpr int SLOT_B = (SLOT + 1) % NSTAGE;                         // slot of the next stage's B blocks
+    constexpr int PAIR_A = SLOT_A >> 1, IMM_A = (SLOT_A & 1) * STAGE;
+    constexpr int PAIR_B = SLOT_B >> 1, IMM_B = (SLOT_B & 1) * STAGE + A_BYTES;
     if constexpr (a == HALF) {
       // Stage s+1 is about to be read and the slot of stage s-1 about to be refilled: every wavefront's loads of
       // stage s+1 must have landed (only the loads of stage s+2 may be in flight) and every wavefront must be
@@ -967,8 +1020,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     constexpr bool SPREAD = Sched::kSpread;
     if constexpr (!SPREAD) {
 #pragma unroll
-      for (int k = 0; k < Sched::nb_at(a); ++k) fb_nxt[B0 + k] = ab[B0 + k].read(stage_base(s + 1) + A_BYTES);
-      fa[na] = aa[na].read(stage_base(s + (a + AD) / NA));             // the last AD steps read the next stage (published at step HALF)
+      for (int k = 0; k < Sched::nb_at(a); ++k) fb_nxt[B0 + k] = ab[B0 + k].template read<PAIR_B, IMM_B>();
+      fa[na] = aa[na].template read<PAIR_A, IMM_A>();                  // the last AD steps read the next stage (published at step HALF)
     }
     __builtin_amdgcn_sched_barrier(0);
     constexpr int W = Sched::allowed(a, RA1, RB1);
@@ -980,12 +1033,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       if constexpr (SPREAD) {       // one request per gap between MFMAs: the A block after MFMA 0, B blocks after the odd ones
         if (b == 0) {
           __builtin_amdgcn_sched_barrier(0);
-          fa[na] = aa[na].read(stage_base(s + (a + AD) / NA));
+          fa[na] = aa[na].template read<PAIR_A, IMM_A>();
           __builtin_amdgcn_sched_barrier(0);
         }
         if ((b & 1) && (b >> 1) < Sched::nb_at(a)) {
           __builtin_amdgcn_sched_barrier(0);
-          fb_nxt[B0 + (b >> 1)] = ab[B0 + (b >> 1)].read(stage_base(s + 1) + A_BYTES);
+          fb_nxt[B0 + (b >> 1)] = ab[B0 + (b >> 1)].template read<PAIR_B, IMM_B>();
           __builtin_amdgcn_sched_barrier(0);
         }
       }
@@ -1018,25 +1071,47 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     }
     __builtin_amdgcn_sched_barrier(0);
   };
-  auto one_stage = [&](int s, half8 (&fb_cur)[8], half8 (&fb_nxt)[8]) {
-    step(s, std::integral_constant<int, 0>{}, fb_cur, fb_nxt);
-    step(s, std::integral_constant<int, 1>{}, fb_cur, fb_nxt);
-    step(s, std::integral_constant<int, 2>{}, fb_cur, fb_nxt);
-    step(s, std::integral_constant<int, 3>{}, fb_cur, fb_nxt);
+  auto one_stage = [&](int s, auto slotc, half8 (&fb_cur)[8], half8 (&fb_nxt)[8]) {
+    step(s, slotc, std::integral_constant<int, 0>{}, fb_cur, fb_nxt);
+    step(s, slotc, std::integral_constant<int, 1>{}, fb_cur, fb_nxt);
+    step(s, slotc, std::integral_constant<int, 2>{}, fb_cur, fb_nxt);
+    step(s, slotc, std::integral_constant<int, 3>{}, fb_cur, fb_nxt);
     if constexpr (NA == 8) {
-      step(s, std::integral_constant<int, 4 % NA>{}, fb_cur, fb_nxt);
-      step(s, std::integral_constant<int, 5 % NA>{}, fb_cur, fb_nxt);
-      step(s, std::integral_constant<int, 6 % NA>{}, fb_cur, fb_nxt);
-      step(s, std::integral_constant<int, 7 % NA>{}, fb_cur, fb_nxt);
+      step(s, slotc, std::integral_constant<int, 4 % NA>{}, fb_cur, fb_nxt);
+      step(s, slotc, std::integral_constant<int, 5 % NA>{}, fb_cur, fb_nxt);
+      step(s, slotc, std::integral_constant<int, 6 % NA>{}, fb_cur, fb_nxt);
+      step(s, slotc, std::integral_constant<int, 7 % NA>{}, fb_cur, fb_nxt);
     }
   };
   // nst is even: the reduction length is a multiple of 64 and splits are cut at multiples of 64
-  for (int s = 0; s < nst; s += 2) {
-    one_stage(s, fb[0], fb[1]);
-    one_stage(s + 1, fb[1], fb[0]);
+  typedef std::integral_constant<int, 0> S0;
+  typedef std::integral_constant<int, 1> S1;
+  typedef std::integral_constant<int, 2> S2;
+  typedef std::integral_constant<int, 3> S3;
+  // Where two paths that end in MFMAs meet (the loop's exit and the two-stage tail), the register allocator may place
+  // accumulator copies on the edges; it knows nothing of the latency of an MFMA issued from assembly, so each path
+  // first lets its last MFMAs retire (32 idle cycles, only in the loop's last trip).
+  int s = 0;
+  for (; s + 4 <= nst; s += 4) {
+    one_stage(s, S0{}, fb[0], fb[1]);
+    one_stage(s + 1, S1{}, fb[1], fb[0]);
+    one_stage(s + 2, S2{}, fb[0], fb[1]);
+    one_stage(s + 3, S3{}, fb[1], fb[0]);
+    if (s + 8 > nst) asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+  }
+  if (s < nst) {                                                       // two stages left, in slots 0 and 1
+    one_stage(s, S0{}, fb[0], fb[1]);
+    one_stage(s + 1, S1{}, fb[1], fb[0]);
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
   }
   // drain the tail prefetches before LDS is released, and let the last MFMAs retire before their results are read
   asm volatile("s_nop 15\n\ts_nop 15\n\ts_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+#pragma unroll
+  for (int a = 0; a < NA; ++a) keep_until_here(fa[a]);
+#pragma unroll
+  for (int b = 0; b < 8; ++b) {
+    keep_until_here(fb[0][b]); keep_until_here(fb[1][b]);
+  }
   __builtin_amdgcn_sched_barrier(0);
 
   // ---- epilogue (whole tiles, FP16 store with optional Inf/NaN vote; the host sends only unsplit problems with a
