@@ -314,6 +314,9 @@ def main():
                          "the first ~30 ms of sustained load, and a step here is only ~0.5 ms")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-next", action="store_true", help="skip the kernels beyond the headline path (batch norm, softmax, other optimizers, statistics)")
+    ap.add_argument("--operands", choices=("workload", "zeros"), default="workload",
+                    help="zeros: run the step on all-zero GEMM operands (diagnostic: the GPU's clock under a GEMM depends on the operand "
+                         "bits; on zeros it stays at its maximum, so the difference to the workload's operands is the power limit)")
     ap.add_argument("--no-configs", action="store_true", help="skip the per-pass figures of the other synthetic configurations")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy, so a counter run of this command holds a kernel of known traffic")
@@ -339,6 +342,8 @@ def main():
         return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).to(dev).view(torch.float16)
 
     X, W16, G = d16(c["A"]), d16(c["B"]), d16(c["G"])
+    if args.operands == "zeros":
+        X.zero_(); W16.zero_(); G.zero_()
     Y = torch.empty((n, n), dtype=torch.float16, device=dev)
     dX = torch.empty((n, n), dtype=torch.float16, device=dev)
     dW = torch.empty((n, n), dtype=torch.float16, device=dev)
@@ -476,7 +481,8 @@ def main():
            "preheat_ms": args.preheat_ms,
            "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "fp16", "data": "synthetic",
-           "config": {"workload": "cfg2: square GEMM M=N=K=4096 fwd+dgrad+wgrad, then unscale/check + momentum master update + scaler on the 16.8M-element weight",
+           "config": {"workload": "cfg2: square GEMM M=N=K=4096 fwd+dgrad+wgrad, then unscale/check + momentum master update + scaler on the 16.8M-element weight"
+                                  + (" [DIAGNOSTIC: all-zero GEMM operands]" if args.operands == "zeros" else ""),
                       "loss_scale": 8192, "master_update_elements": n * n},
            "pct_of_fp16_peak": round(100 * value / MFMA_F16_PEAK_TFLOPS, 2),
            "master_update_pct_of_hbm_peak": round(100 * upd_gbs / HBM_PEAK_GBS, 2),
