@@ -865,17 +865,21 @@ struct DmaFilterOC {
 // A block used two steps later and, in the late steps (a >= NA/2, after the stage's barrier), its share of the next
 // stage's 8 B blocks.  With a single wavefront per SIMD every instruction that is not an MFMA delays the next MFMA
 // unless it sits alone in the gap behind one (measured: 4 VALU operations bunched before a step cost 9 cycles, the
-// same 4 placed one per gap cost none; a bunched pair of LDS reads 10 cycles, spread 2-6), so the 256-row kernel
+// same 4 placed one per gap cost none; a bunched pair of LDS reads 10 cycles, spread 2-6), so the kernel
 // issues its requests one per gap: the A block behind MFMA 0, B blocks behind the odd MFMAs (3, 3, 2 of them in steps
-// 4, 5, 6, so that the last one is a whole step old when step 0 needs it), the LDS-direct load behind MFMA 6.
+// 4, 5, 6, so that the last one is a whole step old when step 0 needs it), the LDS-direct load behind MFMA 6.  The
+// 128-row kernel has only two steps behind its barrier: 6 B blocks behind MFMAs 1-6 of step 2, 2 behind MFMAs 1-2 of
+// step 3, the loads behind MFMA 7 (late steps) and MFMAs 2 and 6 (early steps).
 template <int NA>
 struct FragSched {
   static constexpr int kADist = 2;
-  static constexpr bool kSpread = NA == 8;
+  static constexpr bool kSpread = true;
   static constexpr int nb_at(int a) {               // B blocks requested in step a
-    if (NA == 4) return a >= 2 ? 4 : 0;
+    if (NA == 4) return a == 2 ? 6 : (a == 3 ? 2 : 0);
     return (a == 4 || a == 5) ? 3 : (a == 6 ? 2 : 0);
   }
+  static constexpr int b_gap(int k) { return NA == 4 ? k + 1 : 2 * k + 1; }   // MFMA behind which the step's k-th B request sits
+  static constexpr int kLateLoadGap = NA == 4 ? 7 : 6;                        // ... and the late steps' LDS-direct load
   static constexpr int nb_before(int a) { int n = 0; for (int j = 0; j < a; ++j) n += nb_at(j); return n; }
   static constexpr int last_b_step() { int l = 0; for (int j = 0; j < NA; ++j) if (nb_at(j) > 0) l = j; return l; }
   // LDS read instructions issued in step a (ra1 / rb1 instructions per A / B fragment)
@@ -1036,16 +1040,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
           fa[na] = aa[na].template read<PAIR_A, IMM_A>();
           __builtin_amdgcn_sched_barrier(0);
         }
-        if ((b & 1) && (b >> 1) < Sched::nb_at(a)) {
-          __builtin_amdgcn_sched_barrier(0);
-          fb_nxt[B0 + (b >> 1)] = ab[B0 + (b >> 1)].template read<PAIR_B, IMM_B>();
-          __builtin_amdgcn_sched_barrier(0);
-        }
+#pragma unroll
+        for (int k = 0; k < Sched::nb_at(a); ++k)
+          if (b == Sched::b_gap(k)) {
+            __builtin_amdgcn_sched_barrier(0);
+            fb_nxt[B0 + k] = ab[B0 + k].template read<PAIR_B, IMM_B>();
+            __builtin_amdgcn_sched_barrier(0);
+          }
       }
       // late steps start stage s+3 (one A block each) into the slot just vacated; early steps finish stage s+2 (B blocks)
       constexpr int L1 = SPREAD ? 6 : 3, L2A = SPREAD ? 2 : 1, L2B = SPREAD ? 6 : 5;   // MFMAs followed by an LDS-direct load
       if constexpr (a >= HALF) {
-        if (b == L1) {
+        if (b == (SPREAD ? Sched::kLateLoadGap : 3)) {
           __builtin_amdgcn_sched_barrier(0);
           issue1(s + AHEAD, std::integral_constant<int, a - HALF>{});
           __builtin_amdgcn_sched_barrier(0);
