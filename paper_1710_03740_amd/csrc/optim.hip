@@ -129,7 +129,7 @@ __device__ __forceinline__ int stat_bin(_Float16 h) {
 }
 
 // Every thread counts into its own column of an LDS table [42][256] (conflict-free: the bank is the thread), 16-byte
-// vectors, grid-stride; a workgroup then adds its 42 totals to the global histogram.  The largest finite magnitude
+// vectors, eight in flight per thread, grid-stride; a workgroup then adds its 42 totals to the global histogram.  The largest finite magnitude
 // is kept per lane as packed 16-bit values biased by 0x0400, so that Inf / NaN (>= 0x7C00) turn negative and drop
 // out of a signed maximum; it travels as its bit pattern (order-preserving for magnitudes).
 template <bool VEC>
@@ -155,7 +155,20 @@ __global__ __launch_bounds__(kBS) void k_grad_stats(const uint16_t* __restrict__
   if constexpr (VEC) {
     const size_t nvec = n >> 3;
     done = nvec << 3;
-    for (size_t v = tid; v < nvec; v += stride) {
+    // eight vectors in flight per thread: with 12 wavefronts per CU (the table takes 42 KiB of LDS per workgroup) one
+    // 16-byte load per thread at a time leaves the memory system idle most of the time
+    size_t v = tid;
+    constexpr int kInFlight = 8;
+    for (; v + (kInFlight - 1) * stride < nvec; v += kInFlight * stride) {
+      ou4 q[kInFlight];
+#pragma unroll
+      for (int u = 0; u < kInFlight; ++u) q[u] = __builtin_nontemporal_load(reinterpret_cast<const ou4*>(g) + v + u * stride);
+#pragma unroll
+      for (int u = 0; u < kInFlight; ++u)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) two(q[u][i]);
+    }
+    for (; v < nvec; v += stride) {
       const ou4 q = __builtin_nontemporal_load(reinterpret_cast<const ou4*>(g) + v);
 #pragma unroll
       for (int i = 0; i < 4; ++i) two(q[i]);
