@@ -89,11 +89,11 @@ def test_leading_dimensions_and_unaligned_bases():
 
 @pytest.mark.parametrize("pad", [0, 8, 4, 1])
 def test_whole_tile_kernels_over_more_tiles_than_cus(pad):
-    """272 whole 256 x 256 tiles (more than one per CU), reduction depth of 4 and 6 stages, with output row strides
+    """272 whole 256 x 256 tiles (more than one per CU), reduction depth of 4, 6 and 10 stages, with output row strides
     that keep 16-byte, 8-byte and 2-byte alignment: every store path of the whole-tile kernels."""
     M, N = 4352, 4096
     rng = np.random.default_rng(77 + pad)
-    for K in ((128, 192) if pad == 0 else (128,)):
+    for K in ((128, 192, 320) if pad == 0 else (128,)):      # 4, 6 and 10 stages: whole trips of the 4-stage loop, with and without its 2-stage tail
         X = rng.standard_normal((M, K)).astype(np.float16)
         W = (rng.standard_normal((K, N)) * 0.05).astype(np.float16)
         Yb = torch.full((M, N + pad), 7.0, dtype=torch.float16, device="cuda")
@@ -303,7 +303,7 @@ def test_outputs_with_few_rows_and_many_columns():
     passes, with the folded ReLU forms and the overflow vote."""
     I, J = 384, 16384
     rng = np.random.default_rng(21)
-    for K in (64, 192):
+    for K in (64, 192, 320):                                 # 2, 6 and 10 stages (tail only; loop + tail; two trips + tail)
         X = rng.standard_normal((I, K)).astype(np.float16)
         W = (rng.standard_normal((K, J)) * 0.05).astype(np.float16)
         y, sa, s = gemm.gemm_fwd(X, W, full=True)
