@@ -281,7 +281,7 @@ def measure_configs(torch, mpt, np, dev, workloads):
     name = "cfg4 conv 3x3 256x14x14x256 -> 256"
     mfma_row(name, "fwd (streamed, gathered operand)", fl, timeit(lambda: mpt.mpt_conv3x3_fwd(x, w, y, ws)))
     mfma_row(name, "dgrad (streamed, gathered operand, filter read outer-contiguous)", fl, timeit(lambda: mpt.mpt_conv3x3_dgrad(dy, w, dx, ws)))
-    mfma_row(name, "wgrad (general kernel, split reduction through the workspace)", fl, timeit(lambda: mpt.mpt_conv3x3_wgrad(x, dy, dw, ws=ws)))
+    mfma_row(name, "wgrad (streamed, image gathered per tap, split reduction through the workspace)", fl, timeit(lambda: mpt.mpt_conv3x3_wgrad(x, dy, dw, ws=ws)))
     del x, w, dy, y, dx, dw, ws
 
     # ---- cfg 5: one dynamic-scale step on the 116M-element flat buffer: check, momentum update, scaler (device resident)

@@ -861,6 +861,49 @@ struct DmaFilterOC {
   }
 };
 
+// The image read as B(r = flat pixel (n, y, x), o = tap * Cc + c) for the weight-gradient pass: outer-contiguous, one
+// reduction row is the Cc channels of the pixel shifted by the tap.  Cc is a multiple of 256, so a tile column of 256
+// outer indices lies inside one tap: the shift is the same for the whole workgroup, and a lane needs per load the
+// (y, x) of its pixel for one bounds test (two exact divisions) and one address.
+struct DmaImgOCSrc {
+  const uint16_t* base;
+  int H, W, Cc;
+  FastDiv dW, dH;
+};
+struct DmaImgOC {
+  typedef DmaImgOCSrc Src;
+  static constexpr bool kRC = false;
+  static constexpr int NB = 4;
+  const uint16_t* base;
+  int H, W, Cc, dy, dx, r0;
+  int32_t row[NB];                 // reduction row inside a stage of this lane's piece of block k
+  int32_t coff[NB];                // channel offset of its 16-byte chunk (the LDS swizzle depends on the row)
+  FastDiv dW, dH;
+  __device__ __forceinline__ void init(const Src& m, int o0, int r0_, int wave, int lane) {
+    base = m.base; H = m.H; W = m.W; Cc = m.Cc; dW = m.dW; dH = m.dH; r0 = r0_;
+    const int tap = o0 / m.Cc, c0 = o0 - tap * m.Cc;
+    const int tr = tap / 3, ts = tap - 3 * tr;
+    dy = tr - 1; dx = ts - 1;
+    const int pc = lane & 31;
+#pragma unroll
+    for (int k = 0; k < NB; ++k) {
+      row[k] = (wave * NB + k) * 2 + (lane >> 5);
+      coff[k] = c0 + (2 * ((pc >> 1) ^ oc_key(row[k])) + (pc & 1)) * 8;
+    }
+  }
+  template <int K>
+  __device__ __forceinline__ void issue(int stage_rel, char* lds_blocks) const {
+    const uint32_t p = (uint32_t)(r0 + stage_rel * 32 + row[K]);
+    uint32_t q, x, n, y;
+    dW.divmod(p, q, x);
+    dH.divmod(q, n, y);
+    const int yy = (int)y + dy, xx = (int)x + dx;
+    const bool inside = (unsigned)yy < (unsigned)H && (unsigned)xx < (unsigned)W;
+    const uint16_t* src = inside ? base + ((int64_t)((int)p + dy * W + dx) * Cc + coff[K]) : reinterpret_cast<const uint16_t*>(k_zero_line);
+    __builtin_amdgcn_global_load_lds((global_void_ptr)src, (lds_void_ptr)(lds_blocks + K * 1024), 16, 0, 0);
+  }
+};
+
 // Fragment-request schedule of the one-wavefront-per-SIMD kernel.  A stage is NA steps of 8 MFMAs; step a requests the
 // A block used two steps later and, in the late steps (a >= NA/2, after the stage's barrier), its share of the next
 // stage's 8 B blocks.  With a single wavefront per SIMD every instruction that is not an MFMA delays the next MFMA
@@ -927,7 +970,10 @@ __device__ __forceinline__ void wait_frags9(half8& f, half8 (&g)[8]) {
                : "memory");
 }
 
-template <class AOp, class BOp, int BM>
+// F32OUT selects the epilogue at compile time (both in one kernel spill): false = FP16 store through LDS; true = FP32
+// store, accumulate or split partial straight from the accumulators, 16 bytes per lane (used for the convolution's
+// weight gradient, a long split reduction; on short ones k_gemm_dma's two wavefronts per SIMD are faster).
+template <class AOp, class BOp, int BM, bool F32OUT = false>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_gemm_dma4(typename AOp::Src A, typename BOp::Src B, Problem pb, Epilogue ep) {
   constexpr bool A_RC = AOp::kRC, B_RC = BOp::kRC;
   // BM = 256: tile 256 x 256, 128 x 128 per wavefront.  BM = 128: tile 128 x 256, 64 x 128 per wavefront, for problems
@@ -1120,11 +1166,32 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   }
   __builtin_amdgcn_sched_barrier(0);
 
-  // ---- epilogue (whole tiles, FP16 store with optional Inf/NaN vote; the host sends only unsplit problems with a
-  // 16-byte aligned output and ld % 8 == 0 here).
+  // ---- epilogue (whole tiles; the host sends only 16-byte aligned outputs with whole 16-byte rows here, and FP16
+  // stores only of unsplit problems).
   // acc[a][b][e]: row i = 16a + lane%16, column j = 16b + 4*(lane/16) + e of the wavefront's (BM/2) x 128 block.
   bool bad = false;
-  {
+  if constexpr (F32OUT) {
+    const int64_t split_off = (ep.mode == 3) ? (int64_t)sp * pb.I * pb.J : 0;
+    float* out = reinterpret_cast<float*>(ep.out) + split_off + (int64_t)(i0 + wm * (BM / 2) + (lane & 15)) * ep.ld + j0 + wn * 128 + ((lane >> 4) << 2);
+#pragma unroll
+    for (int a = 0; a < NA; ++a)
+#pragma unroll
+      for (int b = 0; b < 8; ++b) {
+        asm volatile("" : "+a"(acc[a][b]) : : "memory");              // one block at a time out of the accumulation registers
+        float* o = out + (int64_t)(a * 16) * ep.ld + b * 16;
+        float4v v = acc[a][b];
+        if (ep.mode == 2) {
+          const float4v old = *reinterpret_cast<const float4v*>(o);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = __fadd_rn(old[e], v[e]);
+        }
+        if (ep.flag && ep.mode != 3) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) bad |= (__float_as_uint(v[e]) & 0x7F800000u) == 0x7F800000u;
+        }
+        *reinterpret_cast<float4v*>(o) = v;
+      }
+  } else {
     // FP16 store through LDS, so that global stores are whole 256-byte row segments instead of 32-byte pieces:
     // each wavefront rounds its block to FP16 into its own part of the (now idle) ring as [BM/2 rows][256 B],
     // 16-byte unit u of row r kept at unit u ^ (r & 15), then streams it out 16 bytes per lane, 16 lanes per row.
@@ -1163,7 +1230,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       *reinterpret_cast<uint4v*>(out + (int64_t)r * ep.ld) = q;
     }
   }
-  if (ep.flag != nullptr) {
+  if (ep.flag != nullptr && !(F32OUT && ep.mode == 3)) {
     const unsigned long long vote = __builtin_amdgcn_ballot_w64(bad);
     if (vote != 0ull && lane == 0) atomicOr(ep.flag, 1u);
   }
@@ -1175,8 +1242,18 @@ __global__ __launch_bounds__(256) void k_split_reduce(const float* __restrict__ 
   const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
   bool bad = false;
   if (idx < total) {
+    // eight partials in flight per thread (a dependent chain of single loads is bound by the memory latency:
+    // 28 splits took 17 us), added in split order all the same
     float s = part[idx];
-    for (int k = 1; k < splits; ++k) s = __fadd_rn(s, part[(int64_t)k * total + idx]);
+    int k = 1;
+    for (; k + 8 <= splits; k += 8) {
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = part[(int64_t)(k + u) * total + idx];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) s = __fadd_rn(s, v[u]);
+    }
+    for (; k < splits; ++k) s = __fadd_rn(s, part[(int64_t)k * total + idx]);
     const int64_t i = idx / J, j = idx - i * J;
     if (ep.mode == 0) {
       const _Float16 h = (_Float16)s;
@@ -1543,6 +1620,43 @@ extern "C" int mpt_conv3x3_dgrad(void* stream, int64_t Nb, int64_t H, int64_t W,
   return run(static_cast<hipStream_t>(stream), A, B, true, true, P, (int)C, R, ep, ws, ws_bytes);
 }
 
+namespace {
+// Weight gradient of a whole-tile convolution (output channels and input channels multiples of 256, pixel count a
+// multiple of 64) on the streamed kernel: A = dy as a plain outer-contiguous matrix, B = the image gathered per tap.
+// The reduction over the pixels is long and the output small, so it is normally split through the workspace.
+bool try_launch_conv_wgrad_dma(hipStream_t s, const uint16_t* x, const uint16_t* dy, int64_t H, int64_t W, int64_t C, int64_t Kf, int64_t P,
+                               const Epilogue& ep, void* ws, size_t ws_bytes, int& status) {
+  static const bool enabled = mpt_env_int("MPT_GEMM_STREAMED", 1) != 0 && mpt_env_int("MPT_CONV_STREAMED", 1) != 0;
+  const int64_t J = 9 * C;
+  if (!enabled || (Kf % 256) || (C % 256) || (P % 64) || P * C >= (1LL << 31) || P * Kf >= (1LL << 31)) return false;
+  const Plan pl = make_plan(Kf, J, P, ws != nullptr);
+  if (!pl.big) return false;
+  if (ws != nullptr && ws_bytes < plan_ws_bytes(pl, Kf, J)) { status = MPT_ERR_WORKSPACE; return true; }
+  const DmaImgOCSrc B{x, (int)H, (int)W, (int)C, FastDiv((uint32_t)W), FastDiv((uint32_t)H)};
+  Problem pb{(int)Kf, (int)J, (int)P, pl.tiles_i, pl.tiles_j, pl.splits, pl.ktiles_per_split};
+  const unsigned grid = (unsigned)((int64_t)pl.tiles_i * pl.tiles_j * pl.splits);
+  if (pl.splits > 1) {
+    auto k = k_gemm_dma4<DmaOperand4<false, 256>, DmaImgOC, 256, true>;
+    static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, 4 * 32768), true);
+    (void)once;
+    Epilogue first = ep;
+    first.out = ws; first.ld = J; first.mode = 3; first.flag = nullptr;
+    hipLaunchKernelGGL(k, dim3(grid), dim3(256), 4 * 32768, s, DmaMat{dy, Kf}, B, pb, first);
+    if (hipGetLastError() != hipSuccess) { status = MPT_ERR_HIP; return true; }
+    const int64_t total = Kf * J;
+    hipLaunchKernelGGL(k_split_reduce, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, reinterpret_cast<const float*>(ws), pl.splits,
+                       (int)Kf, (int)J, ep);
+  } else {
+    auto k = k_gemm_dma4<DmaOperand4<false, 256>, DmaImgOC, 256, false>;
+    static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, 4 * 32768), true);
+    (void)once;
+    hipLaunchKernelGGL(k, dim3(grid), dim3(256), 4 * 32768, s, DmaMat{dy, Kf}, B, pb, ep);
+  }
+  status = hipGetLastError() == hipSuccess ? MPT_OK : MPT_ERR_HIP;
+  return true;
+}
+}  // namespace
+
 extern "C" int mpt_conv3x3_wgrad(void* stream, int64_t Nb, int64_t H, int64_t W, int64_t C, int64_t Kf, const uint16_t* x,
                                  const uint16_t* dy, uint16_t* dw, uint32_t* flag, void* ws, size_t ws_bytes) {
   if (x == nullptr || dy == nullptr || dw == nullptr) return MPT_ERR_NULL;
@@ -1550,6 +1664,11 @@ extern "C" int mpt_conv3x3_wgrad(void* stream, int64_t Nb, int64_t H, int64_t W,
   if (!mpt_aligned(x, 16) || !mpt_aligned(dy, 16) || !mpt_aligned(dw, 16) || (flag && !mpt_aligned(flag, 4)) ||
       (ws && !mpt_aligned(ws, 16)))
     return MPT_ERR_ALIGN;
+  {
+    int st = MPT_OK;
+    const Epilogue epw{dw, 9 * C, 0, flag, 0, nullptr, 0};
+    if (try_launch_conv_wgrad_dma(static_cast<hipStream_t>(stream), x, dy, H, W, C, Kf, Nb * H * W, epw, ws, ws_bytes, st)) return st;
+  }
   const int P = (int)(Nb * H * W), J = (int)(9 * C);
   MatOC A{dy, Kf, (int)Kf, P};
   ImgOC B{x, (int)H, (int)W, (int)C, J, P, FastDiv((uint32_t)(H * W)), FastDiv((uint32_t)W), FastDiv((uint32_t)C)};

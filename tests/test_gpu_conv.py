@@ -69,7 +69,7 @@ def test_cfg4_resnet_block_full_size():
     gemm_check(dw, o, sa, s, "cfg4 wgrad")
 
 
-@pytest.mark.parametrize("Nb,H,W,C,Kf", [(64, 14, 14, 64, 512), (50, 16, 16, 256, 256), (32, 7, 56, 128, 256)])
+@pytest.mark.parametrize("Nb,H,W,C,Kf", [(64, 14, 14, 64, 512), (50, 16, 16, 256, 256), (32, 7, 56, 128, 256), (12, 8, 8, 512, 256)])
 def test_whole_tile_shapes_forward_and_input_gradient(Nb, H, W, C, Kf):
     """Pixel counts that are whole tiles (49 x 256 rows with two tile columns; 100 x 128 rows; a wide, flat image):
     the streamed forward and input-gradient kernels with the gathered operand, including image borders in every
@@ -92,3 +92,7 @@ def test_whole_tile_shapes_forward_and_input_gradient(Nb, H, W, C, Kf):
     yi, dxi, _ = run_all(xi, wi, dyi, False)
     assert np.array_equal(fp16.bits(yi), fp16.bits(conv.conv3x3_fwd(xi, wi)[0]))
     assert np.array_equal(fp16.bits(dxi), fp16.bits(conv.conv3x3_dgrad(dyi, wi)[0]))
+    # weight gradient with the split workspace (the streamed kernel with the image gathered per tap where the channel
+    # counts are multiples of 256): integer sums are exact in the FP32 partials and in FP16
+    _, _, dwi = run_all(xi, wi, dyi, True)
+    assert np.array_equal(fp16.bits(dwi), fp16.bits(conv.conv3x3_wgrad(xi, dyi)[0]))
