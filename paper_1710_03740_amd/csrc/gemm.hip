@@ -5,9 +5,11 @@
 // Three kernels compute C[i,j] = sum_r A(i,r) * B(r,j):
 //   k_gemm       the general one: any shape, alignment and operand view (plain matrices, gathered image windows,
 //                filter slices), FP16 / FP32 / accumulating stores, split partials;
-//   k_gemm_dma4  whole 256 x 256 (or 128 x 256) tiles of aligned plain matrices with an FP16 store: operands
-//                streamed global -> LDS, one wavefront per SIMD;
-//   k_gemm_dma   the same streaming with two wavefronts per SIMD, for split partials and odd output strides.
+//   k_gemm_dma4  whole 256 x 256 (or 128 x 256) tiles of aligned operands - plain matrices, or the convolution's gathered
+//                image and filter - with an FP16 store (or, for the convolution's weight gradient, FP32 split partials):
+//                operands streamed global -> LDS, one wavefront per SIMD;
+//   k_gemm_dma   the same streaming with two wavefronts per SIMD, for FP32 outputs of plain matrices (store, accumulate,
+//                split partials) and odd output strides.
 // k_gemm_dma4 is the one the square 4096^3 workload runs on.
 //
 // k_gemm works on a BM x BN tile per workgroup with v_mfma_f32_32x32x16_f16.  Operands differ only in how a
