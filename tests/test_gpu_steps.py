@@ -130,6 +130,64 @@ def test_cfg1_mlp_free_running_device_only():
     assert np.abs(host(w1_32) - ow[0]).max() < 1e-4 * np.abs(ow[0]).max() + 1e-6
 
 
+def test_cfg1_mlp_step_replayed_from_a_hip_graph():
+    """The library allocates nothing, never synchronises and clears its scratch with kernels, so a whole step can be
+    captured once and replayed.  Three replays, with eager work of the same library and a synchronisation between them,
+    must leave exactly the bits that three eager steps leave."""
+    c = workloads.mlp()
+    x, lab = dev16(c["x"]), dev(c["labels"])
+    S, inv, lr = c["scale"], 1.0 / c["scale"], 0.05
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    L = torch.zeros(1, dtype=torch.float32, device="cuda")
+    R = torch.zeros(256, dtype=torch.float32, device="cuda")
+    h1, logits, dlog = _empty16(256, 1024), _empty16(256, 10), _empty16(256, 10)
+    dw2, dy1, dw1 = _empty16(1024, 10), _empty16(256, 1024), _empty16(1024, 1024)
+    w1_32, w2_32 = dev(c["w1_32"].copy()), dev(c["w2_32"].copy())
+    w1, w2 = dev16(c["w1_16"]), dev16(c["w2_16"])
+    ws = torch.empty(max([mpt.mpt_gemm_workspace_bytes(op, 256, n_, 1024) for op in (0, 1, 2) for n_ in (1024, 10)] + [16]) // 4,
+                     dtype=torch.float32, device="cuda")
+
+    def step():
+        mpt.mpt_gemm_fwd_relu(x, w1, h1, ws); mpt.mpt_gemm_fwd(h1, w2, logits, ws)
+        mpt.mpt_softmax_xent_scaled(logits, lab, S, dlog, L, R)
+        mpt.mpt_gemm_wgrad(h1, dlog, dw2, flag=flag, ws=ws); mpt.mpt_gemm_dgrad_relu(dlog, w2, h1, dy1, ws)
+        mpt.mpt_gemm_wgrad(x, dy1, dw1, flag=flag, ws=ws)
+        mpt.mpt_master_update(w1_32, None, dw1, w1, inv, lr, 0.0, flag)
+        mpt.mpt_master_update(w2_32, None, dw2, w2, inv, lr, 0.0, flag)
+
+    def reset():
+        w1_32.copy_(dev(c["w1_32"].copy())); w2_32.copy_(dev(c["w2_32"].copy()))
+        w1.copy_(dev16(c["w1_16"])); w2.copy_(dev16(c["w2_16"]))
+
+    eager = []
+    for _ in range(3):
+        step()
+        eager.append((host(w1_32).copy(), host(w2_32).copy(), float(L.item())))
+    assert eager[2][2] < eager[0][2]
+    reset()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                   # first use of every kernel happens outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    reset()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step()
+    reset()
+    scratch = _empty16(256, 1024)
+    for k in range(3):
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(host(w1_32).view(np.uint32), eager[k][0].view(np.uint32)), "replay %d" % k
+        assert np.array_equal(host(w2_32).view(np.uint32), eager[k][1].view(np.uint32)), "replay %d" % k
+        assert float(L.item()) == eager[k][2]
+        mpt.mpt_gemm_fwd(x, w1, scratch, ws)     # eager work of the same library between replays
+        torch.cuda.synchronize()
+    assert int(flag.item()) == 0
+
+
 @pytest.mark.parametrize("t", [0, 19])
 def test_cfg3_lstmp_gemms_teacher_forced(t):
     c = workloads.lstmp(steps=20)
