@@ -453,7 +453,21 @@ def main():
                        "kernel": "k_master_update (momentum, FP16 grad), 116M elements, 20 B/element, 2 elements per thread",
                        "avg_launch_us": round(upd_ms * 1e3, 2),
                        "unscale_check_GBs": round(2.0 * N_FLAT / (chk_ms * 1e-3) / 1e9, 1)}
-    del w, m, g, h, pool
+    # the single-pass form (overflow vote and update in one read of the gradient, results into a second buffer set)
+    w2, m2, h2 = torch.empty_like(w), torch.empty_like(m), torch.empty_like(h)
+    flag.zero_()
+    preheat(torch, lambda: mpt.mpt_master_update_fused(w, m, g, w2, m2, h2, 2.0 ** -16, lr, mu, flag), 40.0)
+    e0.record()
+    for _ in range(reps):
+        mpt.mpt_master_update_fused(w, m, g, w2, m2, h2, 2.0 ** -16, lr, mu, flag)
+    e1.record()
+    torch.cuda.synchronize()
+    fus_ms = e0.elapsed_time(e1) / reps
+    roofline_update["single_pass"] = {"kernel": "k_master_update_fused: Inf/NaN vote + momentum update + FP16 copy in one pass, ping-pong buffers, 20 B/element",
+                                      "avg_launch_us": round(fus_ms * 1e3, 2), "achieved": round(20.0 * N_FLAT / (fus_ms * 1e-3) / 1e9, 1),
+                                      "frac": round(20.0 * N_FLAT / (fus_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                                      "two_kernel_path_us": round((upd_ms + chk_ms) * 1e3, 2)}
+    del w, m, g, h, pool, w2, m2, h2
 
     next_rows = None if args.no_next else measure_next(torch, mpt, np, dev, not args.no_cpu_baseline)
 

@@ -198,6 +198,32 @@ int mpt_master_update(void* stream, size_t n, float* w32_dev, float* m32_dev,
                       float lr, float momentum, const uint32_t* flag_dev);
 
 /* ------------------------------------------------------------------------- *
+ * The same step in ONE pass over the gradient (Sec. 3.2: the overflow test and
+ * the unscaled update read the same values): 20 B per element with momentum
+ * and an FP16 gradient instead of 2 + 20 for mpt_unscale_check followed by
+ * mpt_master_update.  Whether the step must be skipped is known only once every
+ * gradient has been seen, so the results go to a second set of buffers:
+ *   flag_dev[0] |= 1 if any stored gradient is Inf or NaN (tested on the stored
+ *                    bits; at most one atomic per wavefront);
+ *   w32_out, m32_out, w16_out receive the update of mpt_master_update computed
+ *                    as if the step were taken, always.
+ * The caller adopts the output set as the current state only if the flag
+ * stayed 0 (swap the two sets' roles), and keeps the input set otherwise; with
+ * the flag set the outputs hold arithmetic on Inf / NaN and must not be used.
+ * The input set is never written.  m32_in and m32_out are both NULL (plain SGD)
+ * or both given.  The output buffers must not overlap the input buffers (ARG).
+ * Pairs of elements move together when the FP32 arrays are 8-byte and the FP16
+ * arrays 4-byte aligned, else one at a time.  Costs 10 B per element of extra
+ * memory for the second set.
+ * Errors: NULL, ARG (as mpt_master_update; overlap; one momentum pointer only), ALIGN.
+ * ------------------------------------------------------------------------- */
+int mpt_master_update_fused(void* stream, size_t n, const float* w32_in_dev, const float* m32_in_dev,
+                            const void* grad_dev, int grad_is_fp32,
+                            float* w32_out_dev, float* m32_out_dev, uint16_t* w16_out_dev,
+                            float inv_scale, const mpt_scaler* scaler_dev,
+                            float lr, float momentum, uint32_t* flag_dev);
+
+/* ------------------------------------------------------------------------- *
  * Pointwise / reduction glue for a whole step on the device (Sec. 3.3: softmax
  * reduces in FP32 with FP16 input and output; non-linearities are pointwise).
  *   relu_fwd:  h[i]  = max(y[i], 0)

@@ -74,6 +74,17 @@ def master_update(w32, m32, grad, inv_scale, lr, momentum, flag, w16=None):
     return w_new, m_new, rne16(w_new.astype(np.float64))
 
 
+def master_update_fused(w32, m32, grad, inv_scale, lr, momentum):
+    """The same step as one pass over the gradient (Sec. 3.2: the overflow test and the update are two uses of
+    one read).  A skipped step must leave the state untouched, yet whether to skip is only known once every gradient
+    has been seen; so the pass writes its results to a second set of buffers and reports the flag, and the caller adopts
+    the second set only if the flag is clear.  Returns (flag, w32', m32' or None, w16'): the flag of overflow_flag on
+    this gradient and the outputs of master_update computed as if the step were taken.  With the flag set the outputs
+    are not to be used (they hold the arithmetic on Inf / NaN)."""
+    w, m, h = master_update(w32, m32, grad, inv_scale, lr, momentum, 0)
+    return overflow_flag(grad), w, m, h
+
+
 def master_update_wide(w32, m32, grad, inv_scale, lr, momentum):
     """Information only: the same step with FP64 intermediates and one FP32
     rounding per stored value.  A per-step result of master_update lies within

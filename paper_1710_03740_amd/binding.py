@@ -57,6 +57,7 @@ SIGNATURES = {
     "mpt_loss_scale_update_dev": (c_i, [c_vp, c_vp, c_vp]),
     "mpt_unscale_check": (c_i, [c_vp, c_vp, c_i, c_sz, c_f, c_vp, c_vp]),
     "mpt_master_update": (c_i, [c_vp, c_sz, c_vp, c_vp, c_vp, c_i, c_vp, c_f, c_vp, c_f, c_f, c_vp]),
+    "mpt_master_update_fused": (c_i, [c_vp, c_sz, c_vp, c_vp, c_vp, c_i, c_vp, c_vp, c_vp, c_f, c_vp, c_f, c_f, c_vp]),
     "mpt_relu_fwd": (c_i, [c_vp, c_sz, c_vp, c_vp]),
     "mpt_relu_bwd": (c_i, [c_vp, c_sz, c_vp, c_vp, c_vp]),
     "mpt_softmax_xent_scaled": (c_i, [c_vp, c_i64, c_i64, c_vp, c_i64, c_vp, c_f, c_vp, c_vp, c_vp, c_i64]),
@@ -207,6 +208,13 @@ def mpt_master_update(w32, m32, grad, w16, inv_scale, lr, momentum, flag=None, s
     _check("mpt_master_update", lib().mpt_master_update(_stream(), w32.numel(), _p(w32), _p(m32), _p(grad),
                                                         1 if grad.dtype == torch.float32 else 0, _p(w16),
                                                         inv_scale, _p(scaler_dev), lr, momentum, _p(flag)))
+
+
+def mpt_master_update_fused(w32_in, m32_in, grad, w32_out, m32_out, w16_out, inv_scale, lr, momentum, flag, scaler_dev=None):
+    _dev(w32_in, m32_in, grad, w32_out, m32_out, w16_out, flag, scaler_dev)
+    _check("mpt_master_update_fused", lib().mpt_master_update_fused(_stream(), w32_in.numel(), _p(w32_in), _p(m32_in), _p(grad),
+                                                                    1 if grad.dtype == torch.float32 else 0, _p(w32_out), _p(m32_out),
+                                                                    _p(w16_out), inv_scale, _p(scaler_dev), lr, momentum, _p(flag)))
 
 
 def mpt_optimizer_update(kind, hp, w32, state1, state2, grad, w16, inv_scale, flag=None, scaler_dev=None):

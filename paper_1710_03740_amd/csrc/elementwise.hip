@@ -117,6 +117,72 @@ __global__ __launch_bounds__(BS) void k_master_update(
   }
 }
 
+// One pass over the gradient: overflow vote and update together, results into a second set of buffers (the caller
+// adopts them only if the flag stayed clear).  Same access shape as k_master_update; PAIRS = false is the
+// element-wise form for buffers that are only element-aligned.
+template <bool MOM, bool G32, bool PAIRS>
+__global__ __launch_bounds__(kThreads) void k_master_update_fused(
+    size_t n, const float* __restrict__ w_in, const float* __restrict__ m_in, const void* __restrict__ grad,
+    float* __restrict__ w_out, float* __restrict__ m_out, uint16_t* __restrict__ h_out, float inv_scale,
+    const mpt_scaler* __restrict__ scaler, float lr, float mu, uint32_t* __restrict__ flag) {
+  const float inv = scaler != nullptr ? scaler->inv_scale : inv_scale;
+  const size_t stride = (size_t)gridDim.x * kThreads;
+  const size_t tid = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  bool bad = false;
+  auto one = [&](size_t i) {
+    float graw;
+    if constexpr (G32) {
+      graw = reinterpret_cast<const float*>(grad)[i];
+      bad |= float_special(__float_as_uint(graw));
+    } else {
+      const uint16_t b = reinterpret_cast<const uint16_t*>(grad)[i];
+      bad |= (b & 0x7C00u) == 0x7C00u;
+      graw = (float)__builtin_bit_cast(_Float16, b);
+    }
+    float m = 0.f;
+    if constexpr (MOM) m = m_in[i];
+    const float w = step1<MOM>(w_in[i], m, graw, inv, lr, mu);
+    w_out[i] = w;
+    if constexpr (MOM) m_out[i] = m;
+    reinterpret_cast<_Float16*>(h_out)[i] = (_Float16)w;
+  };
+  if constexpr (PAIRS) {
+    const size_t npair = n >> 1;
+    for (size_t q = tid; q < npair; q += stride) {
+      float g[2];
+      if constexpr (G32) {
+        const f2 a = ld<true>(reinterpret_cast<const f2*>(grad) + q);
+        g[0] = a[0]; g[1] = a[1];
+        bad |= float_special(__float_as_uint(a[0])) | float_special(__float_as_uint(a[1]));
+      } else {
+        const h2 a = ld<true>(reinterpret_cast<const h2*>(grad) + q);
+        const uint32_t b = __builtin_bit_cast(uint32_t, a);
+        bad |= ((b & 0x7C00u) == 0x7C00u) | ((b & 0x7C000000u) == 0x7C000000u);
+        g[0] = (float)a[0]; g[1] = (float)a[1];
+      }
+      f2 w = ld<true>(reinterpret_cast<const f2*>(w_in) + q);
+      f2 m = {0, 0};
+      if constexpr (MOM) m = ld<true>(reinterpret_cast<const f2*>(m_in) + q);
+      h2 h;
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        float mi = m[i];
+        w[i] = step1<MOM>(w[i], mi, g[i], inv, lr, mu);
+        m[i] = mi;
+        h[i] = (_Float16)w[i];
+      }
+      st<true>(reinterpret_cast<f2*>(w_out) + q, w);
+      if constexpr (MOM) st<true>(reinterpret_cast<f2*>(m_out) + q, m);
+      st<true>(reinterpret_cast<h2*>(h_out) + q, h);
+    }
+    if ((n & 1) && tid == 0) one(n - 1);
+  } else {
+    for (size_t i = tid; i < n; i += stride) one(i);
+  }
+  const unsigned long long vote = __builtin_amdgcn_ballot_w64(bad);
+  if (vote != 0ull && (threadIdx.x & 63) == 0) atomicOr(flag, 1u);
+}
+
 // Same step for buffers that are only element-aligned: one element per thread per trip.
 template <bool MOM, bool G32>
 __global__ __launch_bounds__(kThreads) void k_master_update_scalar(
@@ -553,6 +619,41 @@ extern "C" int mpt_master_update(void* stream, size_t n, float* w32, float* m32,
     else     { if (g32) MPT_MS(false, true); else MPT_MS(false, false); }
 #undef MPT_MS
   }
+  MPT_LAUNCH_CHECK();
+  return MPT_OK;
+}
+
+extern "C" int mpt_master_update_fused(void* stream, size_t n, const float* w_in, const float* m_in, const void* grad, int grad_is_fp32,
+                                       float* w_out, float* m_out, uint16_t* h_out, float inv_scale, const mpt_scaler* scaler,
+                                       float lr, float momentum, uint32_t* flag) {
+  if (n == 0) return MPT_OK;
+  if (w_in == nullptr || grad == nullptr || w_out == nullptr || h_out == nullptr || flag == nullptr) return MPT_ERR_NULL;
+  if ((m_in == nullptr) != (m_out == nullptr)) return MPT_ERR_ARG;
+  if (!mpt_finite(lr) || !mpt_finite(momentum)) return MPT_ERR_ARG;
+  if (scaler == nullptr && (!mpt_finite(inv_scale) || !(inv_scale > 0.f))) return MPT_ERR_ARG;
+  auto overlap = [n](const float* a, const float* b) { return a != nullptr && b != nullptr && a < b + n && b < a + n; };
+  if (overlap(w_in, w_out) || overlap(m_in, m_out) || overlap(w_in, m_out) || overlap(m_in, w_out)) return MPT_ERR_ARG;
+  const size_t gsz = grad_is_fp32 ? 4 : 2;
+  if (!mpt_aligned(w_in, 4) || !mpt_aligned(w_out, 4) || (m_in && (!mpt_aligned(m_in, 4) || !mpt_aligned(m_out, 4))) ||
+      !mpt_aligned(grad, gsz) || !mpt_aligned(h_out, 2) || !mpt_aligned(flag, 4) || (scaler && !mpt_aligned(scaler, 4)))
+    return MPT_ERR_ALIGN;
+  const bool pairs = mpt_aligned(w_in, 8) && mpt_aligned(w_out, 8) && (m_in == nullptr || (mpt_aligned(m_in, 8) && mpt_aligned(m_out, 8))) &&
+                     mpt_aligned(grad, grad_is_fp32 ? 8 : 4) && mpt_aligned(h_out, 4);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const unsigned grid = grid_for(pairs ? (n + 1) / 2 : n);
+#define MPT_MF(M, G, P) hipLaunchKernelGGL((k_master_update_fused<M, G, P>), dim3(grid), dim3(kThreads), 0, s, n, w_in, m_in, grad, w_out, m_out, h_out, inv_scale, scaler, lr, momentum, flag)
+  const int sel = (m_in ? 4 : 0) | (grad_is_fp32 ? 2 : 0) | (pairs ? 1 : 0);
+  switch (sel) {
+    case 0: MPT_MF(false, false, false); break;
+    case 1: MPT_MF(false, false, true); break;
+    case 2: MPT_MF(false, true, false); break;
+    case 3: MPT_MF(false, true, true); break;
+    case 4: MPT_MF(true, false, false); break;
+    case 5: MPT_MF(true, false, true); break;
+    case 6: MPT_MF(true, true, false); break;
+    default: MPT_MF(true, true, true); break;
+  }
+#undef MPT_MF
   MPT_LAUNCH_CHECK();
   return MPT_OK;
 }

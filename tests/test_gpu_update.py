@@ -98,6 +98,80 @@ def test_master_update_bit_exact(n, mom, g32):
     assert np.array_equal(fp16.bits(host16(d_h)), fp16.bits(hw))
 
 
+@pytest.mark.parametrize("n", [1, 5, 8, 13, 1000, 65536 + 7, (1 << 20) + 3])
+@pytest.mark.parametrize("mom", [False, True])
+@pytest.mark.parametrize("g32", [False, True])
+def test_master_update_fused_bit_exact(n, mom, g32):
+    """One pass: flag and update together, into a second set of buffers; the inputs are never written."""
+    rng = np.random.default_rng(n * 4 + mom * 2 + g32 + 77)
+    w = rng.uniform(-0.05, 0.05, n).astype(F32)
+    m = (rng.standard_normal(n) * 1e-3).astype(F32) if mom else None
+    g = _rand_grads(rng, n, -24, 10)
+    if g32:
+        g = g.astype(F32) * F32(1.37)
+    inv, lr, mu = float(F32(2.0 ** -10)), 1e-3, 0.9
+    wf, ww, mw, hw = update.master_update_fused(w, m, g, inv, lr, mu)
+    assert wf == 0
+    d_w, d_m, d_g = dev(w), (dev(m) if mom else None), dev(g)
+    o_w = torch.full((n,), 7.0, dtype=torch.float32, device="cuda")
+    o_m = torch.full((n,), 7.0, dtype=torch.float32, device="cuda") if mom else None
+    o_h = torch.full((n,), 7.0, dtype=torch.float16, device="cuda")
+    flag = _flag()
+    mpt.mpt_master_update_fused(d_w, d_m, d_g, o_w, o_m, o_h, inv, lr, mu, flag)
+    assert int(flag.item()) == 0
+    assert np.array_equal(host(o_w).view(np.uint32), ww.view(np.uint32))
+    if mom:
+        assert np.array_equal(host(o_m).view(np.uint32), mw.view(np.uint32))
+        assert np.array_equal(host(d_m).view(np.uint32), m.view(np.uint32))
+    assert np.array_equal(fp16.bits(host16(o_h)), fp16.bits(hw))
+    assert np.array_equal(host(d_w).view(np.uint32), w.view(np.uint32))
+    # a special value anywhere (first, last, middle) raises the flag; the input set is still untouched
+    for pos in sorted({0, n - 1, n // 2}):
+        gb = g.copy()
+        gb[pos] = np.inf if pos % 2 == 0 else np.nan
+        flag.zero_()
+        mpt.mpt_master_update_fused(d_w, d_m, dev(gb), o_w, o_m, o_h, inv, lr, mu, flag)
+        assert int(flag.item()) == update.master_update_fused(w, m, gb, inv, lr, mu)[0] == 1
+        assert np.array_equal(host(d_w).view(np.uint32), w.view(np.uint32))
+
+
+def test_master_update_fused_ping_pong_trajectory_matches_the_two_kernel_path():
+    """12 steps with overflows at steps 3 and 8, on views that are only element-aligned: the caller swaps the two buffer
+    sets after a clean step and keeps the current set after an overflow; master, momentum and FP16 copy follow the
+    check + update path of the oracle bit for bit, and the device-side scaler halves the scale twice."""
+    rng = np.random.default_rng(5)
+    n = 40001
+    w = rng.uniform(-0.05, 0.05, n).astype(F32)
+    m = np.zeros(n, dtype=F32)
+    cur = [dev(np.concatenate([[0.0], w]).astype(F32))[1:], dev(np.concatenate([[0.0], m]).astype(F32))[1:], None]
+    nxt = [torch.zeros(n + 1, dtype=torch.float32, device="cuda")[1:], torch.zeros(n + 1, dtype=torch.float32, device="cuda")[1:],
+           torch.zeros(n + 1, dtype=torch.float16, device="cuda")[1:]]
+    cur[2] = dev16(np.concatenate([[0.0], w]).astype(np.float16))[1:]
+    h = fp16.rne16(w.astype(np.float64))
+    sc = Scaler(scale=2.0 ** 12, growth_interval=1000)
+    d_sc = mpt.scaler_to_device(mpt.mpt_scaler_init(2.0 ** 12, 1000))
+    flag = _flag()
+    for step in range(12):
+        g = _rand_grads(rng, n, -20, -2)
+        g = (g.astype(np.float32) * np.float32(sc.scale)).astype(np.float16)
+        if step in (3, 8):
+            g[rng.integers(0, n)] = np.inf
+        d_g = dev16(np.concatenate([[0.0], g]).astype(np.float16))[1:]
+        mpt.mpt_master_update_fused(cur[0], cur[1], d_g, nxt[0], nxt[1], nxt[2], 1.0, 0.01, 0.9, flag, scaler_dev=d_sc)
+        overflow = int(flag.item())                     # the caller's decision point (the flag is cleared by the scaler kernel)
+        mpt.mpt_loss_scale_update_dev(d_sc, flag)
+        wf, w2, m2, h2 = update.master_update_fused(w, m, g, sc.inv_scale, 0.01, 0.9)
+        assert overflow == wf == (1 if step in (3, 8) else 0)
+        sc.update(wf)
+        if not overflow:
+            cur, nxt = nxt, cur
+            w, m, h = w2, m2, h2
+        assert np.array_equal(host(cur[0]).view(np.uint32), w.view(np.uint32)), step
+        assert np.array_equal(host(cur[1]).view(np.uint32), m.view(np.uint32)), step
+        assert np.array_equal(fp16.bits(host16(cur[2])), fp16.bits(h)), step
+    assert mpt.scaler_from_device(d_sc).scale == sc.scale == 2.0 ** 10
+
+
 def test_master_update_unaligned_and_skip():
     rng = np.random.default_rng(9)
     n = 7777

@@ -160,3 +160,25 @@ def test_fp32_gradient_input():
     assert w[0] == F32(1.0) - F32(2.0 ** -30) or w[0] == F32(1.0)
     w, _, _ = update.master_update(F32([0.0]), None, F32([2.0 ** -30 * 1024]), 2.0 ** -10, 1.0, 0.0, 0)
     assert w[0] == -F32(2.0 ** -30)
+
+
+def test_single_pass_form_is_check_plus_unconditional_update():
+    """master_update_fused: flag of the stored gradient; outputs of the step as if taken.  Pinned to the two parts it is
+    made of (each pinned above) and to hand values: w = 1, g = 2^-3 * S, lr = 0.5 -> 1 - 2^-4 exactly; an Inf anywhere
+    raises the flag and leaves the inputs alone."""
+    S = 1024.0
+    w = np.array([1.0, -2.0, 0.5], dtype=np.float32)
+    m = np.zeros(3, dtype=np.float32)
+    g = (np.array([2.0 ** -3, 0.0, -2.0 ** -5]) * S).astype(np.float16)
+    flag, w2, m2, h2 = update.master_update_fused(w, m, g, 1.0 / S, 0.5, 0.9)
+    assert flag == 0
+    assert np.array_equal(m2, np.array([2.0 ** -3, 0.0, -2.0 ** -5], dtype=np.float32))
+    assert np.array_equal(w2, np.array([1.0 - 2.0 ** -4, -2.0, 0.5 + 2.0 ** -6], dtype=np.float32))
+    assert np.array_equal(fp16.bits(h2), fp16.bits(w2.astype(np.float16)))
+    wa, ma, ha = update.master_update(w, m, g, 1.0 / S, 0.5, 0.9, update.unscale_check(g, 1.0 / S)[1])
+    assert np.array_equal(wa, w2) and np.array_equal(ma, m2) and np.array_equal(fp16.bits(ha), fp16.bits(h2))
+    g_bad = g.copy(); g_bad[1] = np.float16(np.inf)
+    w_keep, m_keep = w.copy(), m.copy()
+    flag, _, _, _ = update.master_update_fused(w, m, g_bad, 1.0 / S, 0.5, 0.9)
+    assert flag == 1 and np.array_equal(w, w_keep) and np.array_equal(m, m_keep)
+    assert update.master_update_fused(w, None, g, 1.0 / S, 0.5, 0.0)[2] is None
