@@ -469,6 +469,22 @@ def main():
                                       "two_kernel_path_us": round((upd_ms + chk_ms) * 1e3, 2)}
     del w, m, g, h, pool, w2, m2, h2
 
+    # the ceiling the GEMM figures are read against: the FP16 MFMA instruction out of registers, no memory traffic,
+    # sustained, on all-zero operands and on operands with random mantissas (the clock is power-limited on the latter)
+    sink = torch.zeros(1, dtype=torch.float32, device=dev)
+    ceiling = {}
+    for key, rnd in (("zero_operands", 0), ("random_mantissa_operands", 1)):
+        it = 2000
+        preheat(torch, lambda: mpt.mpt_probe_mfma(it, rnd, sink), 60.0)
+        e0.record()
+        for _ in range(20):
+            mpt.mpt_probe_mfma(it, rnd, sink)
+        e1.record()
+        torch.cuda.synchronize()
+        ceiling[key] = round(20 * it * 64 * 16384.0 * 1024 / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
+    ceiling["unit"] = "TFLOP/s"
+    ceiling["kernel"] = "k_probe_mfma: v_mfma_f32_16x16x32_f16 from registers, one wavefront per SIMD, 1 ms launches"
+
     next_rows = None if args.no_next else measure_next(torch, mpt, np, dev, not args.no_cpu_baseline)
 
     config_rows = None if args.no_configs else measure_configs(torch, mpt, np, dev, workloads)
@@ -500,7 +516,7 @@ def main():
                       "loss_scale": 8192, "master_update_elements": n * n},
            "pct_of_fp16_peak": round(100 * value / MFMA_F16_PEAK_TFLOPS, 2),
            "master_update_pct_of_hbm_peak": round(100 * upd_gbs / HBM_PEAK_GBS, 2),
-           "roofline": roofline, "roofline_update": roofline_update, "roofline_next": next_rows, "roofline_configs": config_rows, "cpu_baseline": cpu}
+           "roofline": roofline, "mfma_power_ceiling": ceiling, "roofline_update": roofline_update, "roofline_next": next_rows, "roofline_configs": config_rows, "cpu_baseline": cpu}
     print(json.dumps(out))
 
 

@@ -378,6 +378,19 @@ int mpt_lstm_cell_bwd(void* stream, int64_t B, int64_t H,
                       const uint16_t* c_prev_dev, int64_t ldcp,
                       uint16_t* da_dev, int64_t ldda, uint16_t* dc_prev_dev, int64_t lddcp);
 
+/* ------------------------------------------------------------------------- *
+ * Diagnostic (not a step of the method): the sustained rate of the FP16 MFMA
+ * instruction out of registers, with no memory traffic.  The GPU's clock under
+ * matrix work depends on the operand bits, so this is the ceiling against which
+ * GEMM rates on a given kind of data are read.  One launch runs `iters` x 64
+ * v_mfma_f32_16x16x32_f16 per wavefront on 1024 wavefronts (one per SIMD):
+ * iters * 64 * 16384 * 1024 FLOP; the caller times it with events.
+ * random_operands = 0: all-zero operands; 1: random sign and mantissa, magnitude
+ * 2^-5 .. 2^-1.  sink_dev: one FP32 of device memory (never written in practice).
+ * Errors: NULL, ARG (iters outside 1 .. 2^20), ALIGN.
+ * ------------------------------------------------------------------------- */
+int mpt_probe_mfma(void* stream, int iters, int random_operands, float* sink_dev);
+
 #ifdef __cplusplus
 }
 #endif

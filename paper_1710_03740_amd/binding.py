@@ -57,6 +57,7 @@ SIGNATURES = {
     "mpt_loss_scale_update_dev": (c_i, [c_vp, c_vp, c_vp]),
     "mpt_unscale_check": (c_i, [c_vp, c_vp, c_i, c_sz, c_f, c_vp, c_vp]),
     "mpt_master_update": (c_i, [c_vp, c_sz, c_vp, c_vp, c_vp, c_i, c_vp, c_f, c_vp, c_f, c_f, c_vp]),
+    "mpt_probe_mfma": (c_i, [c_vp, c_i, c_i, c_vp]),
     "mpt_master_update_fused": (c_i, [c_vp, c_sz, c_vp, c_vp, c_vp, c_i, c_vp, c_vp, c_vp, c_f, c_vp, c_f, c_f, c_vp]),
     "mpt_relu_fwd": (c_i, [c_vp, c_sz, c_vp, c_vp]),
     "mpt_relu_bwd": (c_i, [c_vp, c_sz, c_vp, c_vp, c_vp]),
@@ -259,6 +260,11 @@ def scaler_to_device(s, device="cuda"):
 
 def scaler_from_device(buf):
     return mpt_scaler.from_buffer_copy(bytes(buf.cpu().numpy().tobytes()))
+
+
+def mpt_probe_mfma(iters, random_operands, sink):
+    _dev(sink)
+    _check("mpt_probe_mfma", lib().mpt_probe_mfma(_stream(), iters, 1 if random_operands else 0, _p(sink)))
 
 
 # ---------------------------------------------------------------- glue

@@ -13,7 +13,7 @@ INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libmpt.so")
 OBJDIR = os.path.join(HERE, "_build")
 
-HIP_SOURCES = ["elementwise.hip", "gemm.hip", "norm.hip", "optim.hip", "lstm.hip"]
+HIP_SOURCES = ["elementwise.hip", "gemm.hip", "norm.hip", "optim.hip", "lstm.hip", "probe.hip"]
 CXX_SOURCES = ["host.cpp"]
 
 # -ffp-contract=off: the update path is specified as separately rounded FP32 operations.

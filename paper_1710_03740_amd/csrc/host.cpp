@@ -16,7 +16,7 @@ extern "C" const char* mpt_status_string(int status) {
   }
 }
 
-extern "C" int mpt_version(void) { return 105; }
+extern "C" int mpt_version(void) { return 106; }
 
 extern "C" int mpt_scaler_init(mpt_scaler* s, float scale, int32_t growth_interval) {
   if (s == nullptr) return MPT_ERR_NULL;

@@ -129,6 +129,8 @@ def test_argument_errors_before_any_launch(L):
     assert L.mpt_master_update_fused(Z, 8, P, Z, P, 0, Q, Z, Q, 0.0, Z, 0.1, 0.9, P) == -5
     assert L.mpt_master_update_fused(Z, 8, P, Z, P, 0, ctypes.c_void_p(0x200002), Z, Q, 1.0, Z, 0.1, 0.9, P) == -3
     assert L.mpt_master_update_fused(Z, 0, Z, Z, Z, 0, Z, Z, Z, 1.0, Z, 0.1, 0.9, Z) == 0
+    assert L.mpt_probe_mfma(Z, 10, 0, Z) == -1
+    assert L.mpt_probe_mfma(Z, 0, 0, P) == -5
     assert L.mpt_loss_scale_update_dev(Z, Z, P) == -1
     assert L.mpt_relu_fwd(Z, 8, Z, P) == -1
     assert L.mpt_relu_bwd(Z, 8, P, P, Z) == -1

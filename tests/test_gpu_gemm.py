@@ -377,3 +377,22 @@ def test_random_shapes_strides_and_offsets():
         mpt.mpt_gemm_wgrad(view(X, px, ox), view(dY, py, oy), wv, ws=_ws(2, M, N, K) if split else None)
         dw, sa, s = gemm.gemm_wgrad(X, dY, full=True)
         gemm_check(np.ascontiguousarray(host16(wb)[:, ow:ow + N]), dw, sa, s, "wgrad " + label)
+
+
+def test_mfma_probe_runs_and_is_slower_on_random_mantissas_than_on_zeros():
+    """The diagnostic entry point: both operand kinds run to completion; the rate on zeros is not below the rate on
+    random mantissas (on this hardware it is about a third higher once the clock has settled)."""
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    rates = {}
+    for rnd in (0, 1):
+        for _ in range(150):
+            mpt.mpt_probe_mfma(1000, rnd, sink)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(50):
+            mpt.mpt_probe_mfma(1000, rnd, sink)
+        e1.record(); torch.cuda.synchronize()
+        rates[rnd] = 50 * 1000 * 64 * 16384.0 * 1024 / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    assert float(sink.item()) == 0.0
+    assert 500.0 < rates[1] <= rates[0] * 1.02 and rates[0] < 2600.0, rates
