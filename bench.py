@@ -201,10 +201,21 @@ def measure_configs(torch, mpt, np, dev, workloads):
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / reps * 1e-3
 
-    def mfma_row(cfg, name, flops, sec):
+    def mfma_row(cfg, name, flops, sec, alg_bytes=None):
+        """A contraction: read against the matrix peak, or - when its algorithmic bytes (every operand and the result
+        once) put it below the ridge of 2500 TFLOP/s / 8 TB/s = 312.5 FLOP/B - against HBM; both rates are given."""
         tf = flops / sec / 1e12
-        rows.append({"config": cfg, "pass": name, "bound": "mfma", "achieved": round(tf, 1), "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(tf / MFMA_F16_PEAK_TFLOPS, 4), "us": round(sec * 1e6, 1)})
+        row = {"config": cfg, "pass": name, "bound": "mfma", "achieved": round(tf, 1), "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
+               "frac": round(tf / MFMA_F16_PEAK_TFLOPS, 4), "us": round(sec * 1e6, 1)}
+        if alg_bytes is not None:
+            gbs = alg_bytes / sec / 1e9
+            row["tflops"], row["algorithmic_MB"], row["flop_per_byte"] = round(tf, 1), round(alg_bytes / 1e6, 1), round(flops / alg_bytes, 1)
+            if flops / alg_bytes < MFMA_F16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9):
+                row.update({"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4)})
+        rows.append(row)
+
+    def gemm_bytes(i, j, r, out_bytes=2, read_out=False):
+        return 2.0 * (i * r + r * j) + out_bytes * i * j * (2 if read_out else 1)
 
     def d16(a):
         return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).to(dev).view(torch.float16)
@@ -260,14 +271,14 @@ def measure_configs(torch, mpt, np, dev, workloads):
     dWp32 = torch.zeros(HC, RP, dtype=torch.float32, device=dev)
     name = "cfg3 LSTM-with-projection, batch 256"
     fg, fp = 2.0 * Bt * DK * G4, 2.0 * Bt * HC * RP
-    mfma_row(name, "gate fwd 256 x 32768 x 2048", fg, timeit(lambda: mpt.mpt_gemm_fwd(xh[:Bt], Wg, gates, ws)))
-    mfma_row(name, "gate dgrad 256 x 2048 x 32768 (split reduction through the workspace)", fg, timeit(lambda: mpt.mpt_gemm_dgrad(dga[:Bt], Wg, dxh, ws)))
-    mfma_row(name, "gate wgrad per timestep 2048 x 32768 x 256", fg, timeit(lambda: mpt.mpt_gemm_wgrad(xh[:Bt], dga[:Bt], dWg, ws=ws)))
-    mfma_row(name, "gate wgrad, 20 timesteps in one contraction 2048 x 32768 x 5120", T * fg, timeit(lambda: mpt.mpt_gemm_wgrad(xh, dga, dWg, ws=ws), reps=5))
-    mfma_row(name, "projection fwd 256 x 1024 x 8192 (split)", fp, timeit(lambda: mpt.mpt_gemm_fwd(hh, Wp, proj, ws)))
-    mfma_row(name, "projection dgrad 256 x 8192 x 1024", fp, timeit(lambda: mpt.mpt_gemm_dgrad(dr, Wp, dh, ws)))
+    mfma_row(name, "gate fwd 256 x 32768 x 2048", fg, timeit(lambda: mpt.mpt_gemm_fwd(xh[:Bt], Wg, gates, ws)), gemm_bytes(Bt, G4, DK))
+    mfma_row(name, "gate dgrad 256 x 2048 x 32768 (split reduction through the workspace)", fg, timeit(lambda: mpt.mpt_gemm_dgrad(dga[:Bt], Wg, dxh, ws)), gemm_bytes(Bt, DK, G4))
+    mfma_row(name, "gate wgrad per timestep 2048 x 32768 x 256", fg, timeit(lambda: mpt.mpt_gemm_wgrad(xh[:Bt], dga[:Bt], dWg, ws=ws)), gemm_bytes(DK, G4, Bt))
+    mfma_row(name, "gate wgrad, 20 timesteps in one contraction 2048 x 32768 x 5120", T * fg, timeit(lambda: mpt.mpt_gemm_wgrad(xh, dga, dWg, ws=ws), reps=5), gemm_bytes(DK, G4, T * Bt))
+    mfma_row(name, "projection fwd 256 x 1024 x 8192 (split)", fp, timeit(lambda: mpt.mpt_gemm_fwd(hh, Wp, proj, ws)), gemm_bytes(Bt, RP, HC))
+    mfma_row(name, "projection dgrad 256 x 8192 x 1024", fp, timeit(lambda: mpt.mpt_gemm_dgrad(dr, Wp, dh, ws)), gemm_bytes(Bt, HC, RP))
     mfma_row(name, "projection wgrad per timestep, accumulated into an FP32 gradient 8192 x 1024 x 256", fp,
-             timeit(lambda: mpt.mpt_gemm_wgrad(hh, dr, dWp32, accumulate=True)))
+             timeit(lambda: mpt.mpt_gemm_wgrad(hh, dr, dWp32, accumulate=True)), gemm_bytes(HC, RP, Bt, out_bytes=4, read_out=True))
     del Wg, Wp, xh, hh, dga, dr, gates, dxh, dWg, proj, dh, dWp32, ws
 
     # ---- cfg 4: 3x3 convolution block, NHWC 256 x 14 x 14 x 256 -> 256 channels (implicit GEMM 50176 x 256 x 2304)
@@ -279,9 +290,10 @@ def measure_configs(torch, mpt, np, dev, workloads):
     y, dx, dw = e16(Nb, H, W_, Kf), e16(Nb, H, W_, C), e16(Kf, 3, 3, C)
     fl = 2.0 * Nb * H * W_ * Kf * 9 * C
     name = "cfg4 conv 3x3 256x14x14x256 -> 256"
-    mfma_row(name, "fwd (streamed, gathered operand)", fl, timeit(lambda: mpt.mpt_conv3x3_fwd(x, w, y, ws)))
-    mfma_row(name, "dgrad (streamed, gathered operand, filter read outer-contiguous)", fl, timeit(lambda: mpt.mpt_conv3x3_dgrad(dy, w, dx, ws)))
-    mfma_row(name, "wgrad (streamed, image gathered per tap, split reduction through the workspace)", fl, timeit(lambda: mpt.mpt_conv3x3_wgrad(x, dy, dw, ws=ws)))
+    conv_bytes = 2.0 * (Nb * H * W_ * C + Kf * 9 * C + Nb * H * W_ * Kf)      # image, filter and the other image, each once
+    mfma_row(name, "fwd (streamed, gathered operand)", fl, timeit(lambda: mpt.mpt_conv3x3_fwd(x, w, y, ws)), conv_bytes)
+    mfma_row(name, "dgrad (streamed, gathered operand, filter read outer-contiguous)", fl, timeit(lambda: mpt.mpt_conv3x3_dgrad(dy, w, dx, ws)), conv_bytes)
+    mfma_row(name, "wgrad (streamed, image gathered per tap, split reduction through the workspace)", fl, timeit(lambda: mpt.mpt_conv3x3_wgrad(x, dy, dw, ws=ws)), conv_bytes)
     del x, w, dy, y, dx, dw, ws
 
     # ---- cfg 5: one dynamic-scale step on the 116M-element flat buffer: check, momentum update, scaler (device resident)
