@@ -25,38 +25,42 @@ __device__ __forceinline__ float tanhf_(float x) {
   return copysignf(ax < 0.0625f ? small : big, x);
 }
 
-template <int V>
+// NT: nontemporal accesses, for tensors that outgrow the 256 MB memory-side cache (streaming them is faster there,
+// slower for small tensors that the next kernel reads again).
+template <int V, bool NT = false>
 __device__ __forceinline__ void ld16(const uint16_t* p, float (&v)[V]) {
   if constexpr (V == 8) {
-    const lh8 q = *reinterpret_cast<const lh8*>(p);
+    const lh8 q = NT ? __builtin_nontemporal_load(reinterpret_cast<const lh8*>(p)) : *reinterpret_cast<const lh8*>(p);
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] = (float)q[e];
   } else if constexpr (V == 4) {
-    const lh4 q = *reinterpret_cast<const lh4*>(p);
+    const lh4 q = NT ? __builtin_nontemporal_load(reinterpret_cast<const lh4*>(p)) : *reinterpret_cast<const lh4*>(p);
 #pragma unroll
     for (int e = 0; e < 4; ++e) v[e] = (float)q[e];
   } else {
     v[0] = (float)*reinterpret_cast<const _Float16*>(p);
   }
 }
-template <int V>
+template <int V, bool NT = false>
 __device__ __forceinline__ void st16(uint16_t* p, const float (&v)[V]) {
   if constexpr (V == 8) {
     lh8 q;
 #pragma unroll
     for (int e = 0; e < 8; ++e) q[e] = (_Float16)mpt_rounded_f32(v[e]);
-    *reinterpret_cast<lh8*>(p) = q;
+    if constexpr (NT) __builtin_nontemporal_store(q, reinterpret_cast<lh8*>(p));
+    else *reinterpret_cast<lh8*>(p) = q;
   } else if constexpr (V == 4) {
     lh4 q;
 #pragma unroll
     for (int e = 0; e < 4; ++e) q[e] = (_Float16)mpt_rounded_f32(v[e]);
-    *reinterpret_cast<lh4*>(p) = q;
+    if constexpr (NT) __builtin_nontemporal_store(q, reinterpret_cast<lh4*>(p));
+    else *reinterpret_cast<lh4*>(p) = q;
   } else {
     *reinterpret_cast<_Float16*>(p) = (_Float16)mpt_rounded_f32(v[0]);
   }
 }
 
-template <int V>
+template <int V, bool NT>
 __global__ __launch_bounds__(kT) void k_lstm_cell_fwd(int64_t B, int64_t H, const uint16_t* __restrict__ gx, int64_t ldgx,
                                                       const uint16_t* __restrict__ gr, int64_t ldgr, const float* __restrict__ bias,
                                                       const uint16_t* cprev, int64_t ldcp, uint16_t* __restrict__ act, int64_t ldact,
@@ -68,10 +72,10 @@ __global__ __launch_bounds__(kT) void k_lstm_cell_fwd(int64_t B, int64_t H, cons
   float a[4][V], cp[V];
 #pragma unroll
   for (int g = 0; g < 4; ++g) {
-    ld16<V>(gx + b * ldgx + g * H + j, a[g]);
+    ld16<V, NT>(gx + b * ldgx + g * H + j, a[g]);
     if (gr != nullptr) {
       float r[V];
-      ld16<V>(gr + b * ldgr + g * H + j, r);
+      ld16<V, NT>(gr + b * ldgr + g * H + j, r);
 #pragma unroll
       for (int e = 0; e < V; ++e) a[g][e] = __fadd_rn(a[g][e], r[e]);
     }
@@ -80,7 +84,7 @@ __global__ __launch_bounds__(kT) void k_lstm_cell_fwd(int64_t B, int64_t H, cons
       for (int e = 0; e < V; ++e) a[g][e] = __fadd_rn(a[g][e], bias[g * H + j + e]);
     }
   }
-  ld16<V>(cprev + b * ldcp + j, cp);
+  ld16<V, NT>(cprev + b * ldcp + j, cp);
   float cn[V], hn[V];
 #pragma unroll
   for (int e = 0; e < V; ++e) {
@@ -90,12 +94,12 @@ __global__ __launch_bounds__(kT) void k_lstm_cell_fwd(int64_t B, int64_t H, cons
     hn[e] = __fmul_rn(o, tanhf_(cn[e]));
   }
 #pragma unroll
-  for (int g = 0; g < 4; ++g) st16<V>(act + b * ldact + g * H + j, a[g]);
-  st16<V>(c + b * ldc + j, cn);
-  st16<V>(h + b * ldh + j, hn);
+  for (int g = 0; g < 4; ++g) st16<V, NT>(act + b * ldact + g * H + j, a[g]);
+  st16<V, NT>(c + b * ldc + j, cn);
+  st16<V, NT>(h + b * ldh + j, hn);
 }
 
-template <int V>
+template <int V, bool NT>
 __global__ __launch_bounds__(kT) void k_lstm_cell_bwd(int64_t B, int64_t H, const uint16_t* __restrict__ dh, int64_t lddh,
                                                       const uint16_t* dcn, int64_t lddcn, const uint16_t* __restrict__ act, int64_t ldact,
                                                       const uint16_t* __restrict__ c, int64_t ldc, const uint16_t* __restrict__ cprev, int64_t ldcp,
@@ -106,12 +110,12 @@ __global__ __launch_bounds__(kT) void k_lstm_cell_bwd(int64_t B, int64_t H, cons
   const int64_t b = u / per_row, j = (u - b * per_row) * V;
   float a[4][V], dhv[V], dc[V], cv[V], cp[V];
 #pragma unroll
-  for (int g = 0; g < 4; ++g) ld16<V>(act + b * ldact + g * H + j, a[g]);
-  ld16<V>(dh + b * lddh + j, dhv);
-  ld16<V>(c + b * ldc + j, cv);
-  ld16<V>(cprev + b * ldcp + j, cp);
+  for (int g = 0; g < 4; ++g) ld16<V, NT>(act + b * ldact + g * H + j, a[g]);
+  ld16<V, NT>(dh + b * lddh + j, dhv);
+  ld16<V, NT>(c + b * ldc + j, cv);
+  ld16<V, NT>(cprev + b * ldcp + j, cp);
   if (dcn != nullptr) {
-    ld16<V>(dcn + b * lddcn + j, dc);
+    ld16<V, NT>(dcn + b * lddcn + j, dc);
   } else {
 #pragma unroll
     for (int e = 0; e < V; ++e) dc[e] = 0.f;
@@ -129,8 +133,8 @@ __global__ __launch_bounds__(kT) void k_lstm_cell_bwd(int64_t B, int64_t H, cons
     dprev[e] = __fmul_rn(d, f);
   }
 #pragma unroll
-  for (int g = 0; g < 4; ++g) st16<V>(da + b * ldda + g * H + j, out[g]);
-  st16<V>(dcp + b * lddcp + j, dprev);
+  for (int g = 0; g < 4; ++g) st16<V, NT>(da + b * ldda + g * H + j, out[g]);
+  st16<V, NT>(dcp + b * lddcp + j, dprev);
 }
 
 bool vec_ok(const void* p, int64_t ld) { return p == nullptr || (mpt_aligned(p, 16) && (ld % 8) == 0); }
@@ -150,8 +154,10 @@ extern "C" int mpt_lstm_cell_fwd(void* stream, int64_t B, int64_t H, const uint1
   const bool vec = (H % 8) == 0 && vec_ok(gx, ldgx) && vec_ok(gr, ldgr) && vec_ok(c_prev, ldcp) && vec_ok(act, ldact) && vec_ok(c, ldc) && vec_ok(h, ldh);
   const int64_t units = vec ? B * (H / 4) : B * H;          // 4 cells (8 bytes) per lane: measured 5.5 vs 5.3 TB/s against 8 cells
   const unsigned grid = (unsigned)((units + kT - 1) / kT);
-  if (vec) hipLaunchKernelGGL(k_lstm_cell_fwd<4>, dim3(grid), dim3(kT), 0, st, B, H, gx, ldgx, gr, ldgr, bias, c_prev, ldcp, act, ldact, c, ldc, h, ldh);
-  else hipLaunchKernelGGL(k_lstm_cell_fwd<1>, dim3(grid), dim3(kT), 0, st, B, H, gx, ldgx, gr, ldgr, bias, c_prev, ldcp, act, ldact, c, ldc, h, ldh);
+  const bool stream_it = vec && B * H * 30 > (192LL << 20);   // bytes moved beyond the memory-side cache
+  if (stream_it) hipLaunchKernelGGL((k_lstm_cell_fwd<4, true>), dim3(grid), dim3(kT), 0, st, B, H, gx, ldgx, gr, ldgr, bias, c_prev, ldcp, act, ldact, c, ldc, h, ldh);
+  else if (vec) hipLaunchKernelGGL((k_lstm_cell_fwd<4, false>), dim3(grid), dim3(kT), 0, st, B, H, gx, ldgx, gr, ldgr, bias, c_prev, ldcp, act, ldact, c, ldc, h, ldh);
+  else hipLaunchKernelGGL((k_lstm_cell_fwd<1, false>), dim3(grid), dim3(kT), 0, st, B, H, gx, ldgx, gr, ldgr, bias, c_prev, ldcp, act, ldact, c, ldc, h, ldh);
   MPT_LAUNCH_CHECK();
   return MPT_OK;
 }
@@ -169,8 +175,10 @@ extern "C" int mpt_lstm_cell_bwd(void* stream, int64_t B, int64_t H, const uint1
                    vec_ok(da, ldda) && vec_ok(dc_prev, lddcp);
   const int64_t units = vec ? B * (H / 4) : B * H;          // 4 cells (8 bytes) per lane: measured 5.5 vs 5.3 TB/s against 8 cells
   const unsigned grid = (unsigned)((units + kT - 1) / kT);
-  if (vec) hipLaunchKernelGGL(k_lstm_cell_bwd<4>, dim3(grid), dim3(kT), 0, st, B, H, dh, lddh, dc_next, lddcn, act, ldact, c, ldc, c_prev, ldcp, da, ldda, dc_prev, lddcp);
-  else hipLaunchKernelGGL(k_lstm_cell_bwd<1>, dim3(grid), dim3(kT), 0, st, B, H, dh, lddh, dc_next, lddcn, act, ldact, c, ldc, c_prev, ldcp, da, ldda, dc_prev, lddcp);
+  const bool stream_it = vec && B * H * 22 > (192LL << 20);
+  if (stream_it) hipLaunchKernelGGL((k_lstm_cell_bwd<4, true>), dim3(grid), dim3(kT), 0, st, B, H, dh, lddh, dc_next, lddcn, act, ldact, c, ldc, c_prev, ldcp, da, ldda, dc_prev, lddcp);
+  else if (vec) hipLaunchKernelGGL((k_lstm_cell_bwd<4, false>), dim3(grid), dim3(kT), 0, st, B, H, dh, lddh, dc_next, lddcn, act, ldact, c, ldc, c_prev, ldcp, da, ldda, dc_prev, lddcp);
+  else hipLaunchKernelGGL((k_lstm_cell_bwd<1, false>), dim3(grid), dim3(kT), 0, st, B, H, dh, lddh, dc_next, lddcn, act, ldact, c, ldc, c_prev, ldcp, da, ldda, dc_prev, lddcp);
   MPT_LAUNCH_CHECK();
   return MPT_OK;
 }

@@ -37,7 +37,7 @@ def _inputs(B, H, seed):
     return gx, gr, bias, cp, dh, dcn
 
 
-@pytest.mark.parametrize("B,H", [(1, 8), (3, 24), (5, 7), (64, 1024), (256, 8192)])
+@pytest.mark.parametrize("B,H", [(1, 8), (3, 24), (5, 7), (64, 1024), (256, 8192), (1536, 8192)])   # the last: > 192 MB moved, the streaming instances
 def test_cell_forward_and_backward_teacher_forced(B, H):
     gx, gr, bias, cp, dh, dcn = _inputs(B, H, B * 31 + H)
     for use_gr, use_bias in ((True, True), (False, False)):
