@@ -111,6 +111,66 @@ def _dev(*ts):
             raise ValueError("mpt binding takes device tensors only")
 
 
+# The C ABI sees pointers and sizes only, so a tensor of the wrong dtype, a transposed view or a buffer shorter than
+# its neighbours would be read or written out of bounds on the device.  Every wrapper checks its tensors against each
+# other here, before the library is touched; a mismatch raises ValueError.
+_F16, _F32, _I32, _I64, _U8 = torch.float16, torch.float32, torch.int32, torch.int64, torch.uint8
+
+
+def _want(name, t, dtypes, shape=None, numel=None, optional=False):
+    """t: tensor (or None when optional); dtypes: one dtype or a tuple; shape: exact shape; numel: exact element count."""
+    if t is None:
+        if optional:
+            return
+        raise ValueError("%s: a tensor is required" % name)
+    if not isinstance(dtypes, tuple):
+        dtypes = (dtypes,)
+    if t.dtype not in dtypes:
+        raise ValueError("%s: dtype %s, expected %s" % (name, t.dtype, " or ".join(str(d) for d in dtypes)))
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError("%s: shape %s, expected %s" % (name, tuple(t.shape), tuple(shape)))
+    if numel is not None and t.numel() != numel:
+        raise ValueError("%s: %d elements, expected %d" % (name, t.numel(), numel))
+
+
+def _rows(name, t):
+    """A row-major matrix view: unit stride along the last axis and a row stride that covers a row."""
+    if t.dim() != 2:
+        raise ValueError("%s: expected a matrix, got %d dimensions" % (name, t.dim()))
+    if t.shape[1] > 1 and t.stride(1) != 1:
+        raise ValueError("%s: last-axis stride %d, expected 1 (transposed views are not accepted)" % (name, t.stride(1)))
+    if t.shape[0] > 1 and t.stride(0) < t.shape[1]:
+        raise ValueError("%s: row stride %d is smaller than the row length %d" % (name, t.stride(0), t.shape[1]))
+
+
+def _flat(name, t, optional=False):
+    """A dense buffer (elements in memory order, no gaps)."""
+    if t is None and optional:
+        return
+    if not t.is_contiguous():
+        raise ValueError("%s: expected a contiguous buffer" % name)
+
+
+def _mat(name, t, dtypes, shape, optional=False):
+    _want(name, t, dtypes, optional=optional)
+    if t is None:
+        return
+    _rows(name, t)
+    if tuple(t.shape) != tuple(shape):
+        raise ValueError("%s: shape %s, expected %s" % (name, tuple(t.shape), tuple(shape)))
+
+
+def _dim2(name, t):
+    if t is None or t.dim() != 2:
+        raise ValueError("%s: expected a matrix" % name)
+    return t.shape
+
+
+def _ws_ok(ws):
+    if ws is not None:
+        _flat("ws", ws)
+
+
 def mpt_version():
     return lib().mpt_version()
 
@@ -128,44 +188,64 @@ def _ws(ws):
     return (_p(ws), c_sz(0 if ws is None else ws.numel() * ws.element_size()))
 
 
+def _fwd_shapes(X, W, Y, yname):
+    M, K = _dim2("X", X)
+    N = _dim2("W", W)[1]
+    _mat("X", X, _F16, (M, K)); _mat("W", W, _F16, (K, N)); _mat(yname, Y, _F16, (M, N))
+    return M, N, K
+
+
+def _dgrad_shapes(dY, W, dX):
+    M, N = _dim2("dY", dY)
+    K = _dim2("W", W)[0]
+    _mat("dY", dY, _F16, (M, N)); _mat("W", W, _F16, (K, N)); _mat("dX", dX, _F16, (M, K))
+    return M, N, K
+
+
 def mpt_gemm_fwd(X, W, Y, ws=None):
+    M, N, K = _fwd_shapes(X, W, Y, "Y")
+    _ws_ok(ws)
     _dev(X, W, Y, ws)
-    M, K = X.shape
-    N = W.shape[1]
     p, b = _ws(ws)
     _check("mpt_gemm_fwd", lib().mpt_gemm_fwd(_stream(), M, N, K, _p(X), X.stride(0), _p(W), W.stride(0), _p(Y), Y.stride(0), p, b))
 
 
 def mpt_gemm_dgrad(dY, W, dX, ws=None):
+    M, N, K = _dgrad_shapes(dY, W, dX)
+    _ws_ok(ws)
     _dev(dY, W, dX, ws)
-    M, N = dY.shape
-    K = W.shape[0]
     p, b = _ws(ws)
     _check("mpt_gemm_dgrad", lib().mpt_gemm_dgrad(_stream(), M, N, K, _p(dY), dY.stride(0), _p(W), W.stride(0), _p(dX), dX.stride(0), p, b))
 
 
 def mpt_gemm_fwd_relu(X, W, H, ws=None):
+    M, N, K = _fwd_shapes(X, W, H, "H")
+    _ws_ok(ws)
     _dev(X, W, H, ws)
-    M, K = X.shape
-    N = W.shape[1]
     p, b = _ws(ws)
     _check("mpt_gemm_fwd_relu", lib().mpt_gemm_fwd_relu(_stream(), M, N, K, _p(X), X.stride(0), _p(W), W.stride(0), _p(H), H.stride(0), p, b))
 
 
 def mpt_gemm_dgrad_relu(dY, W, H, dX, ws=None):
+    M, N, K = _dgrad_shapes(dY, W, dX)
+    _mat("H", H, _F16, (M, K))
+    _ws_ok(ws)
     _dev(dY, W, H, dX, ws)
-    M, N = dY.shape
-    K = W.shape[0]
     p, b = _ws(ws)
     _check("mpt_gemm_dgrad_relu", lib().mpt_gemm_dgrad_relu(_stream(), M, N, K, _p(dY), dY.stride(0), _p(W), W.stride(0),
                                                             _p(H), H.stride(0), _p(dX), dX.stride(0), p, b))
 
 
 def mpt_gemm_wgrad(X, dY, dW, accumulate=False, flag=None, ws=None):
-    _dev(X, dY, dW, flag, ws)
-    M, K = X.shape
-    N = dY.shape[1]
+    M, K = _dim2("X", X)
+    N = _dim2("dY", dY)[1]
+    _mat("X", X, _F16, (M, K)); _mat("dY", dY, _F16, (M, N)); _mat("dW", dW, (_F16, _F32), (K, N))
+    _want("flag", flag, _I32, numel=1, optional=True)
+    _ws_ok(ws)
     out_fp32 = 1 if dW.dtype == torch.float32 else 0
+    if accumulate and not out_fp32:
+        raise ValueError("dW: accumulate needs an FP32 output")
+    _dev(X, dY, dW, flag, ws)
     p, b = _ws(ws)
     _check("mpt_gemm_wgrad", lib().mpt_gemm_wgrad(_stream(), M, N, K, _p(X), X.stride(0), _p(dY), dY.stride(0), _p(dW), dW.stride(0),
                                                   out_fp32, 1 if accumulate else 0, _p(flag), p, b))
@@ -176,35 +256,67 @@ def mpt_conv3x3_workspace_bytes(op, Nb, H, W, C, Kf):
     return lib().mpt_conv3x3_workspace_bytes(op, Nb, H, W, C, Kf)
 
 
-def mpt_conv3x3_fwd(x, w, y, ws=None):
-    _dev(x, w, y, ws)
+def _conv_shapes(x, xname, w, y, yname):
+    """x-like [Nb,H,W,C], filter-like [Kf,3,3,C], y-like [Nb,H,W,Kf]; all dense FP16."""
+    if x is None or x.dim() != 4 or w is None or w.dim() != 4 or y is None:
+        raise ValueError("conv: expected 4-d tensors %s [Nb,H,W,C], filter [Kf,3,3,C], %s [Nb,H,W,Kf]" % (xname, yname))
     Nb, H, W, C = x.shape
+    Kf = w.shape[0]
+    _want(xname, x, _F16); _want("filter", w, _F16, shape=(Kf, 3, 3, C)); _want(yname, y, _F16, shape=(Nb, H, W, Kf))
+    _flat(xname, x); _flat("filter", w); _flat(yname, y)
+    return Nb, H, W, C, Kf
+
+
+def mpt_conv3x3_fwd(x, w, y, ws=None):
+    Nb, H, W, C, Kf = _conv_shapes(x, "x", w, y, "y")
+    _ws_ok(ws)
+    _dev(x, w, y, ws)
     p, b = _ws(ws)
-    _check("mpt_conv3x3_fwd", lib().mpt_conv3x3_fwd(_stream(), Nb, H, W, C, w.shape[0], _p(x), _p(w), _p(y), p, b))
+    _check("mpt_conv3x3_fwd", lib().mpt_conv3x3_fwd(_stream(), Nb, H, W, C, Kf, _p(x), _p(w), _p(y), p, b))
 
 
 def mpt_conv3x3_dgrad(dy, w, dx, ws=None):
+    Nb, H, W, C, Kf = _conv_shapes(dx, "dx", w, dy, "dy")
+    _ws_ok(ws)
     _dev(dy, w, dx, ws)
-    Nb, H, W, Kf = dy.shape
     p, b = _ws(ws)
-    _check("mpt_conv3x3_dgrad", lib().mpt_conv3x3_dgrad(_stream(), Nb, H, W, w.shape[3], Kf, _p(dy), _p(w), _p(dx), p, b))
+    _check("mpt_conv3x3_dgrad", lib().mpt_conv3x3_dgrad(_stream(), Nb, H, W, C, Kf, _p(dy), _p(w), _p(dx), p, b))
 
 
 def mpt_conv3x3_wgrad(x, dy, dw, flag=None, ws=None):
+    Nb, H, W, C, Kf = _conv_shapes(x, "x", dw, dy, "dy")
+    _want("flag", flag, _I32, numel=1, optional=True)
+    _ws_ok(ws)
     _dev(x, dy, dw, flag, ws)
-    Nb, H, W, C = x.shape
     p, b = _ws(ws)
-    _check("mpt_conv3x3_wgrad", lib().mpt_conv3x3_wgrad(_stream(), Nb, H, W, C, dy.shape[3], _p(x), _p(dy), _p(dw), _p(flag), p, b))
+    _check("mpt_conv3x3_wgrad", lib().mpt_conv3x3_wgrad(_stream(), Nb, H, W, C, Kf, _p(x), _p(dy), _p(dw), _p(flag), p, b))
 
 
 # ---------------------------------------------------------------- loss-scaled update path
 def mpt_unscale_check(grad, inv_scale, flag, g32_out=None):
+    _want("grad", grad, (_F16, _F32)); _flat("grad", grad)
+    _want("flag", flag, _I32, numel=1)
+    _want("g32_out", g32_out, _F32, numel=grad.numel(), optional=True); _flat("g32_out", g32_out, optional=True)
     _dev(grad, flag, g32_out)
     _check("mpt_unscale_check", lib().mpt_unscale_check(_stream(), _p(grad), 1 if grad.dtype == torch.float32 else 0,
                                                         grad.numel(), inv_scale, _p(g32_out), _p(flag)))
 
 
+def _update_buffers(w32, states, grad, w16, flag, scaler_dev):
+    """The flat buffers of one update: same element count everywhere, documented dtypes, dense."""
+    _want("w32", w32, _F32); _flat("w32", w32)
+    n = w32.numel()
+    for name, t in states:
+        _want(name, t, _F32, numel=n, optional=True); _flat(name, t, optional=True)
+    _want("grad", grad, (_F16, _F32), numel=n); _flat("grad", grad)
+    _want("w16", w16, _F16, numel=n); _flat("w16", w16)
+    _want("flag", flag, _I32, numel=1, optional=True)
+    _want("scaler_dev", scaler_dev, _U8, numel=ctypes.sizeof(mpt_scaler), optional=True)
+    return n
+
+
 def mpt_master_update(w32, m32, grad, w16, inv_scale, lr, momentum, flag=None, scaler_dev=None):
+    _update_buffers(w32, [("m32", m32)], grad, w16, flag, scaler_dev)
     _dev(w32, m32, grad, w16, flag, scaler_dev)
     _check("mpt_master_update", lib().mpt_master_update(_stream(), w32.numel(), _p(w32), _p(m32), _p(grad),
                                                         1 if grad.dtype == torch.float32 else 0, _p(w16),
@@ -212,6 +324,11 @@ def mpt_master_update(w32, m32, grad, w16, inv_scale, lr, momentum, flag=None, s
 
 
 def mpt_master_update_fused(w32_in, m32_in, grad, w32_out, m32_out, w16_out, inv_scale, lr, momentum, flag, scaler_dev=None):
+    n = _update_buffers(w32_in, [("m32_in", m32_in), ("m32_out", m32_out)], grad, w16_out, flag, scaler_dev)
+    _want("w32_out", w32_out, _F32, numel=n); _flat("w32_out", w32_out)
+    _want("flag", flag, _I32, numel=1)
+    if (m32_in is None) != (m32_out is None):
+        raise ValueError("m32_in and m32_out: both or neither")
     _dev(w32_in, m32_in, grad, w32_out, m32_out, w16_out, flag, scaler_dev)
     _check("mpt_master_update_fused", lib().mpt_master_update_fused(_stream(), w32_in.numel(), _p(w32_in), _p(m32_in), _p(grad),
                                                                     1 if grad.dtype == torch.float32 else 0, _p(w32_out), _p(m32_out),
@@ -220,6 +337,11 @@ def mpt_master_update_fused(w32_in, m32_in, grad, w32_out, m32_out, w16_out, inv
 
 def mpt_optimizer_update(kind, hp, w32, state1, state2, grad, w16, inv_scale, flag=None, scaler_dev=None):
     """kind: a key of OPT_KINDS; hp: an mpt_opt_params (host struct)."""
+    if kind not in OPT_KINDS:
+        raise ValueError("kind: %r, expected one of %s" % (kind, sorted(OPT_KINDS)))
+    _update_buffers(w32, [("state1", state1), ("state2", state2)], grad, w16, flag, scaler_dev)
+    if state1 is None or (kind == "adam" and state2 is None):
+        raise ValueError("optimizer state: state1 is required (and state2 for adam)")
     _dev(w32, state1, state2, grad, w16, flag, scaler_dev)
     _check("mpt_optimizer_update", lib().mpt_optimizer_update(_stream(), w32.numel(), OPT_KINDS[kind], ctypes.byref(hp), _p(w32), _p(state1),
                                                               _p(state2), _p(grad), 1 if grad.dtype == torch.float32 else 0, _p(w16),
@@ -228,6 +350,9 @@ def mpt_optimizer_update(kind, hp, w32, state1, state2, grad, w16, inv_scale, fl
 
 def mpt_grad_stats(grad, hist, absmax_bits, accumulate=False):
     """hist: int64[42] device tensor; absmax_bits: int32[1] device tensor."""
+    _want("grad", grad, _F16); _flat("grad", grad)
+    _want("hist", hist, _I64, numel=42); _flat("hist", hist)
+    _want("absmax_bits", absmax_bits, _I32, numel=1)
     _dev(grad, hist, absmax_bits)
     _check("mpt_grad_stats", lib().mpt_grad_stats(_stream(), _p(grad), grad.numel(), 1 if accumulate else 0, _p(hist), _p(absmax_bits)))
 
@@ -248,6 +373,7 @@ def mpt_loss_scale_update(s, overflow):
 
 
 def mpt_loss_scale_update_dev(scaler_dev, flag):
+    _want("scaler_dev", scaler_dev, _U8, numel=ctypes.sizeof(mpt_scaler)); _want("flag", flag, _I32, numel=1)
     _dev(scaler_dev, flag)
     _check("mpt_loss_scale_update_dev", lib().mpt_loss_scale_update_dev(_stream(), _p(scaler_dev), _p(flag)))
 
@@ -263,24 +389,34 @@ def scaler_from_device(buf):
 
 
 def mpt_probe_mfma(iters, random_operands, sink):
+    _want("sink", sink, _F32, numel=1)
     _dev(sink)
     _check("mpt_probe_mfma", lib().mpt_probe_mfma(_stream(), iters, 1 if random_operands else 0, _p(sink)))
 
 
 # ---------------------------------------------------------------- glue
 def mpt_relu_fwd(y, h):
+    _want("y", y, _F16); _flat("y", y); _want("h", h, _F16, numel=y.numel()); _flat("h", h)
     _dev(y, h)
     _check("mpt_relu_fwd", lib().mpt_relu_fwd(_stream(), y.numel(), _p(y), _p(h)))
 
 
 def mpt_relu_bwd(dh, y, dy):
+    _want("y", y, _F16); _flat("y", y)
+    _want("dh", dh, _F16, numel=y.numel()); _flat("dh", dh); _want("dy", dy, _F16, numel=y.numel()); _flat("dy", dy)
     _dev(dh, y, dy)
     _check("mpt_relu_bwd", lib().mpt_relu_bwd(_stream(), y.numel(), _p(dh), _p(y), _p(dy)))
 
 
 def mpt_softmax_xent_scaled(logits, labels, scale, dlogits, loss=None, row_loss=None):
+    B, C = _dim2("logits", logits)
+    _mat("logits", logits, _F16, (B, C)); _mat("dlogits", dlogits, _F16, (B, C))
+    _want("labels", labels, _I32, numel=B); _flat("labels", labels)
+    _want("loss", loss, _F32, numel=1, optional=True)
+    _want("row_loss", row_loss, _F32, numel=B, optional=True); _flat("row_loss", row_loss, optional=True)
+    if loss is not None and row_loss is None:
+        raise ValueError("row_loss: required when loss is given")
     _dev(logits, labels, dlogits, loss, row_loss)
-    B, C = logits.shape
     _check("mpt_softmax_xent_scaled", lib().mpt_softmax_xent_scaled(_stream(), B, C, _p(logits), logits.stride(0), _p(labels),
                                                                     scale, _p(loss), _p(row_loss), _p(dlogits), dlogits.stride(0)))
 
@@ -290,31 +426,44 @@ def mpt_bn_workspace_bytes(P, C):
     return lib().mpt_bn_workspace_bytes(P, C)
 
 
+def _bn_shapes(x, vectors, tensors):
+    """x [P, C] FP16; per-channel FP32 vectors of C elements; further FP16 tensors of x's shape."""
+    P, C = _dim2("x", x)
+    _mat("x", x, _F16, (P, C))
+    for name, v in vectors:
+        _want(name, v, _F32, numel=C); _flat(name, v)
+    for name, t in tensors:
+        _mat(name, t, _F16, (P, C))
+    return P, C
+
+
 def mpt_bn_stats(x, mean, var, ws):
+    P, C = _bn_shapes(x, [("mean", mean), ("var", var)], [])
+    _ws_ok(ws)
     _dev(x, mean, var, ws)
-    P, C = x.shape
     p, b = _ws(ws)
     _check("mpt_bn_stats", lib().mpt_bn_stats(_stream(), P, C, _p(x), x.stride(0), _p(mean), _p(var), p, b))
 
 
 def mpt_bn_apply(x, mean, var, gamma, beta, eps, y, relu=False):
+    P, C = _bn_shapes(x, [("mean", mean), ("var", var), ("gamma", gamma), ("beta", beta)], [("y", y)])
     _dev(x, mean, var, gamma, beta, y)
-    P, C = x.shape
     _check("mpt_bn_apply", lib().mpt_bn_apply(_stream(), P, C, _p(x), x.stride(0), _p(mean), _p(var), _p(gamma), _p(beta),
                                               eps, 1 if relu else 0, _p(y), y.stride(0)))
 
 
 def mpt_bn_bwd_reduce(x, dy, mean, var, eps, dgamma, dbeta, ws):
+    P, C = _bn_shapes(x, [("mean", mean), ("var", var), ("dgamma", dgamma), ("dbeta", dbeta)], [("dy", dy)])
+    _ws_ok(ws)
     _dev(x, dy, mean, var, dgamma, dbeta, ws)
-    P, C = x.shape
     p, b = _ws(ws)
     _check("mpt_bn_bwd_reduce", lib().mpt_bn_bwd_reduce(_stream(), P, C, _p(x), x.stride(0), _p(dy), dy.stride(0), _p(mean), _p(var),
                                                         eps, _p(dgamma), _p(dbeta), p, b))
 
 
 def mpt_bn_bwd_apply(x, dy, mean, var, gamma, eps, dgamma, dbeta, dx):
+    P, C = _bn_shapes(x, [("mean", mean), ("var", var), ("gamma", gamma), ("dgamma", dgamma), ("dbeta", dbeta)], [("dy", dy), ("dx", dx)])
     _dev(x, dy, mean, var, gamma, dgamma, dbeta, dx)
-    P, C = x.shape
     _check("mpt_bn_bwd_apply", lib().mpt_bn_bwd_apply(_stream(), P, C, _p(x), x.stride(0), _p(dy), dy.stride(0), _p(mean), _p(var),
                                                       _p(gamma), eps, _p(dgamma), _p(dbeta), _p(dx), dx.stride(0)))
 
@@ -325,14 +474,21 @@ def _ld(t):
 
 
 def mpt_lstm_cell_fwd(gx, gr, bias, c_prev, act, c, h):
+    B, H = _dim2("c_prev", c_prev)
+    _mat("c_prev", c_prev, _F16, (B, H)); _mat("c", c, _F16, (B, H)); _mat("h", h, _F16, (B, H))
+    _mat("gx", gx, _F16, (B, 4 * H)); _mat("gr", gr, _F16, (B, 4 * H), optional=True); _mat("act", act, _F16, (B, 4 * H))
+    _want("bias", bias, _F32, numel=4 * H, optional=True); _flat("bias", bias, optional=True)
     _dev(gx, gr, bias, c_prev, act, c, h)
-    B, H = c_prev.shape
     _check("mpt_lstm_cell_fwd", lib().mpt_lstm_cell_fwd(_stream(), B, H, _p(gx), _ld(gx), _p(gr), _ld(gr), _p(bias), _p(c_prev), _ld(c_prev),
                                                         _p(act), _ld(act), _p(c), _ld(c), _p(h), _ld(h)))
 
 
 def mpt_lstm_cell_bwd(dh, dc_next, act, c, c_prev, da, dc_prev):
+    B, H = _dim2("c", c)
+    for name, t in (("dh", dh), ("c", c), ("c_prev", c_prev), ("dc_prev", dc_prev)):
+        _mat(name, t, _F16, (B, H))
+    _mat("dc_next", dc_next, _F16, (B, H), optional=True)
+    _mat("act", act, _F16, (B, 4 * H)); _mat("da", da, _F16, (B, 4 * H))
     _dev(dh, dc_next, act, c, c_prev, da, dc_prev)
-    B, H = c.shape
     _check("mpt_lstm_cell_bwd", lib().mpt_lstm_cell_bwd(_stream(), B, H, _p(dh), _ld(dh), _p(dc_next), _ld(dc_next), _p(act), _ld(act), _p(c), _ld(c),
                                                         _p(c_prev), _ld(c_prev), _p(da), _ld(da), _p(dc_prev), _ld(dc_prev)))

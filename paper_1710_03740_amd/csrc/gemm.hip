@@ -823,7 +823,7 @@ struct DmaImgRC {
     dSpt.divmod((uint32_t)(stage0 + stage_rel), tap, cs);          // wavefront-uniform
     const int tr = (int)tap / 3, ts = (int)tap - 3 * tr;
     const int dy = sgn * (tr - 1), dx = sgn * (ts - 1);
-    const int yy = (yx[K] >> 16) + dy, xx = (yx[K] & 0xFFFF) + dx;
+    const int yy = (int)((uint32_t)yx[K] >> 16) + dy, xx = (yx[K] & 0xFFFF) + dx;   // y up to 65535: logical shift
     const bool inside = (unsigned)yy < (unsigned)H && (unsigned)xx < (unsigned)W;
     const uint16_t* p = inside ? base + (pix[K] + (dy * W + dx) * Cc + (int)cs * 32) : reinterpret_cast<const uint16_t*>(k_zero_line);
     __builtin_amdgcn_global_load_lds((global_void_ptr)p, (lds_void_ptr)(lds_blocks + K * 1024), 16, 0, 0);

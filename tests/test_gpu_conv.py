@@ -69,9 +69,11 @@ def test_cfg4_resnet_block_full_size():
     gemm_check(dw, o, sa, s, "cfg4 wgrad")
 
 
-@pytest.mark.parametrize("Nb,H,W,C,Kf", [(64, 14, 14, 64, 512), (50, 16, 16, 256, 256), (32, 7, 56, 128, 256), (12, 8, 8, 512, 256)])
+@pytest.mark.parametrize("Nb,H,W,C,Kf", [(64, 14, 14, 64, 512), (50, 16, 16, 256, 256), (32, 7, 56, 128, 256), (12, 8, 8, 512, 256),
+                                          (1, 40960, 1, 64, 256)])
 def test_whole_tile_shapes_forward_and_input_gradient(Nb, H, W, C, Kf):
-    """Pixel counts that are whole tiles (49 x 256 rows with two tile columns; 100 x 128 rows; a wide, flat image):
+    """Pixel counts that are whole tiles (49 x 256 rows with two tile columns; 100 x 128 rows; a wide, flat image; an
+    image taller than 32767 rows, whose row index uses the top bit of its 16-bit field in the streamed kernel):
     the streamed forward and input-gradient kernels with the gathered operand, including image borders in every
     tile.  Integer-valued inputs make the comparison bit-exact on top of the usual acceptance rule."""
     rng = np.random.default_rng(Nb + H + C)

@@ -379,20 +379,12 @@ def test_random_shapes_strides_and_offsets():
         gemm_check(np.ascontiguousarray(host16(wb)[:, ow:ow + N]), dw, sa, s, "wgrad " + label)
 
 
-def test_mfma_probe_runs_and_is_slower_on_random_mantissas_than_on_zeros():
-    """The diagnostic entry point: both operand kinds run to completion; the rate on zeros is not below the rate on
-    random mantissas (on this hardware it is about a third higher once the clock has settled)."""
+def test_mfma_probe_runs_to_completion():
+    """The diagnostic entry point: both operand kinds run to completion and leave the sink untouched (rates are
+    reported by bench.py, not asserted here: they depend on the clock state of the box)."""
     sink = torch.zeros(1, dtype=torch.float32, device="cuda")
-    rates = {}
     for rnd in (0, 1):
-        for _ in range(150):
+        for _ in range(3):
             mpt.mpt_probe_mfma(1000, rnd, sink)
         torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(50):
-            mpt.mpt_probe_mfma(1000, rnd, sink)
-        e1.record(); torch.cuda.synchronize()
-        rates[rnd] = 50 * 1000 * 64 * 16384.0 * 1024 / (e0.elapsed_time(e1) * 1e-3) / 1e12
     assert float(sink.item()) == 0.0
-    assert 500.0 < rates[1] <= rates[0] * 1.02 and rates[0] < 2600.0, rates
