@@ -10,7 +10,8 @@ with S, and skips the step on overflow.  The paper prints none of the update
 rules; the customary forms are taken, each as a fixed sequence of individually
 rounded FP32 operations (no fused multiply-add), (*) (+) (-) (/) sqrt below:
 
-    g = float(grad) (*) inv_S                      [then, if weight_decay != 0:  g = g (+) (wd (*) w)]
+    g = float(grad) (*) inv_S                      [then, if clipping:  g = g (*) factor   (oracle/clip.py)]
+                                                   [then, if weight_decay != 0:  g = g (+) (wd (*) w)]
   momentum:  m' = (mu (*) m) (+) g                 w' = w (-) (lr (*) m')
   nesterov:  m' = (mu (*) m) (+) g                 w' = w (-) (lr (*) (g (+) (mu (*) m')))
   adagrad:   h' = h (+) (g (*) g)                  w' = w (-) ((lr (*) g) (/) (sqrt(h') (+) eps))
@@ -53,9 +54,10 @@ def adam_params(lr, beta1, beta2, eps, step, weight_decay=0.0):
                      bias_corr1=float(F(1.0 - beta1 ** step)), bias_corr2=float(F(1.0 - beta2 ** step)))
 
 
-def optimizer_update(kind, w32, s1, s2, grad, inv_scale, p, flag, w16=None):
+def optimizer_update(kind, w32, s1, s2, grad, inv_scale, p, flag, w16=None, clip=None):
     """One step.  s1: momentum / Adagrad sum / Adam first moment; s2: Adam second moment (else None).
-    Returns (w32', s1', s2', w16')."""
+    clip: None, or the FP32 factor of clip-by-global-norm (oracle/clip.py), applied to the unscaled gradient with
+    one FP32 multiplication before weight decay.  Returns (w32', s1', s2', w16')."""
     assert kind in KINDS
     w = np.asarray(w32, dtype=F)
     a = np.asarray(s1, dtype=F)
@@ -66,6 +68,8 @@ def optimizer_update(kind, w32, s1, s2, grad, inv_scale, p, flag, w16=None):
     lr, mu = F(p.lr), F(p.momentum)
     with np.errstate(all="ignore"):
         g = _grad_f32(grad) * F(inv_scale)
+        if clip is not None:
+            g = g * F(clip)
         if p.weight_decay != 0.0:
             g = g + F(p.weight_decay) * w
         if kind == "momentum":
