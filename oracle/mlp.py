@@ -2,8 +2,9 @@
 the oracle's parts in the order of the paper's iteration (Fig. 1 caption and
 Sec. 3.1-3.3): FP16 copy -> forward -> scaled loss -> backward-activation and
 backward-weight -> unscale + overflow check -> FP32 master update -> FP16 copy.
-Test infrastructure only.  Parity unpinned beyond the composition of pinned
-parts: the paper prints no numbers for such a step.
+Test infrastructure only.  The paper prints no numbers for such a step; the
+wiring is pinned stage by stage, and end to end, against FP64 autograd of the
+same network (tests/test_oracle_mlp.py).
 """
 from . import gemm, loss, update
 
