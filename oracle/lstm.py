@@ -66,3 +66,41 @@ def lstmp_layer_fwd(x16, Wx16, Wr16, Wp16, bias32, r0_16, c0_16):
         r, _ = gemm.gemm_fwd(h, Wp16)
         out.append(dict(gx=gx_all[t], gr=gr, act=act, c=c, h=h, r=r))
     return out
+
+
+def lstmp_layer_bwd(x16, Wx16, Wr16, Wp16, r0_16, c0_16, fwd, dr_ext16, dc_last16=None):
+    """Backward pass through time of the free-running layer (the reverse of lstmp_layer_fwd, same stored tensors).
+
+    fwd: the list lstmp_layer_fwd returned.  dr_ext16: [T, B, P], the gradient of the (scaled) loss with respect to
+    each projected output r_t as it arrives from the layers above.  dc_last16: gradient with respect to the last
+    cell state (None = 0).  Per step, last to first, every stored tensor FP16, every contraction by the GEMM rule:
+        dr_t   = rne16(dr_ext_t + dr_rec)            dr_rec: what step t+1 sent back through W_r (0 at the last step)
+        dh_t   = dr_t W_p^T                           (activation gradient of the projection)
+        da_t, dc_prev = cell backward(dh_t, dc_next, act_t, c_t, c_{t-1})
+        dr_rec = da_t W_r^T                           (activation gradient of the recurrent product)
+    and over all steps at once (reduction length T*B, one FP16 store each, Sec. 3.3):
+        dx = dA W_x^T;   dW_x = x^T dA;   dW_r = r_prev^T dA;   dW_p = h^T dR;   dbias = sum over rows of dA (FP32)
+    Returns a dict; "da", "dh", "dr" are lists per step."""
+    T, B, I = x16.shape
+    P = Wp16.shape[1]
+    dr_rec = np.zeros((B, P), dtype=np.float16)
+    dc_next = np.zeros_like(c0_16) if dc_last16 is None else dc_last16
+    da_l, dh_l, dr_l = [None] * T, [None] * T, [None] * T
+    for t in range(T - 1, -1, -1):
+        dr = rne16(to_f64(dr_ext16[t]) + to_f64(dr_rec))
+        dh, _ = gemm.gemm_dgrad(dr, Wp16)
+        c_prev = fwd[t - 1]["c"] if t > 0 else c0_16
+        da, dc_next = lstm_cell_bwd(dh, dc_next, fwd[t]["act"], fwd[t]["c"], c_prev)
+        dr_rec, _ = gemm.gemm_dgrad(da, Wr16)
+        da_l[t], dh_l[t], dr_l[t] = da, dh, dr
+    dA = np.concatenate(da_l, axis=0)
+    dR = np.concatenate(dr_l, axis=0)
+    h_all = np.concatenate([f["h"] for f in fwd], axis=0)
+    r_prev = np.concatenate([r0_16] + [f["r"] for f in fwd[:-1]], axis=0)
+    dx, _ = gemm.gemm_dgrad(dA, Wx16)
+    dWx, _ = gemm.gemm_wgrad(x16.reshape(T * B, I), dA)
+    dWr, _ = gemm.gemm_wgrad(r_prev, dA)
+    dWp, _ = gemm.gemm_wgrad(h_all, dR)
+    dbias = to_f64(dA).sum(axis=0).astype(np.float32)
+    return dict(da=da_l, dh=dh_l, dr=dr_l, dx=dx.reshape(T, B, I), dWx=dWx, dWr=dWr, dWp=dWp, dbias=dbias,
+                dr0=dr_rec, dc0=dc_next)

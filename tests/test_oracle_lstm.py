@@ -93,3 +93,65 @@ def test_layer_is_the_composition_of_cell_and_contractions():
         r, _ = gemm.gemm_fwd(h, Wp)
         assert np.array_equal(fp16.bits(r), fp16.bits(out[t]["r"])) and np.array_equal(fp16.bits(c), fp16.bits(out[t]["c"]))
     assert np.abs(out[-1]["r"].astype(np.float64)).max() > 0
+
+
+def _torch_layer(x, Wx, Wr, Wp, bias, r0, c0):
+    """The same layer in FP64 torch, nothing rounded: returns the lists of r_t and c_t."""
+    T = x.shape[0]
+    H = Wp.shape[0]
+    r, c, rs, cs = r0, c0, [], []
+    for t in range(T):
+        a = x[t] @ Wx + r @ Wr + bias
+        i, f, o = torch.sigmoid(a[:, :H]), torch.sigmoid(a[:, H:2 * H]), torch.sigmoid(a[:, 3 * H:])
+        g = torch.tanh(a[:, 2 * H:3 * H])
+        c = f * c + i * g
+        r = (o * torch.tanh(c)) @ Wp
+        rs.append(r); cs.append(c)
+    return rs, cs
+
+
+def test_backward_through_time_against_fp64_autograd():
+    """lstmp_layer_bwd against autograd of the un-rounded FP64 layer with the loss sum_t <dr_ext_t, r_t> + <dc_last, c_T>,
+    whose gradient with respect to r_t is exactly dr_ext_t.  The oracle stores FP16 at every stage, so agreement is to
+    FP16 accuracy; a structural mistake (recurrent gradient not carried, the state gradient dropped, W_r and W_p
+    confused or not transposed, c_{t-1} taken from the wrong step, the time-batched sums missing a step) is off by
+    tens of percent.  Planted versions of three such mistakes are shown to fail the same comparison."""
+    rng = np.random.default_rng(11)
+    T, B, I, H, P = 5, 6, 10, 12, 8
+    x = _f16(rng.standard_normal((T, B, I)))
+    Wx, Wr, Wp = _f16(rng.uniform(-0.4, 0.4, (I, 4 * H))), _f16(rng.uniform(-0.4, 0.4, (P, 4 * H))), _f16(rng.uniform(-0.5, 0.5, (H, P)))
+    bias = rng.uniform(-0.2, 0.2, 4 * H).astype(np.float32)
+    r0, c0 = _f16(rng.standard_normal((B, P)) * 0.5), _f16(rng.standard_normal((B, H)) * 0.5)
+    dr_ext = _f16(rng.standard_normal((T, B, P)) * 0.25)
+    dc_last = _f16(rng.standard_normal((B, H)) * 0.25)
+    fwd = lstm.lstmp_layer_fwd(x, Wx, Wr, Wp, bias, r0, c0)
+    out = lstm.lstmp_layer_bwd(x, Wx, Wr, Wp, r0, c0, fwd, dr_ext, dc_last)
+
+    t = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float64)).requires_grad_(True)
+    tx, tWx, tWr, tWp, tb, tr0, tc0 = t(x), t(Wx), t(Wr), t(Wp), t(bias), t(r0), t(c0)
+    rs, cs = _torch_layer(tx, tWx, tWr, tWp, tb, tr0, tc0)
+    loss = sum((torch.from_numpy(dr_ext[k].astype(np.float64)) * rs[k]).sum() for k in range(T)) + (torch.from_numpy(dc_last.astype(np.float64)) * cs[-1]).sum()
+    loss.backward()
+    # forward first: the stored r_t follow the FP64 layer to FP16 accuracy
+    for k in range(T):
+        assert np.abs(fwd[k]["r"].astype(np.float64) - rs[k].detach().numpy()).max() < 2.0 ** -7
+
+    def close(got, want, name, tol=2.0 ** -6):
+        got, want = np.asarray(got, dtype=np.float64), want.numpy()
+        err = np.abs(got - want).max() / np.abs(want).max()
+        assert err < tol, (name, err)
+        return err
+
+    pairs = (("dx", tx), ("dWx", tWx), ("dWr", tWr), ("dWp", tWp), ("dbias", tb), ("dr0", tr0), ("dc0", tc0))
+    for name, ten in pairs:
+        close(out[name], ten.grad, name)
+
+    def wrong(mutate):
+        bad = mutate()
+        return max(np.abs(np.asarray(bad[n], dtype=np.float64) - ten.grad.numpy()).max() / np.abs(ten.grad.numpy()).max() for n, ten in pairs)
+
+    # planted mistakes, each in a copy of the routine's inputs / structure
+    assert wrong(lambda: lstm.lstmp_layer_bwd(x, Wx, Wr, Wp, r0, c0, fwd, dr_ext, None)) > 0.05                      # state gradient dropped
+    shifted = [fwd[0]] + fwd[:-1]
+    assert wrong(lambda: lstm.lstmp_layer_bwd(x, Wx, Wr, Wp, r0, c0, shifted, dr_ext, dc_last)) > 0.05              # stored tensors of the wrong step
+    assert wrong(lambda: lstm.lstmp_layer_bwd(x, Wx, np.zeros_like(Wr), Wp, r0, c0, fwd, dr_ext, dc_last)) > 0.05   # recurrent gradient not carried
