@@ -33,6 +33,10 @@ typedef float float4v __attribute__((ext_vector_type(4)));
 typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
 typedef uint32_t uint2v __attribute__((ext_vector_type(2)));
 
+#ifndef MPT_GEMM_DEPTH_DEFAULT
+#define MPT_GEMM_DEPTH_DEFAULT 64  // reduction depth per stage of the streamed 256 x 256 kernel: 64 (k_gemm_dma64) or 32 (k_gemm_dma4)
+#endif
+
 namespace {
 
 constexpr int BK = 64;            // reduction depth of one LDS tile
@@ -1238,6 +1242,368 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   }
 }
 
+// ---------------------------------------------------------------- one wavefront per SIMD, reduction depth 64 per stage
+// The same tile, wavefront blocks, fragment schedule and epilogue as k_gemm_dma4 (BM = 256), with the operand slices
+// moved in stages of reduction depth 64: a reduction-contiguous operand is then fetched as whole 128-byte row
+// slices, one cache line per 8 lanes, where a depth-32 stage asks the L2 for half lines (twice the requests).
+// LDS holds two slots of 32 KiB per operand (A at 0 and 32 KiB, B at 64 and 96 KiB); a slot is one stage:
+//   RC operand: [256 outer][128 B]; 16-byte chunk c (0..7, reduction indices 8c..8c+7) of row o at chunk c ^ ((o >> 1) & 7)
+//               (16 lanes reading the same chunk of 16 consecutive rows then cover all 64 banks once);
+//   OC operand: two depth-32 images of k_gemm_dma4's layout, 16 KiB each.
+// A stage is consumed as two half stages of depth 32 (8 steps of 8 MFMAs each, exactly k_gemm_dma4's stage), so the
+// fragment requests, waits and their immediates are the same; only the movement differs.  Per stage D (16 steps):
+//   step 0   barrier F: every wavefront has finished reading A(D-1); steps 0-3 then fetch A(D+1) into its slot;
+//   step 12  wait for all own loads, barrier P: A(D+1) and B(D+1) have landed everywhere, and every wavefront holds
+//            the last B fragments of stage D in registers; steps 12-15 then fetch B(D+2) into B(D)'s slot.
+// Loads are issued two per step, each alone in a gap between MFMAs; the youngest is 9 steps old when it must have
+// landed, as in k_gemm_dma4.  Requirements (host): I, J multiples of 256, R of 64, unsplit FP16 store.
+template <bool RC>
+struct DmaOperand64 {
+  typedef DmaMat Src;
+  static constexpr bool kRC = RC;
+  static constexpr int NB = 8;       // 1 KiB blocks per wavefront per stage (256 outer x 64 r halves = 32 KiB / 4 wavefronts)
+  const uint16_t* p[RC ? 2 : 4];     // RC: lane's source in blocks 0 and 1 (blocks 2j, 2j+1 lie 16j rows further); OC: blocks 0-3 (4-7: 32 r further)
+  int64_t ld;
+  __device__ __forceinline__ void init(const DmaMat& m, int o0, int wave, int lane) {
+    ld = m.ld;
+    if constexpr (RC) {
+#pragma unroll
+      for (int k = 0; k < 2; ++k) {                                  // block k of the wavefront: rows 64w + 8k .. +7, lane -> (row, position)
+        const int row = wave * 64 + k * 8 + (lane >> 3);
+        const int chunk = (lane & 7) ^ ((row >> 1) & 7);             // rows 16 further have the same key
+        p[k] = m.base + (int64_t)(o0 + row) * m.ld + chunk * 8;
+      }
+    } else {
+      const int pc = lane & 31;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int row = (wave * 4 + k) * 2 + (lane >> 5);
+        const int c = 2 * ((pc >> 1) ^ oc_key(row)) + (pc & 1);
+        p[k] = m.base + (int64_t)row * m.ld + o0 + c * 8;
+      }
+    }
+  }
+  // K-th load of stage d (reduction indices 64d .. 64d+63) into the operand slot at `slot`
+  template <int K>
+  __device__ __forceinline__ void issue(int d, char* slot, int wave) const {
+    if constexpr (RC) {
+      const uint16_t* src = p[K & 1] + ((int64_t)d * 64 + (int64_t)(K >> 1) * 16 * ld);
+      __builtin_amdgcn_global_load_lds((global_void_ptr)src, (lds_void_ptr)(slot + (wave * 8 + K) * 1024), 16, 0, 0);
+    } else {
+      const uint16_t* src = p[K & 3] + (int64_t)(2 * d + (K >> 2)) * 32 * ld;
+      __builtin_amdgcn_global_load_lds((global_void_ptr)src, (lds_void_ptr)(slot + (K >> 2) * 16384 + (wave * 4 + (K & 3)) * 1024), 16, 0, 0);
+    }
+  }
+};
+
+// The convolution's gathered image rows (see DmaImgRC) for stages of depth 64: Cc is a multiple of 64, so a stage is
+// 64 consecutive channels of one tap, a whole 128-byte line per pixel.  Src::dSpt divides by the stages per tap, Cc / 64.
+struct DmaImgRC64 {
+  typedef DmaImgSrc Src;
+  static constexpr bool kRC = true;
+  const uint16_t* base;
+  int32_t pix[8];                  // element offset of the lane's pixel (centre tap) + its 16-byte chunk, per block
+  int32_t yx[8];                   // y << 16 | x
+  int H, W, Cc, sgn;
+  FastDiv dSpt;
+  __device__ __forceinline__ void init(const Src& m, int o0, int wave, int lane) {
+    base = m.base; H = m.H; W = m.W; Cc = m.Cc; sgn = m.sgn; dSpt = m.dSpt;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int row = wave * 64 + k * 8 + (lane >> 3);
+      const int chunk = (lane & 7) ^ ((row >> 1) & 7);
+      uint32_t n, rem, y, x;
+      m.dHW.divmod((uint32_t)(o0 + row), n, rem);
+      m.dW.divmod(rem, y, x);
+      pix[k] = (int32_t)(((n * (uint32_t)H + y) * (uint32_t)W + x) * (uint32_t)Cc) + chunk * 8;
+      yx[k] = (int32_t)((y << 16) | x);
+    }
+  }
+  template <int K>
+  __device__ __forceinline__ void issue(int d, char* slot, int wave) const {
+    uint32_t tap, cs;
+    dSpt.divmod((uint32_t)d, tap, cs);                               // wavefront-uniform
+    const int tr = (int)tap / 3, ts = (int)tap - 3 * tr;
+    const int dy = sgn * (tr - 1), dx = sgn * (ts - 1);
+    const int yy = (int)((uint32_t)yx[K] >> 16) + dy, xx = (yx[K] & 0xFFFF) + dx;
+    const bool inside = (unsigned)yy < (unsigned)H && (unsigned)xx < (unsigned)W;
+    const uint16_t* p = inside ? base + (pix[K] + (dy * W + dx) * Cc + (int)cs * 64) : reinterpret_cast<const uint16_t*>(k_zero_line);
+    __builtin_amdgcn_global_load_lds((global_void_ptr)p, (lds_void_ptr)(slot + (wave * 8 + K) * 1024), 16, 0, 0);
+  }
+};
+
+// The filter read outer-contiguous for the input-gradient pass (see DmaFilterOC), stages of depth 64: Kf is a multiple
+// of 64, so a stage is 64 consecutive k of one tap; Src::dSpt divides by the stages per tap, Kf / 64.
+struct DmaFilterOC64 {
+  typedef DmaFilterSrc Src;
+  static constexpr bool kRC = false;
+  const uint16_t* p[4];            // lane's source for reduction row (k = row, tap = 0) of blocks 0-3 (4-7: 32 k further)
+  int Cc;
+  FastDiv dSpt;
+  __device__ __forceinline__ void init(const Src& m, int o0, int wave, int lane) {
+    Cc = m.Cc; dSpt = m.dSpt;
+    const int pc = lane & 31;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int row = (wave * 4 + k) * 2 + (lane >> 5);
+      const int c = 2 * ((pc >> 1) ^ oc_key(row)) + (pc & 1);
+      p[k] = m.base + (int64_t)row * 9 * m.Cc + o0 + c * 8;
+    }
+  }
+  template <int K>
+  __device__ __forceinline__ void issue(int d, char* slot, int wave) const {
+    uint32_t tap, ks;
+    dSpt.divmod((uint32_t)d, tap, ks);
+    const uint16_t* q = p[K & 3] + ((int64_t)((int)ks * 64 + (K >> 2) * 32) * 9 + tap) * Cc;
+    __builtin_amdgcn_global_load_lds((global_void_ptr)q, (lds_void_ptr)(slot + (K >> 2) * 16384 + (wave * 4 + (K & 3)) * 1024), 16, 0, 0);
+  }
+};
+
+// Fragment addresses for the depth-64 slots: two registers per fragment.  RC: the lane's address for the first and
+// the second half stage (they differ by an XOR, not by a constant); the slot goes into the immediate.  OC: the two
+// transposing reads of a fragment; slot and half stage go into the immediate.
+template <bool RC>
+struct FragAddr64 {
+  uint32_t at[2];
+  __device__ __forceinline__ void init(int outer0, int lane, uint32_t operand0) {
+    if constexpr (RC) {
+      const int r = outer0 + (lane & 15), c = lane >> 4;
+#pragma unroll
+      for (int kh = 0; kh < 2; ++kh) at[kh] = operand0 + r * 128 + ((((kh << 2) | c) ^ ((r >> 1) & 7)) << 4);
+    } else {
+      FragAddr<false, 256> f;
+      f.init(outer0, lane);
+      at[0] = operand0 + f.off[0];
+      at[1] = operand0 + f.off[1];
+    }
+  }
+  template <int SLOT4>                                               // SLOT4 = 2 * slot + half stage
+  __device__ __forceinline__ half8 read() const {
+    if constexpr (RC) {
+      return lds_read_b128_imm<(SLOT4 >> 1) * 32768>(at[SLOT4 & 1]);
+    } else {
+      constexpr int IMM = (SLOT4 >> 1) * 32768 + (SLOT4 & 1) * 16384;
+      const uint2v lo = lds_read_tr_b64_imm<IMM>(at[0]);
+      const uint2v hi = lds_read_tr_b64_imm<IMM>(at[1]);
+      uint4v q = {lo[0], lo[1], hi[0], hi[1]};
+      return __builtin_bit_cast(half8, q);
+    }
+  }
+};
+
+template <class AOp, class BOp>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_gemm_dma64(typename AOp::Src A, typename BOp::Src B, Problem pb, Epilogue ep) {
+  constexpr bool A_RC = AOp::kRC, B_RC = BOp::kRC;
+  constexpr int NA = 8, HALF = 4, BM = 256;
+  typedef FragSched<NA> Sched;
+  constexpr int AD = Sched::kADist;
+  constexpr int OPSLOT = 32768, B_BASE = 2 * OPSLOT;
+  constexpr int RA1 = A_RC ? 1 : 2, RB1 = B_RC ? 1 : 2;
+  static_assert(Sched::kSpread && AD == 2, "the request schedule this kernel was written for");
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  const int t = threadIdx.x, lane = t & 63, wave = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+  int ti, tj, sp;
+  tile_of(pb, blockIdx.x, ti, tj, sp);
+  const int i0 = ti * BM, j0 = tj * 256;
+  const int nd = pb.R / 64;                                            // stages (>= 1)
+  const int nst = 2 * nd;                                              // half stages
+
+  AOp da;
+  BOp db;
+  da.init(A, i0, wave, lane);
+  db.init(B, j0, wave, lane);
+  // load K of stage d of A / B into slot `sl`; past the end: refetch the last stage into a slot nobody reads
+  auto issueA = [&](int d, int sl, auto kc) { da.template issue<decltype(kc)::value>(min(d, nd - 1), lds + sl * OPSLOT, wave); };
+  auto issueB = [&](int d, int sl, auto kc) { db.template issue<decltype(kc)::value>(min(d, nd - 1), lds + B_BASE + sl * OPSLOT, wave); };
+  auto issueA8 = [&](int d, int sl) {
+    issueA(d, sl, std::integral_constant<int, 0>{}); issueA(d, sl, std::integral_constant<int, 1>{});
+    issueA(d, sl, std::integral_constant<int, 2>{}); issueA(d, sl, std::integral_constant<int, 3>{});
+    issueA(d, sl, std::integral_constant<int, 4>{}); issueA(d, sl, std::integral_constant<int, 5>{});
+    issueA(d, sl, std::integral_constant<int, 6>{}); issueA(d, sl, std::integral_constant<int, 7>{});
+  };
+  auto issueB8 = [&](int d, int sl) {
+    issueB(d, sl, std::integral_constant<int, 0>{}); issueB(d, sl, std::integral_constant<int, 1>{});
+    issueB(d, sl, std::integral_constant<int, 2>{}); issueB(d, sl, std::integral_constant<int, 3>{});
+    issueB(d, sl, std::integral_constant<int, 4>{}); issueB(d, sl, std::integral_constant<int, 5>{});
+    issueB(d, sl, std::integral_constant<int, 6>{}); issueB(d, sl, std::integral_constant<int, 7>{});
+  };
+  // prologue: stage 0 whole and the B part of stage 1 (steps 0-3 of stage 0 add its A part); the loads go out first so
+  // that the set-up below runs under their latency
+  issueA8(0, 0);
+  issueB8(0, 0);
+  issueB8(1, 1);
+
+  float4v acc[NA][8];
+#pragma unroll
+  for (int a = 0; a < NA; ++a)
+#pragma unroll
+    for (int b = 0; b < 8; ++b)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) acc[a][b][v] = 0.f;
+#pragma unroll
+  for (int a = 0; a < NA; ++a)
+#pragma unroll
+    for (int b = 0; b < 8; ++b) asm volatile("" : "+a"(acc[a][b]));      // cleared here, under the loads' latency, not behind the barrier
+  const uint32_t lds0 = lds_offset(lds);
+  FragAddr64<A_RC> aa[NA];
+  FragAddr64<B_RC> ab[8];
+#pragma unroll
+  for (int a = 0; a < NA; ++a) aa[a].init(wm * 128 + a * 16, lane, lds0);
+#pragma unroll
+  for (int b = 0; b < 8; ++b) ab[b].init(wn * 128 + b * 16, lane, lds0 + B_BASE);
+  half8 fa[NA], fb[2][8];
+
+  asm volatile("s_waitcnt vmcnt(8)\n\ts_barrier" ::: "memory");          // stage 0 has landed everywhere (the 8 loads of B(1) may be in flight)
+#pragma unroll
+  for (int b = 0; b < 8; ++b) fb[0][b] = ab[b].template read<0>();
+#pragma unroll
+  for (int a = 0; a < AD; ++a) fa[a] = aa[a].template read<0>();
+
+  // One step of half stage s (SLOT4 = s % 4 = 2 * slot + half): as in k_gemm_dma4, plus this kernel's barriers and loads.
+  auto step = [&](int s, auto slotc, auto ac, half8 (&fb_cur)[8], half8 (&fb_nxt)[8]) {
+    constexpr int a = decltype(ac)::value, SLOT4 = decltype(slotc)::value;
+    constexpr int KH = SLOT4 & 1, SL = SLOT4 >> 1;
+    constexpr int SLOT4_A = (SLOT4 + (a + AD) / NA) % 4;               // half stage of the A block requested in this step
+    constexpr int SLOT4_B = (SLOT4 + 1) % 4;                           // half stage of the B blocks requested in this step
+    if constexpr (KH == 1 && a == HALF) {
+      // P: the B requests of this step and the A requests of steps 6, 7 read stage D+1, whose loads (A: steps 0-3 of
+      // this stage, B: steps 12-15 of the last one) are all of this wavefront's loads in flight.
+      asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+    }
+    constexpr int B0 = Sched::nb_before(a);
+    constexpr int na = (a + AD) % NA;
+    __builtin_amdgcn_sched_barrier(0);
+    constexpr int W = Sched::allowed(a, RA1, RB1);
+    if constexpr (a == 0) wait_frags9<W>(fa[0], fb_cur);
+    else wait_frag1<W>(fa[a]);
+    if constexpr (KH == 0 && a == 0) {
+      // F: this wavefront's reads of stage D-1 have all returned (the LDS returns data in order and the fragments
+      // just waited for were requested after them); once every wavefront is here, A(D-1)'s slot may be refilled.
+      asm volatile("s_barrier" ::: "memory");
+    }
+#pragma unroll
+    for (int b = 0; b < 8; ++b) {
+      mfma_acc(acc[a][b], fb_cur[b], fa[a]);
+      if (b == 0) {
+        __builtin_amdgcn_sched_barrier(0);
+        fa[na] = aa[na].template read<SLOT4_A>();
+        __builtin_amdgcn_sched_barrier(0);
+      }
+#pragma unroll
+      for (int k = 0; k < Sched::nb_at(a); ++k)
+        if (b == Sched::b_gap(k)) {
+          __builtin_amdgcn_sched_barrier(0);
+          fb_nxt[B0 + k] = ab[B0 + k].template read<SLOT4_B>();
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      // two loads per step in gaps that carry no fragment request: behind MFMAs 2 and 6
+      if constexpr (KH == 0 && a < HALF) {                             // A(D+1) into the other A slot
+        if (b == 2) {
+          __builtin_amdgcn_sched_barrier(0);
+          issueA((s >> 1) + 1, 1 - SL, std::integral_constant<int, 2 * a>{});
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        if (b == 6) {
+          __builtin_amdgcn_sched_barrier(0);
+          issueA((s >> 1) + 1, 1 - SL, std::integral_constant<int, 2 * a + 1>{});
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+      if constexpr (KH == 1 && a >= HALF) {                            // B(D+2) into this stage's B slot
+        if (b == 2) {
+          __builtin_amdgcn_sched_barrier(0);
+          issueB((s >> 1) + 2, SL, std::integral_constant<int, 2 * (a - HALF)>{});
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        if (b == 6) {
+          __builtin_amdgcn_sched_barrier(0);
+          issueB((s >> 1) + 2, SL, std::integral_constant<int, 2 * (a - HALF) + 1>{});
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  auto half_stage = [&](int s, auto slotc, half8 (&fb_cur)[8], half8 (&fb_nxt)[8]) {
+    step(s, slotc, std::integral_constant<int, 0>{}, fb_cur, fb_nxt);
+    step(s, slotc, std::integral_constant<int, 1>{}, fb_cur, fb_nxt);
+    step(s, slotc, std::integral_constant<int, 2>{}, fb_cur, fb_nxt);
+    step(s, slotc, std::integral_constant<int, 3>{}, fb_cur, fb_nxt);
+    step(s, slotc, std::integral_constant<int, 4>{}, fb_cur, fb_nxt);
+    step(s, slotc, std::integral_constant<int, 5>{}, fb_cur, fb_nxt);
+    step(s, slotc, std::integral_constant<int, 6>{}, fb_cur, fb_nxt);
+    step(s, slotc, std::integral_constant<int, 7>{}, fb_cur, fb_nxt);
+  };
+  typedef std::integral_constant<int, 0> S0;
+  typedef std::integral_constant<int, 1> S1;
+  typedef std::integral_constant<int, 2> S2;
+  typedef std::integral_constant<int, 3> S3;
+  // accumulator copies on the edges where the loop's exit and the one-stage tail meet: see k_gemm_dma4
+  int s = 0;
+  for (; s + 4 <= nst; s += 4) {
+    half_stage(s, S0{}, fb[0], fb[1]);
+    half_stage(s + 1, S1{}, fb[1], fb[0]);
+    half_stage(s + 2, S2{}, fb[0], fb[1]);
+    half_stage(s + 3, S3{}, fb[1], fb[0]);
+    if (s + 8 > nst) asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+  }
+  if (s < nst) {                                                       // one stage left, in slot 0
+    half_stage(s, S0{}, fb[0], fb[1]);
+    half_stage(s + 1, S1{}, fb[1], fb[0]);
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+  }
+  asm volatile("s_nop 15\n\ts_nop 15\n\ts_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+#pragma unroll
+  for (int a = 0; a < NA; ++a) keep_until_here(fa[a]);
+#pragma unroll
+  for (int b = 0; b < 8; ++b) {
+    keep_until_here(fb[0][b]); keep_until_here(fb[1][b]);
+  }
+  __builtin_amdgcn_sched_barrier(0);
+
+  // ---- epilogue: k_gemm_dma4's FP16 store through LDS (whole tiles, 16-byte aligned rows)
+  bool bad = false;
+  __syncthreads();
+  char* mine = lds + wave * (BM / 2 * 256);
+  const int li = lane & 15, lg = lane >> 4;
+#pragma unroll
+  for (int a = 0; a < NA; ++a)
+#pragma unroll
+    for (int b = 0; b < 8; ++b) {
+      asm volatile("" : "+a"(acc[a][b]) : : "memory");
+      half4 h;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) h[e] = (_Float16)acc[a][b][e];
+      *reinterpret_cast<half4*>(mine + (a * 16 + li) * 256 + (((2 * b + (lg >> 1)) ^ li) << 4) + (lg & 1) * 8) = h;
+    }
+  uint16_t* out = reinterpret_cast<uint16_t*>(ep.out) + (int64_t)(i0 + wm * (BM / 2)) * ep.ld + j0 + wn * 128 + li * 8;
+#pragma unroll 8
+  for (int it = 0; it < BM / 8; ++it) {
+    const int r = it * 4 + lg;
+    uint4v q = *reinterpret_cast<const uint4v*>(mine + r * 256 + ((li ^ (r & 15)) << 4));
+    if (ep.act == 1) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        q[e] &= (half_bits_positive(q[e]) ? 0x0000FFFFu : 0u) | (half_bits_positive(q[e] >> 16) ? 0xFFFF0000u : 0u);
+    } else if (ep.act == 2) {
+      const uint4v m = *reinterpret_cast<const uint4v*>(ep.mask + (int64_t)(i0 + wm * (BM / 2) + r) * ep.ldmask + j0 + wn * 128 + li * 8);
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        q[e] &= (half_bits_positive(m[e]) ? 0x0000FFFFu : 0u) | (half_bits_positive(m[e] >> 16) ? 0xFFFF0000u : 0u);
+    }
+    if (ep.flag) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) bad |= half_bits_special(q[e]) | half_bits_special(q[e] >> 16);
+    }
+    *reinterpret_cast<uint4v*>(out + (int64_t)r * ep.ld) = q;
+  }
+  if (ep.flag != nullptr) {
+    const unsigned long long vote = __builtin_amdgcn_ballot_w64(bad);
+    if (vote != 0ull && lane == 0) atomicOr(ep.flag, 1u);
+  }
+}
+
 // Sum split partials in split order (fixed, so results are reproducible), then store once.
 __global__ __launch_bounds__(256) void k_split_reduce(const float* __restrict__ part, int splits, int I, int J, Epilogue ep) {
   const int64_t total = (int64_t)I * J;
@@ -1377,7 +1743,13 @@ bool try_launch_dma(hipStream_t s, const AView& A, const BView& B, bool aligned,
     (void)once;
     Problem pb{I, J, R, pl.tiles_i, pl.tiles_j, pl.splits, pl.ktiles_per_split};
     const unsigned grid = (unsigned)((int64_t)pl.tiles_i * pl.tiles_j * pl.splits);
-    if (four) {
+    static const int depth = mpt_env_int("MPT_GEMM_DEPTH", MPT_GEMM_DEPTH_DEFAULT);   // 32: k_gemm_dma4 (tuning only)
+    if (four && depth == 64) {
+      auto k64 = k_gemm_dma64<DmaOperand64<DmaKind<AView>::rc>, DmaOperand64<DmaKind<BView>::rc>>;
+      static bool once64 = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(k64), hipFuncAttributeMaxDynamicSharedMemorySize, 4 * 32768), true);
+      (void)once64;
+      hipLaunchKernelGGL(k64, dim3(grid), dim3(256), 4 * 32768, s, DmaMat{A.base, A.ld}, DmaMat{B.base, B.ld}, pb, ep);
+    } else if (four) {
       hipLaunchKernelGGL(kw4, dim3(grid), dim3(256), 4 * 32768, s, DmaMat{A.base, A.ld}, DmaMat{B.base, B.ld}, pb, ep);
     } else {
       auto k = nstage == 5 ? k5 : k4;
@@ -1557,16 +1929,24 @@ extern "C" size_t mpt_conv3x3_workspace_bytes(int op, int64_t Nb, int64_t H, int
 namespace {
 // Whole-tile convolutions (pixel count a multiple of the tile rows, 256 output channels per tile column, input
 // channels a multiple of 64) take the streamed one-wavefront-per-SIMD kernel with a gathered A operand.
-template <class BOp>
+template <class BOp, class BOp64>
 bool try_launch_conv_dma(hipStream_t s, const uint16_t* img, int64_t H, int64_t W, int64_t Cin, int sgn, const typename BOp::Src& B,
-                         int64_t P, int64_t J, uint16_t* out, int& status) {
+                         const typename BOp64::Src& B64, int64_t P, int64_t J, uint16_t* out, int& status) {
   static const bool enabled = mpt_env_int("MPT_GEMM_STREAMED", 1) != 0 && mpt_env_int("MPT_CONV_STREAMED", 1) != 0;
   if (!enabled || (J % 256) || (Cin % 64) || H >= 65536 || W >= 65536 || P * Cin >= (1LL << 31) || P * J >= (1LL << 31)) return false;
   const int R = (int)(9 * Cin);
   const DmaImgSrc A{img, (int)H, (int)W, (int)Cin, sgn, FastDiv((uint32_t)(H * W)), FastDiv((uint32_t)W), FastDiv((uint32_t)(Cin / 32))};
   Epilogue ep{out, J, 0, nullptr, 0, nullptr, 0};
   const int64_t t256 = (P / 256) * (J / 256), t128 = (P / 128) * (J / 256);
-  if ((P % 256) == 0 && t256 >= kCUs * 3 / 8) {
+  static const int depth = mpt_env_int("MPT_GEMM_DEPTH", MPT_GEMM_DEPTH_DEFAULT);
+  if (depth == 64 && (P % 256) == 0 && t256 >= kCUs * 3 / 8) {
+    auto k = k_gemm_dma64<DmaImgRC64, BOp64>;
+    static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, 4 * 32768), true);
+    (void)once;
+    const DmaImgSrc A64{img, (int)H, (int)W, (int)Cin, sgn, FastDiv((uint32_t)(H * W)), FastDiv((uint32_t)W), FastDiv((uint32_t)(Cin / 64))};
+    Problem pb{(int)P, (int)J, R, (int)(P / 256), (int)(J / 256), 1, R / 64};
+    hipLaunchKernelGGL(k, dim3((unsigned)t256), dim3(256), 4 * 32768, s, A64, B64, pb, ep);
+  } else if ((P % 256) == 0 && t256 >= kCUs * 3 / 8) {
     auto k = k_gemm_dma4<DmaImgRC<256>, BOp, 256>;
     static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, 4 * 32768), true);
     (void)once;
@@ -1595,7 +1975,8 @@ extern "C" int mpt_conv3x3_fwd(void* stream, int64_t Nb, int64_t H, int64_t W, i
   {
     int st = MPT_OK;                 // the workspace, if any, is not needed on this path (its size was not checked: nothing is written to it)
     if (ws == nullptr || ws_bytes >= mpt_conv3x3_workspace_bytes(MPT_OP_FWD, Nb, H, W, C, Kf))
-      if (try_launch_conv_dma<DmaOperand4<true, 256>>(static_cast<hipStream_t>(stream), x, H, W, C, +1, DmaMat{w, 9 * C}, Nb * H * W, Kf, y, st)) return st;
+      if (try_launch_conv_dma<DmaOperand4<true, 256>, DmaOperand64<true>>(static_cast<hipStream_t>(stream), x, H, W, C, +1, DmaMat{w, 9 * C}, DmaMat{w, 9 * C},
+                                                                          Nb * H * W, Kf, y, st)) return st;
   }
   const int P = (int)(Nb * H * W), R = (int)(9 * C);
   ImgRC A{x, (int)H, (int)W, (int)C, P, R, +1, FastDiv((uint32_t)(H * W)), FastDiv((uint32_t)W), FastDiv((uint32_t)C)};
@@ -1612,8 +1993,9 @@ extern "C" int mpt_conv3x3_dgrad(void* stream, int64_t Nb, int64_t H, int64_t W,
   {
     int st = MPT_OK;
     if (ws == nullptr || ws_bytes >= mpt_conv3x3_workspace_bytes(MPT_OP_DGRAD, Nb, H, W, C, Kf))
-      if (try_launch_conv_dma<DmaFilterOC>(static_cast<hipStream_t>(stream), dy, H, W, Kf, -1,
-                                           DmaFilterSrc{w, (int)C, (int)Kf, FastDiv((uint32_t)(Kf / 32))}, Nb * H * W, C, dx, st)) return st;
+      if (try_launch_conv_dma<DmaFilterOC, DmaFilterOC64>(static_cast<hipStream_t>(stream), dy, H, W, Kf, -1,
+                                                          DmaFilterSrc{w, (int)C, (int)Kf, FastDiv((uint32_t)(Kf / 32))},
+                                                          DmaFilterSrc{w, (int)C, (int)Kf, FastDiv((uint32_t)(Kf / 64))}, Nb * H * W, C, dx, st)) return st;
   }
   const int P = (int)(Nb * H * W), R = (int)(9 * Kf);
   ImgRC A{dy, (int)H, (int)W, (int)Kf, P, R, -1, FastDiv((uint32_t)(H * W)), FastDiv((uint32_t)W), FastDiv((uint32_t)Kf)};
