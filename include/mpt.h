@@ -226,6 +226,9 @@ int mpt_master_update_fused(void* stream, size_t n, const float* w32_in_dev, con
 /* ------------------------------------------------------------------------- *
  * Pointwise / reduction glue for a whole step on the device (Sec. 3.3: softmax
  * reduces in FP32 with FP16 input and output; non-linearities are pointwise).
+ *   add_fp16:  out[i] = rne16(a[i] + b[i])                  (exact sum, one rounding; out may alias a or b: where a
+ *              gradient reaches a tensor along two paths, e.g. a recurrent layer's output at step t, used by the
+ *              layer above and by step t+1)
  *   relu_fwd:  h[i]  = max(y[i], 0)
  *   relu_bwd:  dy[i] = y[i] > 0 ? dh[i] : 0
  *   softmax_xent_scaled: p = softmax(logits[b,:]);
@@ -236,6 +239,7 @@ int mpt_master_update_fused(void* stream, size_t n, const float* w32_in_dev, con
  *     labels_dev: int32, each in [0, C) (a value outside is clamped into the range).  C <= 2^24.  Each row is read once and written once when C <= 65536
  *     (16-byte accesses when both tensors are 16-byte aligned with C and the row strides multiples of 8).
  * ------------------------------------------------------------------------- */
+int mpt_add_fp16(void* stream, size_t n, const uint16_t* a_dev, const uint16_t* b_dev, uint16_t* out_dev);
 int mpt_relu_fwd(void* stream, size_t n, const uint16_t* y_dev, uint16_t* h_dev);
 int mpt_relu_bwd(void* stream, size_t n, const uint16_t* dh_dev, const uint16_t* y_dev, uint16_t* dy_dev);
 int mpt_softmax_xent_scaled(void* stream, int64_t B, int64_t C,
@@ -250,7 +254,8 @@ int mpt_softmax_xent_scaled(void* stream, int64_t B, int64_t C,
  * same as in FP32 training).  The paper prints no update rule; the customary
  * ones are used, each a fixed sequence of individually rounded FP32
  * operations, (*) (+) (-) (/) sqrt:
- *     g = float(grad) (*) inv_S        [if weight_decay != 0:  g = g (+) (weight_decay (*) w)]
+ *     g = float(grad) (*) inv_S        [if clip_factor_dev:    g = g (*) *clip_factor_dev]
+ *                                      [if weight_decay != 0:  g = g (+) (weight_decay (*) w)]
  *   MOMENTUM  m' = (mu (*) m) (+) g               w' = w (-) (lr (*) m')
  *   NESTEROV  m' = (mu (*) m) (+) g               w' = w (-) (lr (*) (g (+) (mu (*) m')))
  *   ADAGRAD   h' = h (+) (g (*) g)                w' = w (-) ((lr (*) g) (/) (sqrt(h') (+) eps))
@@ -279,11 +284,35 @@ typedef struct mpt_opt_params {
   float weight_decay;
   float one_minus_beta1, one_minus_beta2;
   float bias_corr1, bias_corr2;
+  const float* clip_factor_dev;  /* NULL, or a device FP32 written by mpt_clip_factor: g = g (*) factor right after unscaling */
 } mpt_opt_params;
 int mpt_optimizer_update(void* stream, size_t n, int kind, const mpt_opt_params* hp_host,
                          float* w32_dev, float* state1_dev, float* state2_dev,
                          const void* grad_dev, int grad_is_fp32, uint16_t* w16_dev,
                          float inv_scale, const mpt_scaler* scaler_dev, const uint32_t* flag_dev);
+
+/* ------------------------------------------------------------------------- *
+ * Gradient clipping by global norm (Sec. 3.2: gradients are unscaled before
+ * the update precisely so that clipping thresholds and weight decay keep
+ * their FP32 values; the paper prints no rule, the customary one is used).
+ *   mpt_grad_sumsq:  sumsq (+)= sum_i ( float(grad[i]) (*) inv_S )^2   each square exact, FP64 sum in an order fixed
+ *                    by n and the alignment alone (same bits every run);  flag |= any Inf/NaN among the stored
+ *                    values (the overflow test of mpt_unscale_check from the same read: 2 B per FP16 element).
+ *                    accumulate = 0 stores, != 0 adds to *sumsq_dev (several buffers, one global norm).
+ *                    sumsq_dev: device double.  ws_dev: device scratch of mpt_grad_norm_workspace_bytes() bytes,
+ *                    8-byte aligned.  inv_scale / scaler_dev as in mpt_master_update.  n = 0 is legal.
+ *   mpt_clip_factor: norm = sqrt(*sumsq_dev) in FP64;  *factor_dev = 1 if norm <= max_norm (or NaN: the step is
+ *                    skipped anyway), else the FP64 quotient max_norm / norm rounded once to FP32;
+ *                    *norm_dev (nullable) = norm rounded to FP32.  max_norm finite, > 0.
+ *   mpt_optimizer_update multiplies the unscaled gradient by *hp->clip_factor_dev (one FP32 multiplication, before
+ *   weight decay) when that pointer is set.  No host synchronisation anywhere.
+ * Errors: NULL, ARG, ALIGN, WORKSPACE.
+ * ------------------------------------------------------------------------- */
+size_t mpt_grad_norm_workspace_bytes(void);
+int mpt_grad_sumsq(void* stream, const void* grad_dev, int grad_is_fp32, size_t n,
+                   float inv_scale, const mpt_scaler* scaler_dev, int accumulate,
+                   double* sumsq_dev, uint32_t* flag_dev, void* ws_dev, size_t ws_bytes);
+int mpt_clip_factor(void* stream, const double* sumsq_dev, float max_norm, float* factor_dev, float* norm_dev);
 
 /* ------------------------------------------------------------------------- *
  * Gradient statistics (Sec. 3.2: exponent histograms of the gradients show

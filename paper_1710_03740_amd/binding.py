@@ -32,7 +32,8 @@ class mpt_scaler(ctypes.Structure):
 
 class mpt_opt_params(ctypes.Structure):
     _fields_ = [("lr", c_f), ("momentum", c_f), ("beta2", c_f), ("eps", c_f), ("weight_decay", c_f),
-                ("one_minus_beta1", c_f), ("one_minus_beta2", c_f), ("bias_corr1", c_f), ("bias_corr2", c_f)]
+                ("one_minus_beta1", c_f), ("one_minus_beta2", c_f), ("bias_corr1", c_f), ("bias_corr2", c_f),
+                ("clip_factor_dev", c_vp)]
 
 
 OPT_KINDS = {"momentum": 0, "nesterov": 1, "adagrad": 2, "adam": 3}
@@ -59,10 +60,14 @@ SIGNATURES = {
     "mpt_master_update": (c_i, [c_vp, c_sz, c_vp, c_vp, c_vp, c_i, c_vp, c_f, c_vp, c_f, c_f, c_vp]),
     "mpt_probe_mfma": (c_i, [c_vp, c_i, c_i, c_vp]),
     "mpt_master_update_fused": (c_i, [c_vp, c_sz, c_vp, c_vp, c_vp, c_i, c_vp, c_vp, c_vp, c_f, c_vp, c_f, c_f, c_vp]),
+    "mpt_add_fp16": (c_i, [c_vp, c_sz, c_vp, c_vp, c_vp]),
     "mpt_relu_fwd": (c_i, [c_vp, c_sz, c_vp, c_vp]),
     "mpt_relu_bwd": (c_i, [c_vp, c_sz, c_vp, c_vp, c_vp]),
     "mpt_softmax_xent_scaled": (c_i, [c_vp, c_i64, c_i64, c_vp, c_i64, c_vp, c_f, c_vp, c_vp, c_vp, c_i64]),
     "mpt_optimizer_update": (c_i, [c_vp, c_sz, c_i, c_vp, c_vp, c_vp, c_vp, c_vp, c_i, c_vp, c_f, c_vp, c_vp]),
+    "mpt_grad_norm_workspace_bytes": (c_sz, []),
+    "mpt_grad_sumsq": (c_i, [c_vp, c_vp, c_i, c_sz, c_f, c_vp, c_i, c_vp, c_vp, c_vp, c_sz]),
+    "mpt_clip_factor": (c_i, [c_vp, c_vp, c_f, c_vp, c_vp]),
     "mpt_grad_stats": (c_i, [c_vp, c_vp, c_sz, c_i, c_vp, c_vp]),
     "mpt_suggest_loss_scale_log2": (c_i, [ctypes.c_uint32, c_i]),
     "mpt_lstm_cell_fwd": (c_i, [c_vp, c_i64, c_i64, c_vp, c_i64, c_vp, c_i64, c_vp, c_vp, c_i64, c_vp, c_i64, c_vp, c_i64, c_vp, c_i64]),
@@ -336,7 +341,7 @@ def mpt_master_update_fused(w32_in, m32_in, grad, w32_out, m32_out, w16_out, inv
 
 
 def mpt_optimizer_update(kind, hp, w32, state1, state2, grad, w16, inv_scale, flag=None, scaler_dev=None):
-    """kind: a key of OPT_KINDS; hp: an mpt_opt_params (host struct)."""
+    """kind: a key of OPT_KINDS; hp: an mpt_opt_params (host struct; its clip_factor_dev is a device address or None)."""
     if kind not in OPT_KINDS:
         raise ValueError("kind: %r, expected one of %s" % (kind, sorted(OPT_KINDS)))
     _update_buffers(w32, [("state1", state1), ("state2", state2)], grad, w16, flag, scaler_dev)
@@ -346,6 +351,30 @@ def mpt_optimizer_update(kind, hp, w32, state1, state2, grad, w16, inv_scale, fl
     _check("mpt_optimizer_update", lib().mpt_optimizer_update(_stream(), w32.numel(), OPT_KINDS[kind], ctypes.byref(hp), _p(w32), _p(state1),
                                                               _p(state2), _p(grad), 1 if grad.dtype == torch.float32 else 0, _p(w16),
                                                               inv_scale, _p(scaler_dev), _p(flag)))
+
+
+def mpt_grad_norm_workspace_bytes():
+    return lib().mpt_grad_norm_workspace_bytes()
+
+
+def mpt_grad_sumsq(grad, inv_scale, sumsq, ws, flag=None, accumulate=False, scaler_dev=None):
+    """sumsq: float64[1] device tensor; ws: device scratch of mpt_grad_norm_workspace_bytes() bytes."""
+    _want("grad", grad, (_F16, _F32)); _flat("grad", grad)
+    _want("sumsq", sumsq, torch.float64, numel=1)
+    _want("flag", flag, _I32, numel=1, optional=True)
+    _want("scaler_dev", scaler_dev, _U8, numel=ctypes.sizeof(mpt_scaler), optional=True)
+    _ws_ok(ws)
+    _dev(grad, sumsq, ws, flag, scaler_dev)
+    p, b = _ws(ws)
+    _check("mpt_grad_sumsq", lib().mpt_grad_sumsq(_stream(), _p(grad), 1 if grad.dtype == torch.float32 else 0, grad.numel(), inv_scale,
+                                                  _p(scaler_dev), 1 if accumulate else 0, _p(sumsq), _p(flag), p, b))
+
+
+def mpt_clip_factor(sumsq, max_norm, factor, norm=None):
+    """factor (and the optional norm): float32[1] device tensors."""
+    _want("sumsq", sumsq, torch.float64, numel=1); _want("factor", factor, _F32, numel=1); _want("norm", norm, _F32, numel=1, optional=True)
+    _dev(sumsq, factor, norm)
+    _check("mpt_clip_factor", lib().mpt_clip_factor(_stream(), _p(sumsq), max_norm, _p(factor), _p(norm)))
 
 
 def mpt_grad_stats(grad, hist, absmax_bits, accumulate=False):
@@ -395,6 +424,13 @@ def mpt_probe_mfma(iters, random_operands, sink):
 
 
 # ---------------------------------------------------------------- glue
+def mpt_add_fp16(a, b, out):
+    _want("a", a, _F16); _flat("a", a)
+    _want("b", b, _F16, numel=a.numel()); _flat("b", b); _want("out", out, _F16, numel=a.numel()); _flat("out", out)
+    _dev(a, b, out)
+    _check("mpt_add_fp16", lib().mpt_add_fp16(_stream(), a.numel(), _p(a), _p(b), _p(out)))
+
+
 def mpt_relu_fwd(y, h):
     _want("y", y, _F16); _flat("y", y); _want("h", h, _F16, numel=y.numel()); _flat("h", h)
     _dev(y, h)

@@ -312,6 +312,28 @@ __global__ __launch_bounds__(kThreads) void k_relu_fwd(size_t n, const uint16_t*
   }
 }
 
+// out = rne16(float(a) + float(b)): the sum of two FP16 values is exact in FP32, so this is one rounding of the exact sum
+__global__ __launch_bounds__(kThreads) void k_add_fp16(size_t n, const uint16_t* __restrict__ a, const uint16_t* __restrict__ b,
+                                                        uint16_t* __restrict__ out, bool vec) {
+  const size_t stride = (size_t)gridDim.x * kThreads;
+  const size_t tid = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  size_t done = 0;
+  if (vec) {
+    const size_t nvec = n >> 3;
+    done = nvec << 3;
+    for (size_t v = tid; v < nvec; v += stride) {
+      const h8 x = reinterpret_cast<const h8*>(a)[v];
+      const h8 y = reinterpret_cast<const h8*>(b)[v];
+      h8 r;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) r[i] = (_Float16)__fadd_rn((float)x[i], (float)y[i]);
+      reinterpret_cast<h8*>(out)[v] = r;
+    }
+  }
+  for (size_t i = done + tid; i < n; i += stride)
+    reinterpret_cast<_Float16*>(out)[i] = (_Float16)__fadd_rn((float)reinterpret_cast<const _Float16*>(a)[i], (float)reinterpret_cast<const _Float16*>(b)[i]);
+}
+
 __global__ __launch_bounds__(kThreads) void k_relu_bwd(size_t n, const uint16_t* __restrict__ dh, const uint16_t* __restrict__ y,
                                                         uint16_t* __restrict__ dy, bool vec) {
   const size_t stride = (size_t)gridDim.x * kThreads;
@@ -662,6 +684,16 @@ extern "C" int mpt_loss_scale_update_dev(void* stream, mpt_scaler* s_dev, uint32
   if (s_dev == nullptr || flag == nullptr) return MPT_ERR_NULL;
   if (!mpt_aligned(s_dev, 4) || !mpt_aligned(flag, 4)) return MPT_ERR_ALIGN;
   hipLaunchKernelGGL(k_scaler_update, dim3(1), dim3(64), 0, static_cast<hipStream_t>(stream), s_dev, flag);
+  MPT_LAUNCH_CHECK();
+  return MPT_OK;
+}
+
+extern "C" int mpt_add_fp16(void* stream, size_t n, const uint16_t* a, const uint16_t* b, uint16_t* out) {
+  if (n == 0) return MPT_OK;
+  if (a == nullptr || b == nullptr || out == nullptr) return MPT_ERR_NULL;
+  if (!mpt_aligned(a, 2) || !mpt_aligned(b, 2) || !mpt_aligned(out, 2)) return MPT_ERR_ALIGN;
+  const bool vec = mpt_aligned(a, 16) && mpt_aligned(b, 16) && mpt_aligned(out, 16);
+  hipLaunchKernelGGL(k_add_fp16, dim3(grid_for(vec ? (n + 7) / 8 : n)), dim3(kThreads), 0, static_cast<hipStream_t>(stream), n, a, b, out, vec);
   MPT_LAUNCH_CHECK();
   return MPT_OK;
 }

@@ -110,3 +110,145 @@ def test_free_running_projected_layer_on_device():
         d = fp16.ulpdist16(fp16.bits(host16(r)), fp16.bits(ref[t]["r"]))
         assert (d <= 2).mean() > 0.9, (t, float((d <= 2).mean()))
     assert np.abs(ref[-1]["r"].astype(np.float64)).max() > 1e-2                                 # the layer is doing something
+
+
+def test_fp16_add_glue():
+    rng = np.random.default_rng(3)
+    for n in (1, 7, 8, 4099):
+        a = (rng.standard_normal(n + 1) * 3).astype(np.float16)
+        b = (np.exp2(rng.uniform(-20, 4, n + 1)) * rng.choice([-1, 1], n + 1)).astype(np.float16)
+        a[0], b[0] = np.float16(65504.0), np.float16(65504.0)                  # overflows to Inf, no saturation
+        for off in (0, 1):
+            want = fp16.rne16(a[off:].astype(np.float64) + b[off:].astype(np.float64))
+            out = _e(n + 1)
+            mpt.mpt_add_fp16(dev16(a)[off:], dev16(b)[off:], out[off:])
+            assert np.array_equal(fp16.bits(host16(out)[off:]), fp16.bits(want))
+    acc = dev16(a)
+    mpt.mpt_add_fp16(acc, dev16(b), acc)                                       # in place
+    assert np.array_equal(fp16.bits(host16(acc)), fp16.bits(fp16.rne16(a.astype(np.float64) + b.astype(np.float64))))
+
+
+def _layer_case(T, B, I, H, P, seed, scale=64.0):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((T, B, I)).astype(np.float16)
+    Wx = (rng.standard_normal((I, 4 * H)) * 0.05).astype(np.float16)
+    Wr = (rng.standard_normal((P, 4 * H)) * 0.05).astype(np.float16)
+    Wp = (rng.standard_normal((H, P)) * 0.03).astype(np.float16)
+    r0 = np.zeros((B, P), np.float16); c0 = np.zeros((B, H), np.float16)
+    dr_ext = (np.exp2(rng.uniform(-16, -6, (T, B, P))) * rng.choice([-1, 1], (T, B, P)) * scale).astype(np.float16)
+    return x, Wx, Wr, Wp, r0, c0, dr_ext
+
+
+def _gemm_close(got16, want16, sabs, s64, label):
+    from gpu_util import gemm_check
+    gemm_check(got16, want16, sabs, s64, label)
+
+
+def test_backward_through_time_teacher_forced():
+    """Every device stage of the backward pass through time is fed the oracle's stored FP16 tensors for that stage
+    (bit-identical) and must reproduce the oracle's output: the FP16 sum of the two gradients of r_t bit for bit, the
+    activation gradients of the projection and of the recurrent product by the GEMM acceptance rule, the cell
+    backward within one FP16 step; then the four time-batched contractions over all steps."""
+    from oracle import gemm
+    T, B, I, H, P = 4, 128, 256, 512, 256
+    x, Wx, Wr, Wp, r0, c0, dr_ext = _layer_case(T, B, I, H, P, 21)
+    fwd = lstm.lstmp_layer_fwd(x, Wx, Wr, Wp, None, r0, c0)
+    ref = lstm.lstmp_layer_bwd(x, Wx, Wr, Wp, r0, c0, fwd, dr_ext)
+    d_Wr, d_Wp, d_Wx = dev16(Wr), dev16(Wp), dev16(Wx)
+    ws = torch.empty(1 << 24, dtype=torch.float32, device="cuda")             # 64 MiB: any split these shapes ask for
+    for t in range(T - 1, -1, -1):
+        print("bptt teacher-forced step", t, flush=True)
+        dr_rec = ref["dr"][t]                                                  # = rne16(dr_ext + what step t+1 sent back)
+        if t < T - 1:
+            rec, sa, s64 = gemm.gemm_dgrad(ref["da"][t + 1], Wr, full=True)
+            d_rec = _e(B, P)
+            mpt.mpt_gemm_dgrad(dev16(ref["da"][t + 1]), d_Wr, d_rec, ws)
+            _gemm_close(host16(d_rec), rec, sa, s64, "dr_rec t=%d" % t)
+            d_sum = _e(B, P)
+            mpt.mpt_add_fp16(dev16(dr_ext[t]), dev16(rec), d_sum)
+            assert np.array_equal(fp16.bits(host16(d_sum)), fp16.bits(dr_rec))
+        dh, sa, s64 = gemm.gemm_dgrad(ref["dr"][t], Wp, full=True)
+        d_dh = _e(B, H)
+        mpt.mpt_gemm_dgrad(dev16(ref["dr"][t]), d_Wp, d_dh, ws)
+        _gemm_close(host16(d_dh), dh, sa, s64, "dh t=%d" % t)
+        c_prev = fwd[t - 1]["c"] if t > 0 else c0
+        dc_next = None if t == T - 1 else lstm.lstm_cell_bwd(ref["dh"][t + 1], _dc_next(ref, fwd, c0, t + 1, T), fwd[t + 1]["act"], fwd[t + 1]["c"], fwd[t]["c"])[1]
+        da, dcp = lstm.lstm_cell_bwd(ref["dh"][t], np.zeros_like(c0) if dc_next is None else dc_next, fwd[t]["act"], fwd[t]["c"], c_prev)
+        assert np.array_equal(fp16.bits(da), fp16.bits(ref["da"][t]))          # the oracle's own chain, re-derived
+        d_da, d_dcp = _e(B, 4 * H), _e(B, H)
+        mpt.mpt_lstm_cell_bwd(dev16(ref["dh"][t]), None if dc_next is None else dev16(dc_next), dev16(fwd[t]["act"]), dev16(fwd[t]["c"]), dev16(c_prev), d_da, d_dcp)
+        gm = np.abs(ref["dh"][t].astype(np.float64)) + (0 if dc_next is None else np.abs(dc_next.astype(np.float64)))
+        _close16(host16(d_da), da, np.concatenate([gm, gm * np.abs(c_prev.astype(np.float64)), gm, gm], axis=1)); _close16(host16(d_dcp), dcp, gm)
+    # the contractions over all steps at once, from the oracle's stored tensors
+    dA, dR = np.concatenate(ref["da"], axis=0), np.concatenate(ref["dr"], axis=0)
+    h_all = np.concatenate([f["h"] for f in fwd], axis=0)
+    r_prev = np.concatenate([r0] + [f["r"] for f in fwd[:-1]], axis=0)
+    d_dA, d_dR = dev16(dA), dev16(dR)
+    out = _e(T * B, I)
+    mpt.mpt_gemm_dgrad(d_dA, d_Wx, out, ws)
+    o, sa, s64 = gemm.gemm_dgrad(dA, Wx, full=True); _gemm_close(host16(out), o, sa, s64, "dx")
+    for name, lhs, rhs, d_rhs, shape in (("dWx", x.reshape(T * B, I), dA, d_dA, (I, 4 * H)), ("dWr", r_prev, dA, d_dA, (P, 4 * H)), ("dWp", h_all, dR, d_dR, (H, P))):
+        out = _e(*shape)
+        mpt.mpt_gemm_wgrad(dev16(lhs), d_rhs, out, ws=ws)
+        o, sa, s64 = gemm.gemm_wgrad(lhs, rhs, full=True)
+        _gemm_close(host16(out), o, sa, s64, name)
+        assert np.array_equal(fp16.bits(o), fp16.bits(ref[name]))
+
+
+def _dc_next(ref, fwd, c0, t, T):
+    """The state gradient arriving at step t from step t+1 in the oracle's chain (zeros at the last step)."""
+    dc = np.zeros_like(c0)
+    for k in range(T - 1, t, -1):
+        dc = lstm.lstm_cell_bwd(ref["dh"][k], dc, fwd[k]["act"], fwd[k]["c"], fwd[k - 1]["c"])[1]
+    return dc
+
+
+def test_backward_through_time_free_running_on_device():
+    """Forward and backward through T steps with no host round trip, composed from the C entry points: per step the
+    FP16 sum of the two gradients of r_t, the projection's activation gradient, the cell backward and the recurrent
+    product's activation gradient; then the four time-batched contractions.  One-step errors feed through the
+    recurrence, so the comparison with the oracle's free-running pass is loose; the stages are checked tightly above."""
+    T, B, I, H, P = 6, 64, 256, 1024, 256
+    x, Wx, Wr, Wp, r0, c0, dr_ext = _layer_case(T, B, I, H, P, 22)
+    fwd = lstm.lstmp_layer_fwd(x, Wx, Wr, Wp, None, r0, c0)
+    ref = lstm.lstmp_layer_bwd(x, Wx, Wr, Wp, r0, c0, fwd, dr_ext)
+    d_x, d_Wx, d_Wr, d_Wp = dev16(x.reshape(T * B, I)), dev16(Wx), dev16(Wr), dev16(Wp)
+    ws = torch.empty(1 << 24, dtype=torch.float32, device="cuda")
+    # forward, keeping what the backward pass needs: act, c, h per step and r_{t-1}
+    gx_all, act_all, c_all, h_all = _e(T * B, 4 * H), _e(T * B, 4 * H), _e(T * B, H), _e(T * B, H)
+    r_prev_all = torch.zeros((T * B, P), dtype=torch.float16, device="cuda")
+    r_last = _e(B, P)
+    gr = _e(B, 4 * H)
+    mpt.mpt_gemm_fwd(d_x, d_Wx, gx_all)
+    c0_d = dev16(c0)
+    sl = lambda buf, t: buf[t * B:(t + 1) * B]
+    for t in range(T):
+        mpt.mpt_gemm_fwd(sl(r_prev_all, t), d_Wr, gr)
+        mpt.mpt_lstm_cell_fwd(sl(gx_all, t), gr, None, c0_d if t == 0 else sl(c_all, t - 1), sl(act_all, t), sl(c_all, t), sl(h_all, t))
+        mpt.mpt_gemm_fwd(sl(h_all, t), d_Wp, sl(r_prev_all, t + 1) if t + 1 < T else r_last, ws)
+    # backward
+    d_ext = dev16(dr_ext.reshape(T * B, P))
+    dR_all, dA_all, dh, dc = _e(T * B, P), _e(T * B, 4 * H), _e(B, H), _e(B, H)
+    dr_rec = _e(B, P)
+    for t in range(T - 1, -1, -1):
+        if t == T - 1:
+            sl(dR_all, t).copy_(sl(d_ext, t))
+        else:
+            mpt.mpt_add_fp16(sl(d_ext, t), dr_rec, sl(dR_all, t))
+        mpt.mpt_gemm_dgrad(sl(dR_all, t), d_Wp, dh, ws)
+        mpt.mpt_lstm_cell_bwd(dh, None if t == T - 1 else dc, sl(act_all, t), sl(c_all, t), c0_d if t == 0 else sl(c_all, t - 1), sl(dA_all, t), dc)
+        mpt.mpt_gemm_dgrad(sl(dA_all, t), d_Wr, dr_rec, ws)
+    dx, dWx, dWr, dWp = _e(T * B, I), _e(I, 4 * H), _e(P, 4 * H), _e(H, P)
+    mpt.mpt_gemm_dgrad(dA_all, d_Wx, dx, ws)
+    mpt.mpt_gemm_wgrad(d_x, dA_all, dWx, ws=ws)
+    mpt.mpt_gemm_wgrad(r_prev_all, dA_all, dWr, ws=ws)
+    mpt.mpt_gemm_wgrad(h_all, dR_all, dWp, ws=ws)
+    torch.cuda.synchronize()
+    for name, got, want in (("dx", dx, ref["dx"].reshape(T * B, I)), ("dWx", dWx, ref["dWx"]), ("dWr", dWr, ref["dWr"]), ("dWp", dWp, ref["dWp"]),
+                            ("dr0", dr_rec, ref["dr0"]), ("dc0", dc, ref["dc0"]), ("dA", dA_all, np.concatenate(ref["da"], axis=0))):
+        g, w = host16(got).astype(np.float64), want.astype(np.float64)
+        assert np.isfinite(g).all(), name
+        err = np.abs(g - w).max() / np.abs(w).max()
+        print("[bptt free-running] %s: max |diff| / max |ref| = %.2e" % (name, err), flush=True)
+        assert err < 1e-2, (name, err)
+        assert np.corrcoef(g.ravel(), w.ravel())[0, 1] > 0.9999, name
