@@ -3,9 +3,12 @@
 
 A "step" is one pass over the whole hot path on the square-GEMM workload
 (M = N = K = 4096): forward, backward-activation and backward-weight GEMMs
-(FP16 in, FP32 accumulate, FP16 store), then on the 16.8M-element weight
-gradient: unscale + Inf/NaN check, FP32 master update with momentum and FP16
-copy, and the device-side loss-scale policy.  Inputs are resident in HBM before
+(FP16 in, FP32 accumulate, FP16 store; the Inf/NaN check of the weight gradient
+rides in the backward-weight GEMM's store), then on the 16.8M-element weight
+gradient: unscaling and FP32 master update with momentum and FP16 copy, skipped
+on overflow, and the device-side loss-scale policy.  Successive steps rotate
+through several buffer sets so that no step finds its operands in the
+memory-side cache from the step before.  Inputs are resident in HBM before
 the timed region.  Prints ONE JSON line.
 
 `value` = FLOPs of the three GEMMs / whole-step time (the update path's time is
@@ -329,6 +332,9 @@ def main():
     ap.add_argument("--operands", choices=("workload", "zeros"), default="workload",
                     help="zeros: run the step on all-zero GEMM operands (diagnostic: the GPU's clock under a GEMM depends on the operand "
                          "bits; on zeros it stays at its maximum, so the difference to the workload's operands is the power limit)")
+    ap.add_argument("--buffer-sets", type=int, default=3,
+                    help="distinct sets of GEMM operands, outputs and master state that the steps rotate through (3 sets = 1 GB: more than the "
+                         "256 MB memory-side cache, so no step finds its operands there from the step before); 1 = everything stays resident")
     ap.add_argument("--no-configs", action="store_true", help="skip the per-pass figures of the other synthetic configurations")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy, so a counter run of this command holds a kernel of known traffic")
@@ -353,39 +359,62 @@ def main():
     def d16(a):
         return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).to(dev).view(torch.float16)
 
-    X, W16, G = d16(c["A"]), d16(c["B"]), d16(c["G"])
-    if args.operands == "zeros":
-        X.zero_(); W16.zero_(); G.zero_()
-    Y = torch.empty((n, n), dtype=torch.float16, device=dev)
-    dX = torch.empty((n, n), dtype=torch.float16, device=dev)
-    dW = torch.empty((n, n), dtype=torch.float16, device=dev)
-    W32 = W16.float()
-    M32 = torch.zeros_like(W32)
+    # Buffer sets: set 0 is the workload as generated; the others hold the same values with the rows rotated (same
+    # distribution, different addresses), so that successive steps touch different memory.
+    nsets = max(1, args.buffer_sets)
+    sets = []
+    for k in range(nsets):
+        sh = (k * 1237) % n
+        Xk, Wk, Gk = (t.roll(sh, 0).contiguous() for t in (d16(c["A"]), d16(c["B"]), d16(c["G"])))
+        if args.operands == "zeros":
+            Xk.zero_(); Wk.zero_(); Gk.zero_()
+        sets.append(dict(X=Xk, W16=Wk, G=Gk, Y=torch.empty((n, n), dtype=torch.float16, device=dev),
+                         dX=torch.empty((n, n), dtype=torch.float16, device=dev), dW=torch.empty((n, n), dtype=torch.float16, device=dev),
+                         W32=Wk.float(), M32=torch.zeros((n, n), dtype=torch.float32, device=dev)))
     flag = torch.zeros(1, dtype=torch.int32, device=dev)
+
+    # numerics of the workload (Sec. 3.2: what FP16 loses without the loss scale) and of the GEMM results, on set 0
+    # before any update touches the weights; the oracle side is computed with the CPU baseline below
+    numerics = None
+    if not args.no_cpu_baseline and args.operands == "workload":
+        s0 = sets[0]
+        mpt.mpt_gemm_fwd(s0["X"], s0["W16"], s0["Y"])
+        mpt.mpt_gemm_dgrad(s0["G"], s0["W16"], s0["dX"])
+        mpt.mpt_gemm_wgrad(s0["X"], s0["G"], s0["dW"])
+        torch.cuda.synchronize()
+        gpu_out = {k: s0[k].cpu().view(torch.int16).numpy().view(np.float16) for k in ("Y", "dX", "dW")}
+        numerics = {}
+        for S in (1.0, 8192.0):
+            q = (c["g_true"] * np.float32(S)).astype(np.float16)
+            numerics["upstream_gradient_S=%g" % S] = {"flushed_to_zero": round(float((q == 0).mean()), 4),
+                                                      "subnormal": round(float(((q != 0) & (np.abs(q) < np.float16(2.0 ** -14))).mean()), 4)}
     scaler = mpt.scaler_to_device(mpt.mpt_scaler_init(8192.0, 1000))
     lr, mu = 1e-3, 0.9
 
     gemm_events = []
 
+    step_no = [0]
+
     def step(record):
         # record = 1: one event pair around the three GEMMs (inside the timed region: the dominant kernel's average launch
         # duration); record = 2: an event after every GEMM (per-pass breakdown, taken after the timed region, since every
         # event costs the queue a few microseconds)
+        b = sets[step_no[0] % nsets]
+        step_no[0] += 1
         if record:
             ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
             ev[0].record()
-        mpt.mpt_gemm_fwd(X, W16, Y)
+        mpt.mpt_gemm_fwd(b["X"], b["W16"], b["Y"])
         if record == 2:
             ev[1].record()
-        mpt.mpt_gemm_dgrad(G, W16, dX)
+        mpt.mpt_gemm_dgrad(b["G"], b["W16"], b["dX"])
         if record == 2:
             ev[2].record()
-        mpt.mpt_gemm_wgrad(X, G, dW)
+        mpt.mpt_gemm_wgrad(b["X"], b["G"], b["dW"], flag=flag)       # the Inf/NaN vote on the stored gradient rides in the epilogue
         if record:
             ev[3].record()
             gemm_events.append(ev)
-        mpt.mpt_unscale_check(dW, 1.0 / 8192.0, flag)
-        mpt.mpt_master_update(W32, M32, dW, W16, 1.0, lr, mu, flag, scaler_dev=scaler)
+        mpt.mpt_master_update(b["W32"], b["M32"], b["dW"], b["W16"], 1.0, lr, mu, flag, scaler_dev=scaler)
         mpt.mpt_loss_scale_update_dev(scaler, flag)
 
     if args.calibrate_copy:
@@ -416,16 +445,32 @@ def main():
     for _ in range(20):                                  # per-pass breakdown, outside the timed region
         step(2)
     torch.cuda.synchronize()
-    per_pass = {k: round(1e3 * sum(ev[i].elapsed_time(ev[i + 1]) for ev in gemm_events[timed_events:]) / 20, 2)
+    n_rot = len(gemm_events)
+    if nsets > 1:                                        # context: the same step with everything left resident (one buffer set)
+        keep = list(sets)
+        del sets[1:]
+        nsets_saved, nsets = nsets, 1
+        for _ in range(10):
+            step(0)
+        for _ in range(30):
+            step(1)
+        torch.cuda.synchronize()
+        resident_us = 1e3 * sum(ev[0].elapsed_time(ev[3]) for ev in gemm_events[n_rot:]) / (3 * 30)
+        sets[:] = keep
+        nsets = nsets_saved
+    else:
+        resident_us = gemm_ms * 1e3
+    per_pass = {k: round(1e3 * sum(ev[i].elapsed_time(ev[i + 1]) for ev in gemm_events[timed_events:timed_events + 20]) / 20, 2)
                 for i, k in enumerate(("fwd", "dgrad", "wgrad"))}
     roofline = {"bound": "mfma", "achieved": round(achieved, 1), "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / MFMA_F16_PEAK_TFLOPS, 4), "traffic": GEMM_TRAFFIC_BYTES,
-                "kernel": "k_gemm_dma4: streamed 256x256 tile, 4 wavefronts x 128x128 of 16x16x32 MFMA blocks, K=32 stages (avg of fwd, dgrad, wgrad)",
+                "kernel": "k_gemm_dma64: streamed 256x256 tile, 4 wavefronts x 128x128 of 16x16x32 MFMA blocks, stages of reduction depth 64 (avg of fwd, dgrad, wgrad)",
+                "buffer_sets": nsets, "avg_launch_us_one_resident_buffer_set": round(resident_us, 2),
                 "avg_launch_us": round(gemm_ms * 1e3, 2),
                 "per_pass_us_with_event_overhead": per_pass}
 
     # the other half of the metric: fused master update on the 116M-parameter flat buffer
-    del X, G, Y, dX, dW, W32, M32
+    sets.clear()
     # one flat allocation carved into master / momentum / gradient / FP16 copy at 2 MiB boundaries, the way a
     # framework lays out a flat parameter buffer (separately cached allocations at odd offsets cost ~4 % here)
     MiB2 = 1 << 21
@@ -510,10 +555,15 @@ def main():
         except Exception:
             cores = os.cpu_count() or 1
         t0 = time.perf_counter()                      # bounded sample: one pass of each of the three GEMMs
-        ogemm.gemm_fwd(c["A"], c["B"])
-        ogemm.gemm_dgrad(c["G"], c["B"])
-        ogemm.gemm_wgrad(c["A"], c["G"])
+        ref = {"Y": ogemm.gemm_fwd(c["A"], c["B"])[0], "dX": ogemm.gemm_dgrad(c["G"], c["B"])[0], "dW": ogemm.gemm_wgrad(c["A"], c["G"])[0]}
         dt = time.perf_counter() - t0
+        if numerics is not None:                      # distance of every GPU result from the oracle's, in FP16 steps
+            from oracle import fp16 as ofp16
+            for k in ("Y", "dX", "dW"):
+                d = ofp16.ulpdist16(ofp16.bits(gpu_out[k]), ofp16.bits(ref[k]))
+                numerics["fp16_steps_from_oracle_" + k] = {"0": round(float((d == 0).mean()), 6), "1": round(float((d == 1).mean()), 6),
+                                                           "2": round(float((d == 2).mean()), 6), ">2": round(float((d > 2).mean()), 6), "max": int(d.max())}
+        del ref
         cpu = {"value": round(flops_step / dt / 1e12, 5), "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
                "sample": "oracle gemm_fwd + gemm_dgrad + gemm_wgrad once each at 4096^3 (each: FP64 matmul, FP64 matmul of magnitudes, "
                          "one FP16 rounding); %.1f s wall" % dt}
@@ -523,12 +573,13 @@ def main():
            "preheat_ms": args.preheat_ms,
            "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "fp16", "data": "synthetic",
-           "config": {"workload": "cfg2: square GEMM M=N=K=4096 fwd+dgrad+wgrad, then unscale/check + momentum master update + scaler on the 16.8M-element weight"
+           "config": {"workload": "cfg2: square GEMM M=N=K=4096 fwd+dgrad+wgrad (Inf/NaN check in the wgrad store), then unscale + momentum master update + scaler on the 16.8M-element weight; %d rotating buffer sets" % nsets
                                   + (" [DIAGNOSTIC: all-zero GEMM operands]" if args.operands == "zeros" else ""),
                       "loss_scale": 8192, "master_update_elements": n * n},
            "pct_of_fp16_peak": round(100 * value / MFMA_F16_PEAK_TFLOPS, 2),
            "master_update_pct_of_hbm_peak": round(100 * upd_gbs / HBM_PEAK_GBS, 2),
-           "roofline": roofline, "mfma_power_ceiling": ceiling, "roofline_update": roofline_update, "roofline_next": next_rows, "roofline_configs": config_rows, "cpu_baseline": cpu}
+           "roofline": roofline, "mfma_power_ceiling": ceiling, "roofline_update": roofline_update, "roofline_next": next_rows, "roofline_configs": config_rows, "numerics": numerics,
+           "cpu_baseline": cpu}
     print(json.dumps(out))
 
 

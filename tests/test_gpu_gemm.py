@@ -388,3 +388,50 @@ def test_mfma_probe_runs_to_completion():
             mpt.mpt_probe_mfma(1000, rnd, sink)
         torch.cuda.synchronize()
     assert float(sink.item()) == 0.0
+
+
+def test_accumulation_inside_the_matrix_instruction():
+    """The evidence for the acceptance rule's allowance (C_ACC in gpu_util): how the FP16 matrix instruction adds.
+    Through mpt_gemm_wgrad with an FP32 store (no FP16 rounding in the way), one product of 1 is summed with sixteen
+    equal small products placed in the same instruction or in the next one.  Round-to-nearest FP32 additions of the
+    exact products would return the exact sum in every case below (all sums are FP32 numbers).  The hardware aligns
+    the addends of an instruction to the largest of them and keeps only a few bits below that value's FP32 step, so
+    small addends are partly or wholly lost: the test prints the stored sums, asserts that each lies within the
+    allowance C_ACC * 2^-24 * sum|a*b| of the exact one (the rule holds on these adversarial inputs), and that the
+    worst case is off by more than 2^-24 * sum|a*b| (so an allowance of one FP32 rounding per result would reject
+    correct hardware results).  The large output takes the streamed kernel (instructions of depth 32), the small one
+    the general kernel (depth 16)."""
+    from gpu_util import C_ACC
+    worst = 0.0
+    for K, N in ((4096, 2048), (256, 256)):
+        M = 64
+        for small in (-12, -13, -14, -15):                   # products 2^-25 .. 2^-28 next to a product of 1
+            for where in (0, 32):                            # small products in the same instruction as the 1, or in the next one
+                X = np.zeros((M, K), dtype=np.float16)
+                dY = np.zeros((M, N), dtype=np.float16)
+                X[0, :] = 1.0
+                dY[0, :] = 1.0
+                X[where + 1:where + 17, :] = 2.0 ** -13
+                dY[where + 1:where + 17, :] = 2.0 ** small
+                out = torch.empty((K, N), dtype=torch.float32, device="cuda")
+                mpt.mpt_gemm_wgrad(dev16(X), dev16(dY), out)
+                got = out.cpu().numpy().astype(np.float64)
+                exact = 1.0 + 16 * 2.0 ** (small - 13)          # also sum|a*b|
+                assert (got == got[0, 0]).all()                  # every output element sees the same sum
+                err = abs(got[0, 0] - exact) / (2.0 ** -24 * exact)
+                worst = max(worst, err)
+                print("[mfma accumulation] %dx%d: 1 + 16 * 2^%d, small products in instruction %d: exact 1 + %g * 2^-24, stored 1 + %g * 2^-24, off by %.2f * 2^-24 * sum|a*b|"
+                      % (K, N, small - 13, where // 32, 16 * 2.0 ** (small - 13 + 24), (got[0, 0] - 1.0) * 2.0 ** 24, err), flush=True)
+                assert err <= C_ACC, (K, N, small, where, got[0, 0], exact)
+    print("[mfma accumulation] worst case: %.2f * 2^-24 * sum|a*b| (allowance: %g)" % (worst, C_ACC), flush=True)
+    assert worst > 1.0
+    # a large accumulator swallows addends below a few bits under its FP32 step: 2^24 + 16 * 0.125 stays 2^24
+    M, K, N = 64, 256, 256
+    X = np.zeros((M, K), dtype=np.float16); dY = np.zeros((M, N), dtype=np.float16)
+    X[0, :] = 4096.0; dY[0, :] = 4096.0                      # 2^24
+    X[1:17, :] = 0.125; dY[1:17, :] = 1.0
+    out = torch.empty((K, N), dtype=torch.float32, device="cuda")
+    mpt.mpt_gemm_wgrad(dev16(X), dev16(dY), out)
+    got = float(out.cpu().numpy()[0, 0])
+    print("[mfma accumulation] 2^24 + 16 * 0.125: stored 2^24 + %g" % (got - 2.0 ** 24), flush=True)
+    assert abs(got - (2.0 ** 24 + 2.0)) <= C_ACC * 2.0 ** -24 * (2.0 ** 24 + 2.0)
