@@ -113,6 +113,23 @@ int mpt_gemm_wgrad(void* stream, int64_t M, int64_t N, int64_t K,
                    int out_fp32, int accumulate, uint32_t* flag_dev,
                    void* ws_dev, size_t ws_bytes);
 
+/* mpt_gemm_wgrad for callers that cannot allocate device memory: code under HIP graph capture, tight serving or
+ * training loops, harnesses that forbid hipMalloc.  Same arguments, results (bit for bit) and errors as
+ * mpt_gemm_wgrad, without the workspace: the FP32 split partials go to a device array of MPT_STATIC_SCRATCH_BYTES
+ * that is part of the library's code object (one copy per GPU, held until the process ends).  The call allocates
+ * and frees nothing; its first use on a device looks the array's address up (hipGetSymbolAddress), so make one call
+ * per device before capturing a graph.  A shape whose split needs more than the array
+ * (mpt_gemm_workspace_bytes(MPT_OP_WGRAD, M, N, K) > MPT_STATIC_SCRATCH_BYTES) is refused with MPT_ERR_WORKSPACE and
+ * nothing is launched.  Every call on one GPU shares that GPU's array: calls that may overlap in time on one GPU
+ * (different streams) race and must not be made; calls on one stream are ordered and safe.  Partials are written
+ * before they are read, so the array needs no clearing between calls. */
+#define MPT_STATIC_SCRATCH_BYTES (32u << 20)
+int mpt_gemm_wgrad_static(void* stream, int64_t M, int64_t N, int64_t K,
+                          const uint16_t* X_dev, int64_t ldx,
+                          const uint16_t* dY_dev, int64_t ldy,
+                          void* dW_dev, int64_t lddw,
+                          int out_fp32, int accumulate, uint32_t* flag_dev);
+
 /* ------------------------------------------------------------------------- *
  * 3x3 convolution, stride 1, zero padding 1, as an implicit GEMM (Sec. 3.3 and
  * Sec. 4 list convolutions among the FP32-accumulated dot products).

@@ -49,6 +49,7 @@ SIGNATURES = {
     "mpt_gemm_fwd_relu": (c_i, _GEMM),
     "mpt_gemm_dgrad_relu": (c_i, [c_vp, c_i64, c_i64, c_i64, c_vp, c_i64, c_vp, c_i64, c_vp, c_i64, c_vp, c_i64, c_vp, c_sz]),
     "mpt_gemm_wgrad": (c_i, [c_vp, c_i64, c_i64, c_i64, c_vp, c_i64, c_vp, c_i64, c_vp, c_i64, c_i, c_i, c_vp, c_vp, c_sz]),
+    "mpt_gemm_wgrad_static": (c_i, [c_vp, c_i64, c_i64, c_i64, c_vp, c_i64, c_vp, c_i64, c_vp, c_i64, c_i, c_i, c_vp]),
     "mpt_conv3x3_workspace_bytes": (c_sz, [c_i, c_i64, c_i64, c_i64, c_i64, c_i64]),
     "mpt_conv3x3_fwd": (c_i, _CONV),
     "mpt_conv3x3_dgrad": (c_i, _CONV),
@@ -254,6 +255,23 @@ def mpt_gemm_wgrad(X, dY, dW, accumulate=False, flag=None, ws=None):
     p, b = _ws(ws)
     _check("mpt_gemm_wgrad", lib().mpt_gemm_wgrad(_stream(), M, N, K, _p(X), X.stride(0), _p(dY), dY.stride(0), _p(dW), dW.stride(0),
                                                   out_fp32, 1 if accumulate else 0, _p(flag), p, b))
+
+
+STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def mpt_gemm_wgrad_static(X, dY, dW, accumulate=False, flag=None):
+    """mpt_gemm_wgrad with the split partials in the library's own device array (no allocation, no workspace)."""
+    M, K = _dim2("X", X)
+    N = _dim2("dY", dY)[1]
+    _mat("X", X, _F16, (M, K)); _mat("dY", dY, _F16, (M, N)); _mat("dW", dW, (_F16, _F32), (K, N))
+    _want("flag", flag, _I32, numel=1, optional=True)
+    out_fp32 = 1 if dW.dtype == torch.float32 else 0
+    if accumulate and not out_fp32:
+        raise ValueError("dW: accumulate needs an FP32 output")
+    _dev(X, dY, dW, flag)
+    _check("mpt_gemm_wgrad_static", lib().mpt_gemm_wgrad_static(_stream(), M, N, K, _p(X), X.stride(0), _p(dY), dY.stride(0), _p(dW), dW.stride(0),
+                                                                out_fp32, 1 if accumulate else 0, _p(flag)))
 
 
 # ---------------------------------------------------------------- conv

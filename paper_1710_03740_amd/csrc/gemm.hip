@@ -24,6 +24,7 @@
 // LDS is double buffered: global loads for tile t+1 are issued before the MFMAs
 // of tile t and written to the other buffer after them; one barrier per tile.
 #include "mpt_internal.h"
+#include <mutex>
 #include <type_traits>
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
@@ -1899,6 +1900,46 @@ extern "C" int mpt_gemm_wgrad(void* stream, int64_t M, int64_t N, int64_t K, con
   MatOC B{dY, ldy, (int)N, (int)M};
   Epilogue ep{dW, lddw, out_fp32 ? (accumulate ? 2 : 1) : 0, flag, 0, nullptr, 0};
   return run(static_cast<hipStream_t>(stream), A, B, mat_fast(X, ldx, K), mat_fast(dY, ldy, N), (int)K, (int)N, (int)M, ep, ws, ws_bytes);
+}
+
+// ---------------------------------------------------------------- weight gradient for callers that cannot allocate
+// The split partials of mpt_gemm_wgrad normally live in a workspace the caller allocates.  This array stands in for
+// it: device memory that exists from the moment the code object is loaded, one copy per GPU, kept until the process
+// ends.  In host code the array's name is not a device address; the address is looked up once per device with
+// hipGetSymbolAddress and only that pointer is handed to kernels.
+static __device__ __align__(256) unsigned char scratch[MPT_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices];            // per device; written once under the mutex
+std::mutex g_scratch_mutex;
+
+int static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MPT_ERR_HIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return MPT_ERR_HIP;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return MPT_OK;
+}
+}  // namespace
+
+extern "C" int mpt_gemm_wgrad_static(void* stream, int64_t M, int64_t N, int64_t K, const uint16_t* X, int64_t ldx,
+                                     const uint16_t* dY, int64_t ldy, void* dW, int64_t lddw, int out_fp32, int accumulate,
+                                     uint32_t* flag) {
+  if (X == nullptr || dY == nullptr || dW == nullptr) return MPT_ERR_NULL;
+  if (!dims_ok(M, N, K) || ldx < K || ldy < N || lddw < N) return MPT_ERR_SHAPE;
+  if (accumulate && !out_fp32) return MPT_ERR_ARG;
+  // the split this shape would use must fit the array; nothing is launched otherwise
+  if (mpt_gemm_workspace_bytes(MPT_OP_WGRAD, M, N, K) > (size_t)MPT_STATIC_SCRATCH_BYTES) return MPT_ERR_WORKSPACE;
+  void* ws = nullptr;
+  const int st = static_scratch(&ws);
+  if (st != MPT_OK) return st;
+  return mpt_gemm_wgrad(stream, M, N, K, X, ldx, dY, ldy, dW, lddw, out_fp32, accumulate, flag, ws, (size_t)MPT_STATIC_SCRATCH_BYTES);
 }
 
 // ---------------------------------------------------------------- C ABI: 3x3 convolution

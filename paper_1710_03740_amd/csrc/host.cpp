@@ -9,7 +9,7 @@ extern "C" const char* mpt_status_string(int status) {
     case MPT_ERR_NULL: return "required pointer is NULL";
     case MPT_ERR_SHAPE: return "bad size or leading dimension";
     case MPT_ERR_ALIGN: return "pointer not aligned to its element type";
-    case MPT_ERR_WORKSPACE: return "workspace too small";
+    case MPT_ERR_WORKSPACE: return "workspace too small (or: split partials exceed the library's static scratch array)";
     case MPT_ERR_ARG: return "scalar argument out of range";
     case MPT_ERR_HIP: return "HIP launch failed";
     default: return "unknown status";
