@@ -142,6 +142,13 @@ def measure_next(torch, mpt, np, dev, with_cpu):
     t = timeit(lambda: mpt.mpt_grad_stats(g, hist, am))
     row("grad_stats (k_grad_stats)", "%d FP16 gradients -> 42-bin exponent histogram + max magnitude" % nf, 2 * nf, t,
         cpu_time(lambda: (ostats.exponent_histogram(gs_), ostats.absmax(gs_)), 2 * ns, "first %d elements" % ns))
+    from oracle import clip as oclip
+    ssq = torch.zeros(1, dtype=torch.float64, device=dev)
+    fl_ = torch.zeros(1, dtype=torch.int32, device=dev)
+    wsn = torch.empty(mpt.mpt_grad_norm_workspace_bytes(), dtype=torch.uint8, device=dev)
+    t = timeit(lambda: mpt.mpt_grad_sumsq(g, 2.0 ** -16, ssq, wsn, flag=fl_))
+    row("grad_sumsq (k_grad_sumsq: sum of squares of the unscaled gradient for clipping + Inf/NaN vote, one read)", "%d FP16 gradients, 2 B/element" % nf, 2 * nf, t,
+        cpu_time(lambda: oclip.unscaled_sumsq(gs_, 2.0 ** -16), 2 * ns, "first %d elements" % ns))
     del pool, w, a, b, g, h
     # ---- LSTM cell (pointwise part) at the time-batched language-model shape: 5120 rows x 8192 cells
     from oracle import lstm as olstm
@@ -183,6 +190,39 @@ def measure_next(torch, mpt, np, dev, with_cpu):
     rows.append({"kernel": "free-running LSTM layer forward (time-batched input GEMM + per step: recurrent GEMM, cell, projection GEMM)",
                  "workload": "T=20, batch 256, 1024 -> 8192 cells -> 1024", "bound": "mfma", "achieved": round(fl / t / 1e12, 1),
                  "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(fl / t / 1e12 / MFMA_F16_PEAK_TFLOPS, 4),
+                 "avg_launch_us": round(t * 1e6, 1), "us_per_step": round(t * 1e6 / T, 1), "cpu_oracle": None})
+    # ---- the same layer's backward pass through time: per step the FP16 sum of the two gradients of r_t, the projection's
+    # activation gradient, the cell backward, the recurrent product's activation gradient; then the time-batched
+    # input gradient and the three weight gradients (reduction length T * batch), all from stored FP16 tensors
+    act_all = torch.randn(T * B2, 4 * H2, device=dev).mul_(0.3).half()          # stand-ins for what the forward pass stored
+    c_all = torch.randn(T * B2, H2, device=dev).half(); h_all = torch.randn(T * B2, H2, device=dev).mul_(0.5).half()
+    rp_all = torch.randn(T * B2, R2, device=dev).mul_(0.5).half()
+    dext = (torch.randn(T * B2, R2, device=dev) * 2.0 ** -8).half()
+    dR, dA = torch.empty_like(dext), torch.empty(T * B2, 4 * H2, device=dev, dtype=torch.float16)
+    dhb, dcb, drec = torch.empty(B2, H2, device=dev, dtype=torch.float16), torch.empty(B2, H2, device=dev, dtype=torch.float16), torch.zeros(B2, R2, device=dev, dtype=torch.float16)
+    dxo = torch.empty(T * B2, I, device=dev, dtype=torch.float16)
+    dWx, dWr, dWp = torch.empty_like(Wx), torch.empty_like(Wr), torch.empty_like(Wp)
+    need = max(mpt.mpt_gemm_workspace_bytes(1, B2, R2, H2), mpt.mpt_gemm_workspace_bytes(1, B2, 4 * H2, R2), mpt.mpt_gemm_workspace_bytes(1, T * B2, 4 * H2, I),
+               mpt.mpt_gemm_workspace_bytes(2, T * B2, 4 * H2, I), mpt.mpt_gemm_workspace_bytes(2, T * B2, 4 * H2, R2), mpt.mpt_gemm_workspace_bytes(2, T * B2, R2, H2), 16)
+    wsb = torch.empty(need // 4 + 4, dtype=torch.float32, device=dev)
+    sl = lambda buf, ts: buf[ts * B2:(ts + 1) * B2]
+
+    def layer_bwd():
+        for ts in range(T - 1, -1, -1):
+            mpt.mpt_add_fp16(sl(dext, ts), drec, sl(dR, ts))
+            mpt.mpt_gemm_dgrad(sl(dR, ts), Wp, dhb, wsb)
+            mpt.mpt_lstm_cell_bwd(dhb, None if ts == T - 1 else dcb, sl(act_all, ts), sl(c_all, ts), sl(c_all, max(ts - 1, 0)), sl(dA, ts), dcb)
+            mpt.mpt_gemm_dgrad(sl(dA, ts), Wr, drec, wsb)
+        mpt.mpt_gemm_dgrad(dA, Wx, dxo, wsb)
+        mpt.mpt_gemm_wgrad(x, dA, dWx, ws=wsb)
+        mpt.mpt_gemm_wgrad(rp_all, dA, dWr, ws=wsb)
+        mpt.mpt_gemm_wgrad(h_all, dR, dWp, ws=wsb)
+    t = timeit(layer_bwd, reps=5, warm=2)
+    flb = 2.0 * T * B2 * (2 * I * 4 * H2 + 2 * R2 * 4 * H2 + 2 * H2 * R2)
+    rows.append({"kernel": "projected-LSTM layer, backward pass through time (per step: FP16 add, projection dgrad, cell backward, recurrent dgrad; then "
+                           "time-batched input dgrad and three wgrads)",
+                 "workload": "T=20, batch 256, 1024 -> 8192 cells -> 1024", "bound": "mfma", "achieved": round(flb / t / 1e12, 1),
+                 "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(flb / t / 1e12 / MFMA_F16_PEAK_TFLOPS, 4),
                  "avg_launch_us": round(t * 1e6, 1), "us_per_step": round(t * 1e6 / T, 1), "cpu_oracle": None})
     return rows
 

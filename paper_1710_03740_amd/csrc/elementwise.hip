@@ -14,10 +14,12 @@ typedef _Float16 h4 __attribute__((ext_vector_type(4)));
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u4 __attribute__((ext_vector_type(4)));
 
+#ifdef MPT_TUNING
 int mpt_env_int(const char* name, int dflt) {
   const char* v = getenv(name);
   return v && *v ? atoi(v) : dflt;
 }
+#endif
 
 namespace {
 
@@ -357,6 +359,7 @@ __global__ __launch_bounds__(kThreads) void k_relu_bwd(size_t n, const uint16_t*
   }
 }
 
+typedef _Float16 sm_h2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
@@ -399,8 +402,10 @@ __global__ __launch_bounds__((WAVES * 64 > kThreads ? WAVES * 64 : kThreads)) vo
       for (int e = 0; e < 8; ++e)
         if (live && c0 + e < C) q[i][e] = z[c0 + e];
     }
-#pragma unroll
-    for (int e = 0; e < 8; ++e) mx = fmaxf(mx, (float)q[i][e]);
+    // row maximum on packed pairs (one instruction per two elements), widened once per chunk
+    sm_h2 m2 = __builtin_elementwise_max(sm_h2{q[i][0], q[i][1]}, sm_h2{q[i][2], q[i][3]});
+    m2 = __builtin_elementwise_max(m2, __builtin_elementwise_max(sm_h2{q[i][4], q[i][5]}, sm_h2{q[i][6], q[i][7]}));
+    mx = fmaxf(mx, fmaxf((float)m2[0], (float)m2[1]));
   }
   auto across = [&](float x, bool is_max) {                // over the row's wavefronts, fixed order
     x = is_max ? wave_max(x) : wave_sum(x);
@@ -417,9 +422,13 @@ __global__ __launch_bounds__((WAVES * 64 > kThreads ? WAVES * 64 : kThreads)) vo
   };
   mx = across(mx, true);
   constexpr float kLog2e = 1.44269504088896340736f;
-  auto ex = [&](_Float16 h) { return __builtin_amdgcn_exp2f(__fmul_rn(__fsub_rn((float)h, mx), kLog2e)); };   // exp(-inf) = 0 for the padding
+  // exp(z - max) = 2^(z * log2(e) - max * log2(e)), one fused multiply-add (rounded once, so at least as accurate as
+  // the two-operation form); exp(-inf) = 0 for the padding
+  const float nmx = -__fmul_rn(mx, kLog2e);
+  auto ex = [&](_Float16 h) { return __builtin_amdgcn_exp2f(__builtin_fmaf((float)h, kLog2e, nmx)); };
   // With few chunks per lane the exponentials are kept in registers for the output pass (the kernel is close to
-  // ALU-bound: two evaluations per element cost a quarter of its instructions); with many they are recomputed.
+  // ALU-bound, so the instruction count per element is kept down: packed maximum, fused exponent argument, one
+  // multiplication per stored value, the label's element handled apart); with many they are recomputed.
   constexpr bool KEEP = NCH <= 4;
   float ev[KEEP ? NCH : 1][8];
   float sum = 0.f;
@@ -435,6 +444,7 @@ __global__ __launch_bounds__((WAVES * 64 > kThreads ? WAVES * 64 : kThreads)) vo
   if (!live) return;
   const int32_t lab = min(max(labels[row], 0), (int32_t)(C - 1));      // a label outside [0, C) is the caller's error; it must not become a wild read
   const float inv = div_rn(1.0f, sum);
+  const float scale_all = __fmul_rn(inv, factor);                        // every element but the label's: p * factor in one multiplication
   _Float16* d = reinterpret_cast<_Float16*>(dlogits) + row * ldd;
 #pragma unroll
   for (int i = 0; i < NCH; ++i) {
@@ -445,8 +455,17 @@ __global__ __launch_bounds__((WAVES * 64 > kThreads ? WAVES * 64 : kThreads)) vo
       float x;
       if constexpr (KEEP) x = ev[i][e];
       else x = ex(q[i][e]);
-      const float p = __fmul_rn(x, inv);
-      o[e] = (_Float16)__fmul_rn(__fsub_rn(p, (c0 + e == lab) ? 1.0f : 0.0f), factor);
+      o[e] = (_Float16)__fmul_rn(x, scale_all);
+    }
+    if (lab >= c0 && lab < c0 + 8) {                                     // one chunk of the row holds the label: (p - 1) * factor there
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        if (c0 + e == lab) {
+          float x;
+          if constexpr (KEEP) x = ev[i][e];
+          else x = ex(q[i][e]);
+          o[e] = (_Float16)__fmul_rn(__fsub_rn(__fmul_rn(x, inv), 1.0f), factor);
+        }
     }
     if constexpr (VEC) {
       if (c0 < C) {
@@ -551,7 +570,7 @@ __global__ __launch_bounds__(kThreads) void k_loss_mean(int64_t B, const float* 
 
 // Grid size for a streaming pass over `units` thread-trips.
 unsigned grid_for(size_t units) {
-  static const int per_cu = mpt_env_int("MPT_EW_BLOCKS_PER_CU", 0);   // 0: one trip per thread
+  static const int per_cu = MPT_TUNABLE("MPT_EW_BLOCKS_PER_CU", 0);   // 0: one trip per thread
   size_t blocks = (units + kThreads - 1) / kThreads;
   if (blocks < 1) blocks = 1;
   if (per_cu > 0) {
@@ -604,13 +623,16 @@ extern "C" int mpt_master_update(void* stream, size_t n, float* w32, float* m32,
     return MPT_ERR_ALIGN;
   const bool vec = mpt_aligned(w32, 8) && (m32 == nullptr || mpt_aligned(m32, 8)) && mpt_aligned(grad, grad_is_fp32 ? 8 : 4) &&
                    mpt_aligned(w16, 4);
-  static const bool nt = mpt_env_int("MPT_EW_NONTEMPORAL", 1) != 0;
+  static const bool nt = MPT_TUNABLE("MPT_EW_NONTEMPORAL", 1) != 0;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const bool mom = m32 != nullptr;
   const bool g32 = grad_is_fp32 != 0;
   if (vec) {
-    static const int bs = mpt_env_int("MPT_EW_BLOCK", 256);             // 64 or 256 (tuning only)
     const size_t quads = (n + 1) / 2;    // thread-trips: one pair each
+#define MPT_MU256(M, G, T)                                                                                                \
+  hipLaunchKernelGGL((k_master_update<M, G, T, 256>), dim3(grid_for(quads)), dim3(256), 0, s, n, w32, m32, grad, w16, inv_scale, scaler, lr, momentum, flag)
+#ifdef MPT_TUNING
+    static const int bs = MPT_TUNABLE("MPT_EW_BLOCK", 256);             // 64 or 256
 #define MPT_MU(M, G, T)                                                                                                   \
   do {                                                                                                                    \
     if (bs == 64) {                                                                                                       \
@@ -618,8 +640,7 @@ extern "C" int mpt_master_update(void* stream, size_t n, float* w32, float* m32,
       hipLaunchKernelGGL((k_master_update<M, G, T, 64>), dim3((unsigned)(blocks > 0x7FFFFFFFu ? 0x7FFFFFFFu : blocks)), dim3(64), 0, s, n, w32, m32, \
                          grad, w16, inv_scale, scaler, lr, momentum, flag);                                                 \
     } else {                                                                                                              \
-      hipLaunchKernelGGL((k_master_update<M, G, T, 256>), dim3(grid_for(quads)), dim3(256), 0, s, n, w32, m32, grad, w16,   \
-                         inv_scale, scaler, lr, momentum, flag);                                                            \
+      MPT_MU256(M, G, T);                                                                                                 \
     }                                                                                                                     \
   } while (0)
     const int sel = (mom ? 4 : 0) | (g32 ? 2 : 0) | (nt ? 1 : 0);
@@ -634,6 +655,12 @@ extern "C" int mpt_master_update(void* stream, size_t n, float* w32, float* m32,
       default: MPT_MU(true, true, true); break;
     }
 #undef MPT_MU
+#else
+    (void)nt;                            // nontemporal accesses, 256-thread workgroups
+    if (mom) { if (g32) MPT_MU256(true, true, true); else MPT_MU256(true, false, true); }
+    else     { if (g32) MPT_MU256(false, true, true); else MPT_MU256(false, false, true); }
+#endif
+#undef MPT_MU256
   } else {
     const unsigned grid = grid_for(n);
 #define MPT_MS(M, G) hipLaunchKernelGGL((k_master_update_scalar<M, G>), dim3(grid), dim3(kThreads), 0, s, n, w32, m32, grad, w16, inv_scale, scaler, lr, momentum, flag)

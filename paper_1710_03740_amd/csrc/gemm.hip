@@ -280,6 +280,14 @@ __device__ __forceinline__ void tile_of(const Problem& pb, int wg, int& ti, int&
 }
 
 __device__ __forceinline__ bool half_bits_special(uint32_t b) { return (b & 0x7C00u) == 0x7C00u; }
+// Inf/NaN vote over many packed FP16 pairs at two instructions per pair: keep the running maximum of the exponent fields
+// of the low and of the high halves (v_pk_max_u16); a field of all ones anywhere shows in the maximum at the end.
+typedef unsigned short ushort2v __attribute__((ext_vector_type(2)));
+struct ExpMax {
+  ushort2v m = {0, 0};
+  __device__ __forceinline__ void add(uint32_t pair) { m = __builtin_elementwise_max(m, __builtin_bit_cast(ushort2v, pair & 0x7C007C00u)); }
+  __device__ __forceinline__ bool special() const { return m[0] == 0x7C00 || m[1] == 0x7C00; }
+};
 
 template <class AView, class BView, bool A_ALIGNED, bool B_ALIGNED, int BM, int BN, int WM, int WN>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void k_gemm(AView A, BView B, Problem pb, Epilogue ep) {
@@ -1216,6 +1224,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         *reinterpret_cast<half4*>(mine + (a * 16 + li) * 256 + (((2 * b + (lg >> 1)) ^ li) << 4) + (lg & 1) * 8) = h;
       }
     uint16_t* out = reinterpret_cast<uint16_t*>(ep.out) + (int64_t)(i0 + wm * (BM / 2)) * ep.ld + j0 + wn * 128 + li * 8;
+    ExpMax emax;
 #pragma unroll 8
     for (int it = 0; it < BM / 8; ++it) {
       const int r = it * 4 + lg;
@@ -1232,10 +1241,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       }
       if (ep.flag) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) bad |= half_bits_special(q[e]) | half_bits_special(q[e] >> 16);
+        for (int e = 0; e < 4; ++e) emax.add(q[e]);
       }
       *reinterpret_cast<uint4v*>(out + (int64_t)r * ep.ld) = q;
     }
+    bad = emax.special();
   }
   if (ep.flag != nullptr && !(F32OUT && ep.mode == 3)) {
     const unsigned long long vote = __builtin_amdgcn_ballot_w64(bad);
@@ -1579,6 +1589,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       *reinterpret_cast<half4*>(mine + (a * 16 + li) * 256 + (((2 * b + (lg >> 1)) ^ li) << 4) + (lg & 1) * 8) = h;
     }
   uint16_t* out = reinterpret_cast<uint16_t*>(ep.out) + (int64_t)(i0 + wm * (BM / 2)) * ep.ld + j0 + wn * 128 + li * 8;
+  ExpMax emax;
 #pragma unroll 8
   for (int it = 0; it < BM / 8; ++it) {
     const int r = it * 4 + lg;
@@ -1595,10 +1606,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     }
     if (ep.flag) {
 #pragma unroll
-      for (int e = 0; e < 4; ++e) bad |= half_bits_special(q[e]) | half_bits_special(q[e] >> 16);
+      for (int e = 0; e < 4; ++e) emax.add(q[e]);
     }
     *reinterpret_cast<uint4v*>(out + (int64_t)r * ep.ld) = q;
   }
+  bad = emax.special();
   if (ep.flag != nullptr) {
     const unsigned long long vote = __builtin_amdgcn_ballot_w64(bad);
     if (vote != 0ull && lane == 0) atomicOr(ep.flag, 1u);
@@ -1653,8 +1665,8 @@ struct Plan {
 constexpr int kCUs = 256;
 
 Plan make_plan(int64_t I, int64_t J, int64_t R, bool allow_split) {
-  static const int force_tile = mpt_env_int("MPT_GEMM_TILE", 0);      // 128 / 256 force a tile size (tuning only)
-  static const int force_split = mpt_env_int("MPT_GEMM_SPLITS", 0);   // >0 forces a split count (tuning only)
+  static const int force_tile = MPT_TUNABLE("MPT_GEMM_TILE", 0);      // 128 / 256 force a tile size (tuning builds only)
+  static const int force_split = MPT_TUNABLE("MPT_GEMM_SPLITS", 0);   // >0 forces a split count (tuning builds only)
   Plan p;
   const int64_t t256 = ((I + 255) / 256) * ((J + 255) / 256);
   p.big = t256 >= kCUs / 2;
@@ -1726,36 +1738,42 @@ template <> struct DmaKind<MatOC> { static constexpr bool ok = true; static cons
 template <class AView, class BView>
 bool try_launch_dma(hipStream_t s, const AView& A, const BView& B, bool aligned, const Plan& pl, int I, int J, int R, const Epilogue& ep, int& status) {
   if constexpr (DmaKind<AView>::ok && DmaKind<BView>::ok) {
-    static const bool enabled = mpt_env_int("MPT_GEMM_STREAMED", 1) != 0;
+    static const bool enabled = MPT_TUNABLE("MPT_GEMM_STREAMED", 1) != 0;
     if (!enabled || !aligned || !pl.big || (I % 256) || (J % 256) || (R % 64)) return false;
     if (ep.mode != 0 && ((ep.ld % 4) || !mpt_aligned(ep.out, 16))) return false;      // FP32 outputs go out 16 bytes per lane
     // FP16 stores of unsplit problems into 16-byte aligned rows take the one-wavefront-per-SIMD kernel (same speed at one
     // tile per CU, about 5 % faster over several); split partials and odd output strides take k_gemm_dma.
-    static const int nwaves = mpt_env_int("MPT_GEMM_WAVES", 4);           // 8 forces k_gemm_dma (tuning only)
+    static const int nwaves = MPT_TUNABLE("MPT_GEMM_WAVES", 4);           // 8 forces k_gemm_dma (tuning builds only)
     const bool four = nwaves == 4 && ep.mode == 0 && pl.splits == 1 && (ep.ld % 8) == 0 && mpt_aligned(ep.out, 16) &&
                       (ep.act != 2 || ((ep.ldmask % 8) == 0 && mpt_aligned(ep.mask, 16)));
-    static const int nstage = mpt_env_int("MPT_GEMM_STAGES", 4);          // 4 or 5 ring slots of 32 KiB (tuning only)
     auto k4 = k_gemm_dma<DmaKind<AView>::rc, DmaKind<BView>::rc, 4>;
+    static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(k4), hipFuncAttributeMaxDynamicSharedMemorySize, 4 * 32768), true);
+    (void)once;
+#ifdef MPT_TUNING
+    static const int nstage = MPT_TUNABLE("MPT_GEMM_STAGES", 4);          // 4 or 5 ring slots of 32 KiB
     auto k5 = k_gemm_dma<DmaKind<AView>::rc, DmaKind<BView>::rc, 5>;
     auto kw4 = k_gemm_dma4<DmaOperand4<DmaKind<AView>::rc, 256>, DmaOperand4<DmaKind<BView>::rc, 256>, 256>;
-    static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(k4), hipFuncAttributeMaxDynamicSharedMemorySize, 4 * 32768),
-                        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k5), hipFuncAttributeMaxDynamicSharedMemorySize, 5 * 32768),
-                        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kw4), hipFuncAttributeMaxDynamicSharedMemorySize, 4 * 32768), true);
-    (void)once;
+    static bool once_t = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(k5), hipFuncAttributeMaxDynamicSharedMemorySize, 5 * 32768),
+                          (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kw4), hipFuncAttributeMaxDynamicSharedMemorySize, 4 * 32768), true);
+    (void)once_t;
+#endif
     Problem pb{I, J, R, pl.tiles_i, pl.tiles_j, pl.splits, pl.ktiles_per_split};
     const unsigned grid = (unsigned)((int64_t)pl.tiles_i * pl.tiles_j * pl.splits);
-    static const int depth = mpt_env_int("MPT_GEMM_DEPTH", MPT_GEMM_DEPTH_DEFAULT);   // 32: k_gemm_dma4 (tuning only)
-    if (four && depth == 64) {
-      auto k64 = k_gemm_dma64<DmaOperand64<DmaKind<AView>::rc>, DmaOperand64<DmaKind<BView>::rc>>;
-      static bool once64 = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(k64), hipFuncAttributeMaxDynamicSharedMemorySize, 4 * 32768), true);
-      (void)once64;
-      hipLaunchKernelGGL(k64, dim3(grid), dim3(256), 4 * 32768, s, DmaMat{A.base, A.ld}, DmaMat{B.base, B.ld}, pb, ep);
-    } else if (four) {
+    auto k64 = k_gemm_dma64<DmaOperand64<DmaKind<AView>::rc>, DmaOperand64<DmaKind<BView>::rc>>;
+    static bool once64 = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(k64), hipFuncAttributeMaxDynamicSharedMemorySize, 4 * 32768), true);
+    (void)once64;
+#ifdef MPT_TUNING
+    static const int depth = MPT_TUNABLE("MPT_GEMM_DEPTH", MPT_GEMM_DEPTH_DEFAULT);   // 32: k_gemm_dma4
+    if (four && depth != 64) {
       hipLaunchKernelGGL(kw4, dim3(grid), dim3(256), 4 * 32768, s, DmaMat{A.base, A.ld}, DmaMat{B.base, B.ld}, pb, ep);
+    } else if (!four && nstage == 5) {
+      hipLaunchKernelGGL(k5, dim3(grid), dim3(512), 5 * 32768, s, DmaMat{A.base, A.ld}, DmaMat{B.base, B.ld}, pb, ep);
+    } else
+#endif
+    if (four) {
+      hipLaunchKernelGGL(k64, dim3(grid), dim3(256), 4 * 32768, s, DmaMat{A.base, A.ld}, DmaMat{B.base, B.ld}, pb, ep);
     } else {
-      auto k = nstage == 5 ? k5 : k4;
-      const int lds = (nstage == 5 ? 5 : 4) * 32768;
-      hipLaunchKernelGGL(k, dim3(grid), dim3(512), lds, s, DmaMat{A.base, A.ld}, DmaMat{B.base, B.ld}, pb, ep);
+      hipLaunchKernelGGL(k4, dim3(grid), dim3(512), 4 * 32768, s, DmaMat{A.base, A.ld}, DmaMat{B.base, B.ld}, pb, ep);
     }
     status = hipGetLastError() == hipSuccess ? MPT_OK : MPT_ERR_HIP;
     return true;
@@ -1770,8 +1788,8 @@ bool try_launch_dma(hipStream_t s, const AView& A, const BView& B, bool aligned,
 template <class AView, class BView>
 bool try_launch_dma128(hipStream_t s, const AView& A, const BView& B, bool aligned, int I, int J, int R, const Epilogue& ep, int& status) {
   if constexpr (DmaKind<AView>::ok && DmaKind<BView>::ok) {
-    static const bool enabled = mpt_env_int("MPT_GEMM_STREAMED", 1) != 0 && mpt_env_int("MPT_GEMM_WAVES", 4) == 4 &&
-                                mpt_env_int("MPT_GEMM_TILE128", 1) != 0;
+    static const bool enabled = MPT_TUNABLE("MPT_GEMM_STREAMED", 1) != 0 && MPT_TUNABLE("MPT_GEMM_WAVES", 4) == 4 &&
+                                MPT_TUNABLE("MPT_GEMM_TILE128", 1) != 0;
     if (!enabled || !aligned || (I % 128) || (J % 256) || (R % 64) || ep.mode != 0) return false;
     if ((ep.ld % 8) || !mpt_aligned(ep.out, 16) || (ep.act == 2 && ((ep.ldmask % 8) || !mpt_aligned(ep.mask, 16)))) return false;
     const int64_t t256 = ((int64_t)(I + 255) / 256) * (J / 256), t128 = (int64_t)(I / 128) * (J / 256);
@@ -1973,13 +1991,17 @@ namespace {
 template <class BOp, class BOp64>
 bool try_launch_conv_dma(hipStream_t s, const uint16_t* img, int64_t H, int64_t W, int64_t Cin, int sgn, const typename BOp::Src& B,
                          const typename BOp64::Src& B64, int64_t P, int64_t J, uint16_t* out, int& status) {
-  static const bool enabled = mpt_env_int("MPT_GEMM_STREAMED", 1) != 0 && mpt_env_int("MPT_CONV_STREAMED", 1) != 0;
+  static const bool enabled = MPT_TUNABLE("MPT_GEMM_STREAMED", 1) != 0 && MPT_TUNABLE("MPT_CONV_STREAMED", 1) != 0;
   if (!enabled || (J % 256) || (Cin % 64) || H >= 65536 || W >= 65536 || P * Cin >= (1LL << 31) || P * J >= (1LL << 31)) return false;
   const int R = (int)(9 * Cin);
   const DmaImgSrc A{img, (int)H, (int)W, (int)Cin, sgn, FastDiv((uint32_t)(H * W)), FastDiv((uint32_t)W), FastDiv((uint32_t)(Cin / 32))};
   Epilogue ep{out, J, 0, nullptr, 0, nullptr, 0};
   const int64_t t256 = (P / 256) * (J / 256), t128 = (P / 128) * (J / 256);
-  static const int depth = mpt_env_int("MPT_GEMM_DEPTH", MPT_GEMM_DEPTH_DEFAULT);
+#ifdef MPT_TUNING
+  static const int depth = MPT_TUNABLE("MPT_GEMM_DEPTH", MPT_GEMM_DEPTH_DEFAULT);
+#else
+  constexpr int depth = 64;
+#endif
   if (depth == 64 && (P % 256) == 0 && t256 >= kCUs * 3 / 8) {
     auto k = k_gemm_dma64<DmaImgRC64, BOp64>;
     static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, 4 * 32768), true);
@@ -1987,12 +2009,14 @@ bool try_launch_conv_dma(hipStream_t s, const uint16_t* img, int64_t H, int64_t 
     const DmaImgSrc A64{img, (int)H, (int)W, (int)Cin, sgn, FastDiv((uint32_t)(H * W)), FastDiv((uint32_t)W), FastDiv((uint32_t)(Cin / 64))};
     Problem pb{(int)P, (int)J, R, (int)(P / 256), (int)(J / 256), 1, R / 64};
     hipLaunchKernelGGL(k, dim3((unsigned)t256), dim3(256), 4 * 32768, s, A64, B64, pb, ep);
+#ifdef MPT_TUNING
   } else if ((P % 256) == 0 && t256 >= kCUs * 3 / 8) {
     auto k = k_gemm_dma4<DmaImgRC<256>, BOp, 256>;
     static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, 4 * 32768), true);
     (void)once;
     Problem pb{(int)P, (int)J, R, (int)(P / 256), (int)(J / 256), 1, R / 64};
     hipLaunchKernelGGL(k, dim3((unsigned)t256), dim3(256), 4 * 32768, s, A, B, pb, ep);
+#endif
   } else if ((P % 128) == 0 && t128 >= kCUs * 3 / 8) {
     auto k = k_gemm_dma4<DmaImgRC<128>, BOp, 128>;
     constexpr int lds = 4 * (128 + 256) * 64;
@@ -2051,7 +2075,7 @@ namespace {
 // The reduction over the pixels is long and the output small, so it is normally split through the workspace.
 bool try_launch_conv_wgrad_dma(hipStream_t s, const uint16_t* x, const uint16_t* dy, int64_t H, int64_t W, int64_t C, int64_t Kf, int64_t P,
                                const Epilogue& ep, void* ws, size_t ws_bytes, int& status) {
-  static const bool enabled = mpt_env_int("MPT_GEMM_STREAMED", 1) != 0 && mpt_env_int("MPT_CONV_STREAMED", 1) != 0;
+  static const bool enabled = MPT_TUNABLE("MPT_GEMM_STREAMED", 1) != 0 && MPT_TUNABLE("MPT_CONV_STREAMED", 1) != 0;
   const int64_t J = 9 * C;
   if (!enabled || (Kf % 256) || (C % 256) || (P % 64) || P * C >= (1LL << 31) || P * Kf >= (1LL << 31)) return false;
   const Plan pl = make_plan(Kf, J, P, ws != nullptr);

@@ -28,5 +28,12 @@ __device__ __forceinline__ float mpt_rounded_f32(float v) {
   return v;
 }
 
-// Tunables read once from the environment (benchmark sweeps only; defaults are the tuned values).
+// Tunables.  The library as shipped has none: MPT_TUNABLE(name, default) is the default, a compile-time constant, and
+// the alternative kernels are not built.  A tuning build (-DMPT_TUNING; measurements only, never the product) reads
+// each value once from the environment variable of that name.
+#ifdef MPT_TUNING
 int mpt_env_int(const char* name, int dflt);
+#define MPT_TUNABLE(name, dflt) mpt_env_int(name, dflt)
+#else
+#define MPT_TUNABLE(name, dflt) (dflt)
+#endif

@@ -230,11 +230,11 @@ __global__ __launch_bounds__(kBS) void k_grad_sumsq(const void* __restrict__ gra
     acc = __builtin_fma(g1, g1, acc);
   };
   size_t done = 0;
-  if constexpr (VEC) {                              // 16-byte vectors, four in flight per thread
+  if constexpr (VEC) {                              // 16-byte vectors, eight in flight per thread
     constexpr int EPV = G32 ? 4 : 8;
     const size_t nvec = n / EPV;
     done = nvec * EPV;
-    constexpr int kInFlight = 4;
+    constexpr int kInFlight = 8;
     size_t v = tid;
     for (; v + (kInFlight - 1) * stride < nvec; v += kInFlight * stride) {
       ou4 q[kInFlight];
@@ -379,7 +379,7 @@ extern "C" int mpt_grad_sumsq(void* stream, const void* grad, int grad_is_fp32, 
   if (n != 0) {
     const bool vec = mpt_aligned(grad, 16);
     const size_t units = vec ? n / (grad_is_fp32 ? 4 : 8) + 7 : n;
-    size_t b = (units + (size_t)kBS * 4 - 1) / ((size_t)kBS * 4);    // about four vectors per thread before the grid stops growing
+    size_t b = (units + (size_t)kBS * 8 - 1) / ((size_t)kBS * 8);    // about eight vectors per thread before the grid stops growing
     if (b < 1) b = 1;
     if (b > (size_t)kNormBlocks) b = kNormBlocks;
     blocks = (int)b;

@@ -1,8 +1,8 @@
 """The streamed GEMM kernels, compiled for gfx950, never touch a register that an LDS read in flight will still
 write, and never touch an accumulation register right behind the MFMA that writes it (see asm_check.py: both are
 hazards the compiler cannot see, because the reads and the MFMAs are issued from inline assembly).  Compiles
-csrc/gemm.hip to device assembly (about a minute and a half) and walks every instantiation of k_gemm_dma and
-k_gemm_dma4."""
+csrc/gemm.hip to device assembly (about a minute and a half) and walks every instantiation of k_gemm_dma,
+k_gemm_dma4 and k_gemm_dma64."""
 import os
 import shutil
 import subprocess
@@ -76,4 +76,4 @@ def test_streamed_gemm_kernels_keep_in_flight_read_registers_untouched(tmp_path)
         assert not found, "%s: %s" % (name, found[:5])
         assert sum("v_mfma" in l for l in lines) >= 64          # it is the kernel body that was walked
         n += 1
-    assert n >= 16                                               # every instantiation of both streamed kernels
+    assert n >= 15                                               # every instantiation of the three streamed kernels

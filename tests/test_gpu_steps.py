@@ -242,6 +242,50 @@ def test_cfg3_wgrad_over_timesteps():
     assert np.array_equal(fp16.bits(host16(d_h)), fp16.bits(hn))
 
 
+def test_cfg3_all_timesteps_sampled_rows():
+    """Every one of the 20 timesteps at the layer's own shapes (the test above compares whole outputs at the first
+    and last step): gate and projection products, forward and activation gradient, teacher-forced with the step's
+    operands; 16 seeded rows of each output are compared with the oracle by the GEMM acceptance rule."""
+    c = workloads.lstmp(steps=20)
+    Wg, Wp = dev16(c["Wg"]), dev16(c["Wp"])
+    B = c["xh"].shape[1]
+    ws = torch.empty(max(mpt.mpt_gemm_workspace_bytes(0, B, 32768, 2048), mpt.mpt_gemm_workspace_bytes(1, B, 32768, 2048),
+                         mpt.mpt_gemm_workspace_bytes(0, B, 1024, 8192), mpt.mpt_gemm_workspace_bytes(1, B, 1024, 8192), 16) // 4,
+                     dtype=torch.float32, device="cuda")
+    gates, proj, dxh, dh = _empty16(B, 32768), _empty16(B, 1024), _empty16(B, 2048), _empty16(B, 8192)
+    for t in range(20):
+        rows = np.sort(np.random.default_rng(100 + t).choice(B, 16, replace=False))
+        xh, h, dg, dr = c["xh"][t], c["h"][t], c["dgates"][t], c["dr"][t]
+        print("cfg3 step", t, flush=True)
+        mpt.mpt_gemm_fwd(dev16(xh), Wg, gates, ws)
+        mpt.mpt_gemm_fwd(dev16(h), Wp, proj, ws)
+        mpt.mpt_gemm_dgrad(dev16(dg), Wg, dxh, ws)
+        mpt.mpt_gemm_dgrad(dev16(dr), Wp, dh, ws)
+        for got, ref, label in ((gates, gemm.gemm_fwd(xh[rows], c["Wg"], full=True), "gate fwd"), (proj, gemm.gemm_fwd(h[rows], c["Wp"], full=True), "proj fwd"),
+                                (dxh, gemm.gemm_dgrad(dg[rows], c["Wg"], full=True), "gate dgrad"), (dh, gemm.gemm_dgrad(dr[rows], c["Wp"], full=True), "proj dgrad")):
+            gemm_check(np.ascontiguousarray(host16(got)[rows]), *ref, "cfg3 %s t=%d (16 rows)" % (label, t))
+
+
+def test_cfg3_gate_wgrad_per_timestep_fp32_accumulation():
+    """The gate weights' gradient at its own per-timestep shape (2048 x 32768 output, reduction over the batch of 256),
+    accumulated in FP32 over all 20 timesteps; 24 seeded rows of the 2048 are followed by the oracle.  Allowance per
+    element: the accumulation allowance of every step's product plus one FP32 rounding of the running sum per step."""
+    c = workloads.lstmp(steps=20)
+    T = c["xh"].shape[0]
+    rows = np.sort(np.random.default_rng(7).choice(2048, 24, replace=False))
+    acc_dev = torch.full((2048, 32768), float("nan"), dtype=torch.float32, device="cuda")
+    acc, allow = None, 0.0
+    for t in range(T):
+        mpt.mpt_gemm_wgrad(dev16(c["xh"][t]), dev16(c["dgates"][t]), acc_dev, accumulate=(t > 0))
+        acc, sa = gemm.gemm_wgrad(np.ascontiguousarray(c["xh"][t][:, rows]), c["dgates"][t], out_fp32=True, acc32=acc)
+        allow = allow + C_ACC * U32 * sa + U32 * np.abs(acc.astype(np.float64))
+    got = host(acc_dev)[rows].astype(np.float64)
+    err = np.abs(got - acc.astype(np.float64))
+    print("[cfg3 gate wgrad per step] worst error / allowance = %.3f" % float((err / allow).max()), flush=True)
+    assert (err <= allow).all()
+    assert np.isfinite(host(acc_dev)).all()
+
+
 def test_conv_batchnorm_relu_block_teacher_forced():
     """A residual-network style block on the device: 3x3 convolution -> batch-norm statistics -> normalise + ReLU,
     then its backward pass (ReLU mask, batch-norm reductions and input gradient, convolution gradients).  Every stage is

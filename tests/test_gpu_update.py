@@ -262,3 +262,63 @@ def test_flat_update_full_size_few_steps():
     """116M parameters in the benchmarked launch configuration: 4 steps, one of
     them with planted Inf/NaN, whole arrays compared."""
     _run_flat(n=116_000_000, steps=4, n_inject=1)
+
+
+def test_flat_update_200_steps_full_size_sampled():
+    """The dynamic-scaling workload at its full size for all 200 steps: 116M parameters, loss scale from 2^16 held
+    on the device, Inf/NaN planted at the seeded steps.  Each step's gradient is formed on the device by the
+    workload's recipe (base buffer rotated by the step's offset, multiplied by the current scale in FP32, stored
+    as FP16 - the same casts as the host recipe, checked below on the sample); the oracle runs the trajectory on
+    a fixed sample of elements (both ends, the ragged tail, every 1160th element) and must agree bit for bit in master,
+    momentum and FP16 copy at the checked steps; the overflow flag and the scaler state are compared at every step."""
+    n, steps = 116_000_000, 200
+    f = workloads.FlatUpdate(n=n, steps=steps, n_inject=8)
+    idx = np.unique(np.concatenate([np.arange(1024), np.arange(n - 1024, n), np.arange(0, n, 1160)])).astype(np.int64)
+    d_idx = torch.from_numpy(idx).cuda()
+    w, m = f.w32[idx].copy(), np.zeros(len(idx), F32)
+    h = fp16.rne16(w.astype(np.float64))
+    d_w = dev(f.w32)
+    d_m = torch.zeros(n, dtype=torch.float32, device="cuda")
+    d_h = d_w.half()                                         # torch's cast rounds to nearest even: checked on the sample
+    assert np.array_equal(fp16.bits(host16(d_h[d_idx])), fp16.bits(h))
+    d_true = dev(f.g_true)
+    d_g = torch.empty(n, dtype=torch.float16, device="cuda")
+    osc = Scaler(scale=f.scale0, growth_interval=1000)
+    d_s = mpt.scaler_to_device(mpt.mpt_scaler_init(f.scale0, 1000))
+    flag = _flag()
+    tail = (n // 8) * 8 if n % 8 else n - 1
+    specials = (0x7C00, 0xFC00, 0x7E00, 0x7C01)
+    skipped = 0
+    for t in range(steps):
+        off = int(f.offsets[t])
+        d_g.copy_(torch.roll(d_true, off) * osc.scale)
+        g_s = ((f.g_true[(idx - off) % n]) * np.float32(osc.scale)).astype(np.float16)      # the same elements, host recipe
+        planted = t in f.inject_steps
+        if planted:                                          # the workload's planting rule (FlatUpdate.grad16)
+            j = f.inject_steps.index(t)
+            gb16 = d_g.view(torch.int16)
+            for i, pos in enumerate((0, n - 1, min(tail, n - 1), int(f.rand_pos[t]))):
+                if (j + i) % 2 == 0 or i == j % 4:
+                    pat = specials[(i + j) % 4]
+                    gb16[pos] = pat - 65536 if pat >= 32768 else pat
+                    hit = np.nonzero(idx == pos)[0]
+                    if len(hit):
+                        g_s.view(np.uint16)[hit[0]] = pat
+        if t % 50 == 0 or planted:
+            assert np.array_equal(fp16.bits(host16(d_g[d_idx])), fp16.bits(g_s)), t        # device recipe = host recipe
+        mpt.mpt_unscale_check(d_g, float(F32(osc.inv_scale)), flag)
+        ov_gpu = int(flag.item())
+        mpt.mpt_master_update(d_w, d_m, d_g, d_h, 1.0, f.lr, f.momentum, flag, scaler_dev=d_s)
+        mpt.mpt_loss_scale_update_dev(d_s, flag)
+        ov = int(planted)
+        assert ov_gpu == ov, t
+        w, m, h = update.master_update(w, m, g_s, float(F32(osc.inv_scale)), f.lr, f.momentum, ov, h)
+        osc.update(ov)
+        skipped += ov
+        got = mpt.scaler_from_device(d_s)
+        assert (got.scale, got.good_steps) == (osc.scale, osc.good_steps), t
+        if t % 50 == 49 or planted or t == steps - 1:
+            assert np.array_equal(host(d_w[d_idx]).view(np.uint32), w.view(np.uint32)), t
+            assert np.array_equal(host(d_m[d_idx]).view(np.uint32), m.view(np.uint32)), t
+            assert np.array_equal(fp16.bits(host16(d_h[d_idx])), fp16.bits(h)), t
+    assert skipped == 8 and osc.scale == f.scale0 / 2 ** 8
