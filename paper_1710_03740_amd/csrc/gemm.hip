@@ -817,8 +817,10 @@ struct DmaImgRC {
   int32_t yx[NB];                  // y << 16 | x
   int H, W, Cc, sgn, stage0;
   FastDiv dSpt;
+  int st_dy, st_dx, st_off;        // of the stage being fetched (wavefront-uniform), worked out by the stage's first load
   __device__ __forceinline__ void init(const Src& m, int o0, int r0, int wave, int lane) {
     base = m.base; H = m.H; W = m.W; Cc = m.Cc; sgn = m.sgn; dSpt = m.dSpt; stage0 = r0 >> 5;
+    st_dy = st_dx = st_off = 0;
     const int row = wave * (BO / 4) + (lane >> 2);
     const int chunk = (lane & 3) ^ ((row >> 1) & 3);
 #pragma unroll
@@ -830,15 +832,23 @@ struct DmaImgRC {
       yx[k] = (int32_t)((y << 16) | x);
     }
   }
+  // A stage's loads are issued in order K = 0, 1, ...: the first works out what the stage has in common, the others
+  // reuse it; pixel or line of zeros is a select on the address, not a branch (see DmaImgRC64).
   template <int K>
-  __device__ __forceinline__ void issue(int stage_rel, char* lds_blocks) const {
-    uint32_t tap, cs;
-    dSpt.divmod((uint32_t)(stage0 + stage_rel), tap, cs);          // wavefront-uniform
-    const int tr = (int)tap / 3, ts = (int)tap - 3 * tr;
-    const int dy = sgn * (tr - 1), dx = sgn * (ts - 1);
-    const int yy = (int)((uint32_t)yx[K] >> 16) + dy, xx = (yx[K] & 0xFFFF) + dx;   // y up to 65535: logical shift
+  __device__ __forceinline__ void issue(int stage_rel, char* lds_blocks) {
+    if constexpr (K == 0) {
+      uint32_t tap, cs;
+      dSpt.divmod((uint32_t)(stage0 + stage_rel), tap, cs);        // wavefront-uniform
+      const int tr = (int)tap / 3, ts = (int)tap - 3 * tr;
+      st_dy = sgn * (tr - 1); st_dx = sgn * (ts - 1);
+      st_off = (st_dy * W + st_dx) * Cc + (int)cs * 32;
+    }
+    const int yy = (int)((uint32_t)yx[K] >> 16) + st_dy, xx = (yx[K] & 0xFFFF) + st_dx;   // y up to 65535: logical shift
     const bool inside = (unsigned)yy < (unsigned)H && (unsigned)xx < (unsigned)W;
-    const uint16_t* p = inside ? base + (pix[K] + (dy * W + dx) * Cc + (int)cs * 32) : reinterpret_cast<const uint16_t*>(k_zero_line);
+    const uintptr_t there = reinterpret_cast<uintptr_t>(base + (pix[K] + st_off));
+    const uintptr_t zeros = reinterpret_cast<uintptr_t>(k_zero_line);
+    const uintptr_t mask = inside ? ~(uintptr_t)0 : (uintptr_t)0;
+    const uint16_t* p = reinterpret_cast<const uint16_t*>((there & mask) | (zeros & ~mask));
     __builtin_amdgcn_global_load_lds((global_void_ptr)p, (lds_void_ptr)(lds_blocks + K * 1024), 16, 0, 0);
   }
 };
@@ -857,8 +867,9 @@ struct DmaFilterOC {
   const uint16_t* p[NB];           // lane's source for reduction row (k = row, tap = 0) of its blocks
   int Cc, stage0;
   FastDiv dSpt;
+  int64_t st_off;                  // element offset of the stage being fetched (wavefront-uniform), set by its first load
   __device__ __forceinline__ void init(const Src& m, int o0, int r0, int wave, int lane) {
-    Cc = m.Cc; dSpt = m.dSpt; stage0 = r0 >> 5;
+    Cc = m.Cc; dSpt = m.dSpt; stage0 = r0 >> 5; st_off = 0;
     const int pc = lane & 31;
 #pragma unroll
     for (int k = 0; k < NB; ++k) {
@@ -868,10 +879,13 @@ struct DmaFilterOC {
     }
   }
   template <int K>
-  __device__ __forceinline__ void issue(int stage_rel, char* lds_blocks) const {
-    uint32_t tap, ks;
-    dSpt.divmod((uint32_t)(stage0 + stage_rel), tap, ks);
-    const uint16_t* q = p[K] + ((int64_t)ks * 32 * 9 + tap) * Cc;
+  __device__ __forceinline__ void issue(int stage_rel, char* lds_blocks) {
+    if constexpr (K == 0) {
+      uint32_t tap, ks;
+      dSpt.divmod((uint32_t)(stage0 + stage_rel), tap, ks);
+      st_off = ((int64_t)ks * 32 * 9 + tap) * Cc;
+    }
+    const uint16_t* q = p[K] + st_off;
     __builtin_amdgcn_global_load_lds((global_void_ptr)q, (lds_void_ptr)(lds_blocks + K * 1024), 16, 0, 0);
   }
 };
@@ -893,28 +907,50 @@ struct DmaImgOC {
   int H, W, Cc, dy, dx, r0;
   int32_t row[NB];                 // reduction row inside a stage of this lane's piece of block k
   int32_t coff[NB];                // channel offset of its 16-byte chunk (the LDS swizzle depends on the row)
-  FastDiv dW, dH;
+  // The image coordinates (y, x) of the lane's pixel decide only whether the shifted pixel is inside the image (the
+  // address is linear in the pixel index).  They are divided out once, for the first stage, and then stepped along:
+  // a block's loads are issued stage after stage (the stage index never jumps by more than one, and repeats past
+  // the end), and a stage is 32 pixels further.
+  int32_t py[NB], px[NB];          // of the stage issued last for block k
+  int last[NB];                    // that stage (wavefront-uniform)
+  int step_x, step_y;              // 32 % W and (32 / W) % H
+  int bad_y, bad_x;                // the one row / column whose shifted pixel falls outside (-1: none), fixed per workgroup
   __device__ __forceinline__ void init(const Src& m, int o0, int r0_, int wave, int lane) {
-    base = m.base; H = m.H; W = m.W; Cc = m.Cc; dW = m.dW; dH = m.dH; r0 = r0_;
+    base = m.base; H = m.H; W = m.W; Cc = m.Cc; r0 = r0_;
     const int tap = o0 / m.Cc, c0 = o0 - tap * m.Cc;
     const int tr = tap / 3, ts = tap - 3 * tr;
     dy = tr - 1; dx = ts - 1;
+    bad_y = dy < 0 ? 0 : (dy > 0 ? m.H - 1 : -1);
+    bad_x = dx < 0 ? 0 : (dx > 0 ? m.W - 1 : -1);
+    step_x = 32 % m.W;
+    step_y = (32 / m.W) % m.H;
     const int pc = lane & 31;
 #pragma unroll
     for (int k = 0; k < NB; ++k) {
       row[k] = (wave * NB + k) * 2 + (lane >> 5);
       coff[k] = c0 + (2 * ((pc >> 1) ^ oc_key(row[k])) + (pc & 1)) * 8;
+      uint32_t q, x, n, y;
+      m.dW.divmod((uint32_t)(r0_ + row[k]), q, x);
+      m.dH.divmod(q, n, y);
+      py[k] = (int32_t)y; px[k] = (int32_t)x; last[k] = 0;
     }
   }
   template <int K>
-  __device__ __forceinline__ void issue(int stage_rel, char* lds_blocks) const {
-    const uint32_t p = (uint32_t)(r0 + stage_rel * 32 + row[K]);
-    uint32_t q, x, n, y;
-    dW.divmod(p, q, x);
-    dH.divmod(q, n, y);
-    const int yy = (int)y + dy, xx = (int)x + dx;
-    const bool inside = (unsigned)yy < (unsigned)H && (unsigned)xx < (unsigned)W;
-    const uint16_t* src = inside ? base + ((int64_t)((int)p + dy * W + dx) * Cc + coff[K]) : reinterpret_cast<const uint16_t*>(k_zero_line);
+  __device__ __forceinline__ void issue(int stage_rel, char* lds_blocks) {
+    const int inc = stage_rel - last[K];                             // 0 or 1, wavefront-uniform
+    last[K] = stage_rel;
+    int x = px[K] + (inc ? step_x : 0);
+    const int carry = x >= W ? 1 : 0;
+    x -= carry ? W : 0;
+    int y = py[K] + (inc ? step_y : 0) + carry;
+    y -= y >= H ? H : 0;
+    px[K] = x; py[K] = y;
+    const bool inside = y != bad_y && x != bad_x;
+    const int p = r0 + stage_rel * 32 + row[K];
+    const uintptr_t there = reinterpret_cast<uintptr_t>(base + ((int64_t)(p + dy * W + dx) * Cc + coff[K]));
+    const uintptr_t zeros = reinterpret_cast<uintptr_t>(k_zero_line);
+    const uintptr_t mask = inside ? ~(uintptr_t)0 : (uintptr_t)0;
+    const uint16_t* src = reinterpret_cast<const uint16_t*>((there & mask) | (zeros & ~mask));
     __builtin_amdgcn_global_load_lds((global_void_ptr)src, (lds_void_ptr)(lds_blocks + K * 1024), 16, 0, 0);
   }
 };
@@ -1317,8 +1353,10 @@ struct DmaImgRC64 {
   int32_t yx[8];                   // y << 16 | x
   int H, W, Cc, sgn;
   FastDiv dSpt;
+  int st_dy, st_dx, st_off;        // of the stage being fetched (wavefront-uniform): tap shift, element offset of tap and channel slice
   __device__ __forceinline__ void init(const Src& m, int o0, int wave, int lane) {
     base = m.base; H = m.H; W = m.W; Cc = m.Cc; sgn = m.sgn; dSpt = m.dSpt;
+    st_dy = st_dx = st_off = 0;
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
       const int row = wave * 64 + k * 8 + (lane >> 3);
@@ -1330,15 +1368,25 @@ struct DmaImgRC64 {
       yx[k] = (int32_t)((y << 16) | x);
     }
   }
+  // The loads of a stage are issued in order K = 0 .. 7; the first one works out what the stage has in common (a
+  // dozen dependent scalar instructions, which would otherwise sit in front of every load of a wavefront that has
+  // nothing else to issue meanwhile), the others reuse it.  The choice between the pixel and the line of zeros is a
+  // select on the address, not a branch.
   template <int K>
-  __device__ __forceinline__ void issue(int d, char* slot, int wave) const {
-    uint32_t tap, cs;
-    dSpt.divmod((uint32_t)d, tap, cs);                               // wavefront-uniform
-    const int tr = (int)tap / 3, ts = (int)tap - 3 * tr;
-    const int dy = sgn * (tr - 1), dx = sgn * (ts - 1);
-    const int yy = (int)((uint32_t)yx[K] >> 16) + dy, xx = (yx[K] & 0xFFFF) + dx;
+  __device__ __forceinline__ void issue(int d, char* slot, int wave) {
+    if constexpr (K == 0) {
+      uint32_t tap, cs;
+      dSpt.divmod((uint32_t)d, tap, cs);                             // wavefront-uniform
+      const int tr = (int)tap / 3, ts = (int)tap - 3 * tr;
+      st_dy = sgn * (tr - 1); st_dx = sgn * (ts - 1);
+      st_off = (st_dy * W + st_dx) * Cc + (int)cs * 64;
+    }
+    const int yy = (int)((uint32_t)yx[K] >> 16) + st_dy, xx = (yx[K] & 0xFFFF) + st_dx;
     const bool inside = (unsigned)yy < (unsigned)H && (unsigned)xx < (unsigned)W;
-    const uint16_t* p = inside ? base + (pix[K] + (dy * W + dx) * Cc + (int)cs * 64) : reinterpret_cast<const uint16_t*>(k_zero_line);
+    const uintptr_t there = reinterpret_cast<uintptr_t>(base + (pix[K] + st_off));
+    const uintptr_t zeros = reinterpret_cast<uintptr_t>(k_zero_line);
+    const uintptr_t mask = inside ? ~(uintptr_t)0 : (uintptr_t)0;
+    const uint16_t* p = reinterpret_cast<const uint16_t*>((there & mask) | (zeros & ~mask));
     __builtin_amdgcn_global_load_lds((global_void_ptr)p, (lds_void_ptr)(slot + (wave * 8 + K) * 1024), 16, 0, 0);
   }
 };
@@ -1351,8 +1399,9 @@ struct DmaFilterOC64 {
   const uint16_t* p[4];            // lane's source for reduction row (k = row, tap = 0) of blocks 0-3 (4-7: 32 k further)
   int Cc;
   FastDiv dSpt;
+  int64_t st_off;                  // element offset of the stage being fetched (wavefront-uniform), set by its first load
   __device__ __forceinline__ void init(const Src& m, int o0, int wave, int lane) {
-    Cc = m.Cc; dSpt = m.dSpt;
+    Cc = m.Cc; dSpt = m.dSpt; st_off = 0;
     const int pc = lane & 31;
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
@@ -1362,10 +1411,13 @@ struct DmaFilterOC64 {
     }
   }
   template <int K>
-  __device__ __forceinline__ void issue(int d, char* slot, int wave) const {
-    uint32_t tap, ks;
-    dSpt.divmod((uint32_t)d, tap, ks);
-    const uint16_t* q = p[K & 3] + ((int64_t)((int)ks * 64 + (K >> 2) * 32) * 9 + tap) * Cc;
+  __device__ __forceinline__ void issue(int d, char* slot, int wave) {
+    if constexpr (K == 0) {
+      uint32_t tap, ks;
+      dSpt.divmod((uint32_t)d, tap, ks);
+      st_off = ((int64_t)((int)ks * 64) * 9 + tap) * Cc;
+    }
+    const uint16_t* q = p[K & 3] + (st_off + (int64_t)((K >> 2) * 32 * 9) * Cc);
     __builtin_amdgcn_global_load_lds((global_void_ptr)q, (lds_void_ptr)(slot + (K >> 2) * 16384 + (wave * 4 + (K & 3)) * 1024), 16, 0, 0);
   }
 };
