@@ -435,3 +435,48 @@ def test_accumulation_inside_the_matrix_instruction():
     got = float(out.cpu().numpy()[0, 0])
     print("[mfma accumulation] 2^24 + 16 * 0.125: stored 2^24 + %g" % (got - 2.0 ** 24), flush=True)
     assert abs(got - (2.0 ** 24 + 2.0)) <= C_ACC * 2.0 ** -24 * (2.0 ** 24 + 2.0)
+
+
+@pytest.mark.parametrize("M,N,K", [(256, 1024, 1024), (256, 10, 1024), (100, 72, 2048), (512, 384, 4096), (256, 1024, 8192)])
+def test_split_reduction_adds_every_partial_in_split_order(M, N, K):
+    """Few output tiles and a long reduction: the launcher splits the reduction and a second pass adds the FP32 partials
+    up.  The partials stay in the caller's workspace as [split][I][J], so the stored FP16 result must be, bit for bit,
+    the FP32 sum of those partials in split order, rounded once, and identical from launch to launch."""
+    rng = np.random.default_rng(M + N + K)
+    X = rng.standard_normal((M, K)).astype(np.float16)
+    W = (rng.standard_normal((K, N)) * 0.05).astype(np.float16)
+    dY = (rng.standard_normal((M, N)) * 0.01).astype(np.float16)
+    dX_, dW_, dG_ = dev16(X), dev16(W), dev16(dY)
+    cases = (("fwd", 0, (M, N), lambda out, ws: mpt.mpt_gemm_fwd(dX_, dW_, out, ws)),
+             ("dgrad", 1, (M, K), lambda out, ws: mpt.mpt_gemm_dgrad(dG_, dW_, out, ws)),
+             ("wgrad", 2, (K, N), lambda out, ws: mpt.mpt_gemm_wgrad(dX_, dG_, out, ws=ws)))
+    for name, op, shape, call in cases:
+        need = mpt.mpt_gemm_workspace_bytes(op, M, N, K)
+        if need == 0:
+            continue
+        I, J = shape
+        splits = need // (I * J * 4)
+        assert splits * I * J * 4 == need and splits >= 2
+        ws = torch.full((need // 4,), float("nan"), dtype=torch.float32, device="cuda")
+        first = None
+        for rep in range(3):
+            out = torch.full(shape, float("nan"), dtype=torch.float16, device="cuda")
+            call(out, ws)
+            got = host16(out)
+            part = ws.cpu().numpy().reshape(splits, I, J)
+            if rep == 0 and np.isnan(part).all():
+                # the workspace size is an upper bound over the kernels the launcher may pick; this shape went
+                # through a whole-tile kernel without a split and left the workspace untouched
+                print("[split order] %s %dx%dx%d: not split" % (name, M, N, K), flush=True)
+                break
+            acc = part[0].copy()
+            for s_ in range(1, splits):
+                acc = acc + part[s_]                      # float32 additions, split order
+            assert acc.dtype == np.float32
+            want = acc.astype(np.float16)
+            assert np.array_equal(fp16.bits(got), fp16.bits(want)), (name, rep)
+            if first is None:
+                first = got
+            assert np.array_equal(fp16.bits(got), fp16.bits(first)), (name, rep)
+        else:
+            print("[split order] %s %dx%dx%d: %d splits of %d x %d" % (name, M, N, K, splits, I, J), flush=True)
