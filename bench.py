@@ -296,7 +296,15 @@ def measure_configs(torch, mpt, np, dev, workloads):
     t = timeit(mlp_step, reps=50)
     fl = 3 * 2.0 * 256 * (1024 * 1024 + 1024 * 10)
     mfma_row("cfg1 MLP 256x1024 -> 1024 -> 10", "whole step: 2 fwd (ReLU folded), loss, 2 wgrad (+Inf/NaN vote), dgrad (mask folded), 2 master updates; split reductions through one workspace", fl, t)
-    del x, w1, w2, w1_32, w2_32
+    # the same step with no host work between its launches: captured once, replayed (first use of every kernel is the
+    # eager timing above, outside the capture)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        mlp_step()
+    t = timeit(graph.replay, reps=50)
+    mfma_row("cfg1 MLP 256x1024 -> 1024 -> 10", "whole step replayed from a HIP graph (the 13 launches back to back, no host work between them)", fl, t)
+    del graph, x, w1, w2, w1_32, w2_32
 
     # ---- cfg 3: projected-LSTM layer products at batch 256 (per timestep), and the time-batched weight gradient
     Bt, T, DK, G4, HC, RP = 256, 20, 2048, 4 * 8192, 8192, 1024
