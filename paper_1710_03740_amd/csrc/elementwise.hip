@@ -8,7 +8,6 @@
 // non-contracting intrinsics so each FP32 operation rounds on its own.
 #include "mpt_internal.h"
 #include <stdlib.h>
-#include <mutex>
 
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));
 typedef _Float16 h4 __attribute__((ext_vector_type(4)));
@@ -21,32 +20,6 @@ int mpt_env_int(const char* name, int dflt) {
   return v && *v ? atoi(v) : dflt;
 }
 #endif
-
-// Arrival counters (see mpt_internal.h): zero when the code object is loaded, kept zero by their users.
-constexpr int kTickets = 1 << 12;
-static __device__ __align__(256) uint32_t tickets_array[kTickets];
-
-namespace {
-constexpr int kTicketDevices = 64;
-uint32_t* g_tickets_ptr[kTicketDevices];     // per device; written once under the mutex
-int g_tickets_next[kTicketDevices];
-std::mutex g_tickets_mutex;
-}  // namespace
-
-uint32_t* mpt_ticket_slice(int count) {
-  int dev = -1;
-  if (count < 1 || count > kTickets || hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kTicketDevices) return nullptr;
-  std::lock_guard<std::mutex> lock(g_tickets_mutex);
-  if (g_tickets_ptr[dev] == nullptr) {
-    void* p = nullptr;
-    if (hipGetSymbolAddress(&p, HIP_SYMBOL(tickets_array)) != hipSuccess || p == nullptr) return nullptr;
-    g_tickets_ptr[dev] = static_cast<uint32_t*>(p);
-  }
-  if (g_tickets_next[dev] + count > kTickets) g_tickets_next[dev] = 0;
-  uint32_t* slice = g_tickets_ptr[dev] + g_tickets_next[dev];
-  g_tickets_next[dev] += count;
-  return slice;
-}
 
 namespace {
 
@@ -386,24 +359,6 @@ __global__ __launch_bounds__(kThreads) void k_relu_bwd(size_t n, const uint16_t*
   }
 }
 
-// Mean of the row losses by the first 256 threads of a workgroup (every thread of the workgroup must call it): each
-// takes a strided share in row order, then a fixed tree - the same additions whoever runs it, so the result does not
-// depend on whether a separate launch or the last workgroup of the softmax kernel computes it.
-__device__ __forceinline__ void loss_mean_by_256(int64_t B, const float* row_loss, float* loss, float* part /* LDS, 256 floats */) {
-  const int t = threadIdx.x;
-  if (t < kThreads) {
-    float acc = 0.f;
-    for (int64_t r = t; r < B; r += kThreads) acc = __fadd_rn(acc, row_loss[r]);
-    part[t] = acc;
-  }
-  __syncthreads();
-  for (int w = kThreads / 2; w > 0; w >>= 1) {
-    if (t < w) part[t] = __fadd_rn(part[t], part[t + w]);
-    __syncthreads();
-  }
-  if (t == 0) loss[0] = div_rn(part[0], (float)B);
-}
-
 typedef _Float16 sm_h2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
@@ -424,7 +379,7 @@ __device__ __forceinline__ float wave_sum(float v) {
 template <int WAVES, int NCH, bool VEC>
 __global__ __launch_bounds__((WAVES * 64 > kThreads ? WAVES * 64 : kThreads)) void k_softmax_xent_rows(
     int64_t B, int64_t C, const uint16_t* __restrict__ logits, int64_t ldl, const int32_t* __restrict__ labels,
-    float factor, uint16_t* __restrict__ dlogits, int64_t ldd, float* row_loss, bool stream, float* loss, uint32_t* ticket) {
+    float factor, uint16_t* __restrict__ dlogits, int64_t ldd, float* __restrict__ row_loss, bool stream) {
   constexpr int NT = WAVES * 64 > kThreads ? WAVES * 64 : kThreads;   // threads per workgroup
   constexpr int T = 64 * WAVES;                                        // threads per row
   __shared__ float red[NT / 64];
@@ -486,7 +441,7 @@ __global__ __launch_bounds__((WAVES * 64 > kThreads ? WAVES * 64 : kThreads)) vo
       sum = __fadd_rn(sum, x);
     }
   sum = across(sum, false);
-  if (live) {
+  if (!live) return;
   const int32_t lab = min(max(labels[row], 0), (int32_t)(C - 1));      // a label outside [0, C) is the caller's error; it must not become a wild read
   const float inv = div_rn(1.0f, sum);
   const float scale_all = __fmul_rn(inv, factor);                        // every element but the label's: p * factor in one multiplication
@@ -526,13 +481,6 @@ __global__ __launch_bounds__((WAVES * 64 > kThreads ? WAVES * 64 : kThreads)) vo
   if (row_loss != nullptr && tr == 0) {
     // -log p[label] = log(sum) - (z[label] - max)
     row_loss[row] = __fsub_rn(logf(sum), __fsub_rn((float)z[lab], mx));
-  }
-  }
-  // the workgroup that finishes last averages the row losses (no second launch)
-  if (ticket != nullptr) {
-    __shared__ uint32_t arrived_last;
-    __shared__ float part[kThreads];
-    if (mpt_last_arriver(ticket, gridDim.x, &arrived_last)) loss_mean_by_256(B, row_loss, loss, part);
   }
 }
 
@@ -609,7 +557,15 @@ __global__ __launch_bounds__(1024) void k_softmax_xent_long(
 // Mean of the row losses: one workgroup, each thread a strided share in row order, then a fixed-order sum (reproducible).
 __global__ __launch_bounds__(kThreads) void k_loss_mean(int64_t B, const float* __restrict__ row_loss, float* __restrict__ loss) {
   __shared__ float part[kThreads];
-  loss_mean_by_256(B, row_loss, loss, part);
+  float acc = 0.f;
+  for (int64_t r = threadIdx.x; r < B; r += kThreads) acc = __fadd_rn(acc, row_loss[r]);
+  part[threadIdx.x] = acc;
+  __syncthreads();
+  for (int w = kThreads / 2; w > 0; w >>= 1) {
+    if ((int)threadIdx.x < w) part[threadIdx.x] = __fadd_rn(part[threadIdx.x], part[threadIdx.x + w]);
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) loss[0] = div_rn(part[0], (float)B);
 }
 
 // Grid size for a streaming pass over `units` thread-trips.
@@ -801,17 +757,15 @@ extern "C" int mpt_softmax_xent_scaled(void* stream, int64_t B, int64_t C, const
   const float factor = scale / (float)B;
   const bool vec = mpt_aligned(logits, 16) && mpt_aligned(dlogits, 16) && (ldl % 8) == 0 && (ldd % 8) == 0 && (C % 8) == 0;
   const bool nontemporal = B * C * 2 > (192LL << 20);   // beyond the memory-side cache
-  uint32_t* ticket = nullptr;
 #define MPT_SM_LAUNCH(WAVES, NCH)                                                                                                   \
   do {                                                                                                                              \
     constexpr unsigned nt = WAVES * 64 > kThreads ? WAVES * 64 : kThreads;                                                          \
     const unsigned rows = nt / (64 * WAVES);                                                                                        \
     const unsigned grid = (unsigned)((B + rows - 1) / rows);                                                                        \
-    if (loss != nullptr) ticket = mpt_ticket_slice(1);   /* the last workgroup then also averages the row losses */               \
     if (vec) hipLaunchKernelGGL((k_softmax_xent_rows<WAVES, NCH, true>), dim3(grid), dim3(nt), 0, s, B, C, logits, ldl, labels,     \
-                                factor, dlogits, ldd, row_loss, nontemporal, loss, ticket);                                         \
+                                factor, dlogits, ldd, row_loss, nontemporal);                                                       \
     else hipLaunchKernelGGL((k_softmax_xent_rows<WAVES, NCH, false>), dim3(grid), dim3(nt), 0, s, B, C, logits, ldl, labels,        \
-                            factor, dlogits, ldd, row_loss, nontemporal, loss, ticket);                                             \
+                            factor, dlogits, ldd, row_loss, nontemporal);                                                           \
   } while (0)
   if (C <= 512) MPT_SM_LAUNCH(1, 1);
   else if (C <= 2048) MPT_SM_LAUNCH(1, 4);
@@ -822,7 +776,7 @@ extern "C" int mpt_softmax_xent_scaled(void* stream, int64_t B, int64_t C, const
   else hipLaunchKernelGGL(k_softmax_xent_long<false>, dim3((unsigned)B), dim3(1024), 0, s, B, C, logits, ldl, labels, factor, dlogits, ldd, row_loss);
 #undef MPT_SM_LAUNCH
   MPT_LAUNCH_CHECK();
-  if (loss != nullptr && ticket == nullptr) {          // rows too long for the register-resident kernel (or no counter to be had)
+  if (loss != nullptr) {
     hipLaunchKernelGGL(k_loss_mean, dim3(1), dim3(kThreads), 0, s, B, row_loss, loss);
     MPT_LAUNCH_CHECK();
   }

@@ -37,30 +37,3 @@ int mpt_env_int(const char* name, int dflt);
 #else
 #define MPT_TUNABLE(name, dflt) (dflt)
 #endif
-
-// Arrival counters for "the workgroup that finishes last does the final step" (a small ordered reduction of partial
-// results without a second launch).  They live in a zero-initialised device array that is part of the library's code object;
-// mpt_ticket_slice hands a launch `count` consecutive counters from a ring (host side, per device, thread-safe).  The
-// last arriver resets its counter, so a slice is all zero again by the time the ring comes back to it: with 4096
-// counters that takes thousands of launches, far more than a stream holds in flight.  Returns nullptr on failure.
-uint32_t* mpt_ticket_slice(int count);
-
-#if defined(__HIPCC__)
-// Called by every thread of a workgroup once its partial results are stored.  True, in every thread, for the workgroup
-// that arrives last among `expected` at *ticket; that workgroup then sees all partial results, from whichever die.
-// lds_word: one word of LDS for the broadcast.
-__device__ __forceinline__ bool mpt_last_arriver(uint32_t* ticket, uint32_t expected, uint32_t* lds_word) {
-  __threadfence();                                   // release: this thread's stores are visible device-wide ...
-  __syncthreads();                                   // ... before the workgroup's arrival is
-  if (threadIdx.x == 0) {
-    const uint32_t prev = atomicAdd(ticket, 1u);     // device scope: performed at the memory side, one order for all dies
-    const bool last = prev == expected - 1u;
-    if (last) atomicExch(ticket, 0u);                // clean for the next launch that gets this counter
-    *lds_word = last ? 1u : 0u;
-  }
-  __syncthreads();
-  const bool last = *lds_word != 0u;
-  if (last) __threadfence();                         // acquire: no stale lines of the other workgroups' results
-  return last;
-}
-#endif
