@@ -1482,7 +1482,7 @@ struct FragAddr64 {
   }
 };
 
-template <class AOp, class BOp>
+template <class AOp, class BOp, bool F32OUT = false>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_gemm_dma64(typename AOp::Src A, typename BOp::Src B, Problem pb, Epilogue ep) {
   constexpr bool A_RC = AOp::kRC, B_RC = BOp::kRC;
   constexpr int NA = 8, HALF = 4, BM = 256;
@@ -1497,7 +1497,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   int ti, tj, sp;
   tile_of(pb, blockIdx.x, ti, tj, sp);
   const int i0 = ti * BM, j0 = tj * 256;
-  const int nd = pb.R / 64;                                            // stages (>= 1)
+  const int d0 = sp * pb.ktiles_per_split;                             // first stage of this workgroup's share of the reduction
+  const int nd = min(pb.ktiles_per_split, pb.R / 64 - d0);             // its stages (>= 1: the host plans no empty split)
   const int nst = 2 * nd;                                              // half stages
 
   AOp da;
@@ -1505,8 +1506,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   da.init(A, i0, wave, lane);
   db.init(B, j0, wave, lane);
   // load K of stage d of A / B into slot `sl`; past the end: refetch the last stage into a slot nobody reads
-  auto issueA = [&](int d, int sl, auto kc) { da.template issue<decltype(kc)::value>(min(d, nd - 1), lds + sl * OPSLOT, wave); };
-  auto issueB = [&](int d, int sl, auto kc) { db.template issue<decltype(kc)::value>(min(d, nd - 1), lds + B_BASE + sl * OPSLOT, wave); };
+  auto issueA = [&](int d, int sl, auto kc) { da.template issue<decltype(kc)::value>(d0 + min(d, nd - 1), lds + sl * OPSLOT, wave); };
+  auto issueB = [&](int d, int sl, auto kc) { db.template issue<decltype(kc)::value>(d0 + min(d, nd - 1), lds + B_BASE + sl * OPSLOT, wave); };
   auto issueA8 = [&](int d, int sl) {
     issueA(d, sl, std::integral_constant<int, 0>{}); issueA(d, sl, std::integral_constant<int, 1>{});
     issueA(d, sl, std::integral_constant<int, 2>{}); issueA(d, sl, std::integral_constant<int, 3>{});
@@ -1653,8 +1654,36 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   }
   __builtin_amdgcn_sched_barrier(0);
 
-  // ---- epilogue: k_gemm_dma4's FP16 store through LDS (whole tiles, 16-byte aligned rows)
+  // ---- epilogue: k_gemm_dma4's two forms (whole tiles, 16-byte aligned rows): FP32 straight from the accumulators
+  // (store, accumulate, or this split's partial), or the FP16 store through LDS
   bool bad = false;
+  if constexpr (F32OUT) {
+    const int64_t split_off = (ep.mode == 3) ? (int64_t)sp * pb.I * pb.J : 0;
+    float* out = reinterpret_cast<float*>(ep.out) + split_off + (int64_t)(i0 + wm * (BM / 2) + (lane & 15)) * ep.ld + j0 + wn * 128 + ((lane >> 4) << 2);
+#pragma unroll
+    for (int a = 0; a < NA; ++a)
+#pragma unroll
+      for (int b = 0; b < 8; ++b) {
+        asm volatile("" : "+a"(acc[a][b]) : : "memory");              // one block at a time out of the accumulation registers
+        float* o = out + (int64_t)(a * 16) * ep.ld + b * 16;
+        float4v v = acc[a][b];
+        if (ep.mode == 2) {
+          const float4v old = *reinterpret_cast<const float4v*>(o);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = __fadd_rn(old[e], v[e]);
+        }
+        if (ep.flag && ep.mode != 3) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) bad |= (__float_as_uint(v[e]) & 0x7F800000u) == 0x7F800000u;
+        }
+        *reinterpret_cast<float4v*>(o) = v;
+      }
+    if (ep.flag != nullptr && ep.mode != 3) {
+      const unsigned long long vote = __builtin_amdgcn_ballot_w64(bad);
+      if (vote != 0ull && lane == 0) atomicOr(ep.flag, 1u);
+    }
+    return;
+  }
   __syncthreads();
   char* mine = lds + wave * (BM / 2 * 256);
   const int li = lane & 15, lg = lane >> 4;
@@ -1820,8 +1849,11 @@ bool try_launch_dma(hipStream_t s, const AView& A, const BView& B, bool aligned,
     Problem pb{I, J, R, pl.tiles_i, pl.tiles_j, pl.splits, pl.ktiles_per_split};
     const unsigned grid = (unsigned)((int64_t)pl.tiles_i * pl.tiles_j * pl.splits);
     auto k64 = k_gemm_dma64<DmaOperand64<DmaKind<AView>::rc>, DmaOperand64<DmaKind<BView>::rc>>;
-    static bool once64 = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(k64), hipFuncAttributeMaxDynamicSharedMemorySize, 4 * 32768), true);
+    auto k64f = k_gemm_dma64<DmaOperand64<DmaKind<AView>::rc>, DmaOperand64<DmaKind<BView>::rc>, true>;
+    static bool once64 = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(k64), hipFuncAttributeMaxDynamicSharedMemorySize, 4 * 32768),
+                          (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k64f), hipFuncAttributeMaxDynamicSharedMemorySize, 4 * 32768), true);
     (void)once64;
+    static const int depth32_f32 = MPT_TUNABLE("MPT_GEMM_F32_DEPTH32", 0);   // 1: FP32 outputs on k_gemm_dma (tuning builds only)
 #ifdef MPT_TUNING
     static const int depth = MPT_TUNABLE("MPT_GEMM_DEPTH", MPT_GEMM_DEPTH_DEFAULT);   // 32: k_gemm_dma4
     if (four && depth != 64) {
@@ -1832,6 +1864,9 @@ bool try_launch_dma(hipStream_t s, const AView& A, const BView& B, bool aligned,
 #endif
     if (four) {
       hipLaunchKernelGGL(k64, dim3(grid), dim3(256), 4 * 32768, s, DmaMat{A.base, A.ld}, DmaMat{B.base, B.ld}, pb, ep);
+    } else if (ep.mode != 0 && depth32_f32 == 0) {
+      // FP32 outputs (store, accumulate, split partials; 16 bytes per lane, checked above) on the same kernel
+      hipLaunchKernelGGL(k64f, dim3(grid), dim3(256), 4 * 32768, s, DmaMat{A.base, A.ld}, DmaMat{B.base, B.ld}, pb, ep);
     } else {
       hipLaunchKernelGGL(k4, dim3(grid), dim3(512), 4 * 32768, s, DmaMat{A.base, A.ld}, DmaMat{B.base, B.ld}, pb, ep);
     }

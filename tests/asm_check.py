@@ -23,15 +23,55 @@ _NO_VGPR_DEST = ("v_mfma", "v_cmp", "v_accvgpr_write", "v_readfirstlane", "v_rea
 _LOADS_WITH_DEST = ("global_load_dword", "global_load_ushort", "global_load_ubyte", "global_load_short", "buffer_load", "scratch_load", "flat_load")
 
 
+def _merge(states):
+    """In-flight lists of several predecessors -> one list that is at least as pending as each: position by position
+    from the newest end, the union of the destinations."""
+    out = []
+    for k in range(1, max((len(s) for s in states), default=0) + 1):
+        dest = set()
+        for s in states:
+            if len(s) >= k:
+                dest |= s[-k][0]
+        out.append((dest, -1))
+    return out[::-1]
+
+
 def check_kernel(lines):
-    """Returns a list of (line index, message) for the instruction lines of one kernel."""
+    """Returns a list of (line index, message) for the instruction lines of one kernel.
+
+    Program order is file order, except at a label that cannot be fallen into (the instruction before it is an
+    unconditional branch or the end of the program) and whose every branch to it lies earlier in the file: there the
+    state is the merge of the states at those branches (the compiler moves cold blocks, such as the tail of the
+    epilogue, behind the main loop, where file order would pair them with the loop's last reads)."""
+    targets = {}
+    for ln in lines:
+        t = ln.split(";")[0].strip()
+        if t.startswith(("s_branch", "s_cbranch")):
+            lab = t.split()[-1]
+            targets[lab] = targets.get(lab, 0) + 1
     inflight, found = [], []
+    at_branch = {}                    # label -> states at the branches to it seen so far
+    falls_through = True
     for n, ln in enumerate(lines):
         t = ln.split(";")[0].strip()
+        if t.endswith(":") and not t.startswith(".amdhsa") and " " not in t:
+            lab = t[:-1]
+            seen = at_branch.get(lab, [])
+            if not falls_through and seen and len(seen) == targets.get(lab, 0):
+                inflight = _merge(seen)
+            elif falls_through and seen:
+                inflight = _merge(seen + [inflight])
+            falls_through = True
+            continue
         if not t or t.endswith(":") or t.startswith("."):
             continue
         parts = t.replace(",", " ").split()
         op, args = parts[0], parts[1:]
+        if op.startswith(("s_branch", "s_cbranch")):
+            at_branch.setdefault(args[-1], []).append(list(inflight))
+            falls_through = op != "s_branch"
+            continue
+        falls_through = op != "s_endpgm"
         if op == "s_waitcnt":
             m = re.search(r"lgkmcnt\((\d+)\)", t)
             if m:
