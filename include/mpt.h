@@ -61,8 +61,11 @@ int mpt_version(void);
  * Workspace: split-reduction needs FP32 partials in caller memory.  Pass
  * ws_dev = NULL, ws_bytes = 0 to forbid splitting (always legal), or a device
  * buffer of at least mpt_gemm_workspace_bytes(op, M, N, K) bytes, 16-byte
- * aligned.  Partials are summed in a fixed order (results are run-to-run
- * deterministic) and rounded once.
+ * aligned.  The size is an upper bound over the kernels the library may pick
+ * for the shape (a whole number of [I][J] FP32 partial outputs; which kernel
+ * runs also depends on the operands' alignment); the partials written lead
+ * the buffer as [split][I][J].  Partials are summed in a fixed order (results
+ * are run-to-run deterministic) and rounded once.
  * ------------------------------------------------------------------------- */
 typedef enum mpt_gemm_op { MPT_OP_FWD = 0, MPT_OP_DGRAD = 1, MPT_OP_WGRAD = 2 } mpt_gemm_op;
 

@@ -24,6 +24,7 @@
 // LDS is double buffered: global loads for tile t+1 are issued before the MFMAs
 // of tile t and written to the other buffer after them; one barrier per tile.
 #include "mpt_internal.h"
+#include <algorithm>
 #include <mutex>
 #include <type_traits>
 
@@ -1798,6 +1799,30 @@ size_t plan_ws_bytes(const Plan& p, int64_t I, int64_t J) {
   return p.splits > 1 ? (size_t)p.splits * (size_t)I * (size_t)J * sizeof(float) : 0;
 }
 
+// A second way to split: 128 x 256 tiles of the streamed kernel, for outputs whose row count is an odd multiple of 128
+// (256-row tiles would compute a padded half tile: 128 x 4096 x 4096 forward 27.5 -> 18.8 us) and whose time the memory
+// traffic decides: few tiles and an arithmetic intensity (every operand and the result once) below the ridge of
+// 2.5 PFLOP/s / 8 TB/s.  (For row counts that are multiples of 256 it measured within 2 % of the 256-row plans either
+// way - gate input gradient 55.8 against 55.5 us, projection 22.7 against 23.2 - and is not used.)  Depends on the shape
+// only, so that the workspace size can be asked for beforehand.
+bool plan_split128(int64_t I, int64_t J, int64_t R, Plan& p) {
+  if ((I % 256) != 128 || (J % 256) || (R % 64)) return false;
+  const int64_t t128 = (I / 128) * (J / 256), kt = R / 64;
+  if (t128 >= kCUs * 3 / 4) return false;
+  int64_t splits = kCUs / t128;
+  if (splits > kt / 8) splits = kt / 8;                               // at least 8 stages of 64 per workgroup
+  if (splits > 64) splits = 64;
+  if (splits < 2 || t128 * splits < kCUs * 3 / 8) return false;
+  const double flops = 2.0 * (double)I * (double)J * (double)R, bytes = 2.0 * ((double)I * R + (double)R * J + (double)I * J);
+  if (flops >= 312.5 * bytes) return false;
+  p.big = false;
+  p.tiles_i = (int)(I / 128);
+  p.tiles_j = (int)(J / 256);
+  p.ktiles_per_split = (int)((kt + splits - 1) / splits);
+  p.splits = (int)((kt + p.ktiles_per_split - 1) / p.ktiles_per_split);   // no empty split
+  return p.splits >= 2;
+}
+
 template <class AView, class BView, bool A_ALIGNED, bool B_ALIGNED>
 int launch_tiles(hipStream_t s, const AView& A, const BView& B, const Plan& pl, int I, int J, int R, const Epilogue& ep) {
   Problem pb{I, J, R, pl.tiles_i, pl.tiles_j, pl.splits, pl.ktiles_per_split};
@@ -1902,6 +1927,26 @@ bool try_launch_dma128(hipStream_t s, const AView& A, const BView& B, bool align
   }
 }
 
+// The split 128-row plan on the streamed kernel's FP32 epilogue: partials [split][I][J] into the workspace.
+template <class AView, class BView>
+bool try_launch_split128(hipStream_t s, const AView& A, const BView& B, bool aligned, const Plan& p, int I, int J, int R, float* ws, int& status) {
+  if constexpr (DmaKind<AView>::ok && DmaKind<BView>::ok) {
+    static const bool enabled = MPT_TUNABLE("MPT_GEMM_STREAMED", 1) != 0 && MPT_TUNABLE("MPT_GEMM_SPLIT128", 1) != 0;
+    if (!enabled || !aligned || !mpt_aligned(ws, 16)) return false;
+    auto k = k_gemm_dma4<DmaOperand4<DmaKind<AView>::rc, 128>, DmaOperand4<DmaKind<BView>::rc, 256>, 128, true>;
+    constexpr int lds = 4 * (128 + 256) * 64;
+    static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, lds), true);
+    (void)once;
+    Problem pb{I, J, R, p.tiles_i, p.tiles_j, p.splits, p.ktiles_per_split};
+    Epilogue part{ws, J, 3, nullptr, 0, nullptr, 0};
+    hipLaunchKernelGGL(k, dim3((unsigned)((int64_t)p.tiles_i * p.tiles_j * p.splits)), dim3(256), lds, s, DmaMat{A.base, A.ld}, DmaMat{B.base, B.ld}, pb, part);
+    status = hipGetLastError() == hipSuccess ? MPT_OK : MPT_ERR_HIP;
+    return true;
+  } else {
+    return false;
+  }
+}
+
 // Run one contraction: single pass, or split partials + ordered reduction.
 template <class AView, class BView>
 int run(hipStream_t s, const AView& A, const BView& B, bool a_aligned, bool b_aligned, int I, int J, int R, Epilogue ep, void* ws, size_t ws_bytes) {
@@ -1910,6 +1955,16 @@ int run(hipStream_t s, const AView& A, const BView& B, bool a_aligned, bool b_al
   if (ws != nullptr && ws_bytes < plan_ws_bytes(pl, I, J)) return MPT_ERR_WORKSPACE;
   int st = MPT_OK;
   if (try_launch_dma128(s, A, B, aligned, I, J, R, ep, st)) return st;
+  Plan p128;
+  if (ws != nullptr && plan_split128(I, J, R, p128) && ws_bytes >= plan_ws_bytes(p128, I, J) &&
+      try_launch_split128(s, A, B, aligned, p128, I, J, R, reinterpret_cast<float*>(ws), st)) {
+    if (st != MPT_OK) return st;
+    const int64_t total = (int64_t)I * J;
+    hipLaunchKernelGGL(k_split_reduce, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
+                       reinterpret_cast<const float*>(ws), p128.splits, I, J, ep);
+    MPT_LAUNCH_CHECK();
+    return MPT_OK;
+  }
   Epilogue first = ep;
   if (pl.splits > 1) {
     first.out = ws; first.ld = J; first.mode = 3; first.flag = nullptr;
@@ -1951,7 +2006,11 @@ extern "C" size_t mpt_gemm_workspace_bytes(int op, int64_t M, int64_t N, int64_t
     case MPT_OP_WGRAD: I = K; J = N; R = M; break;
     default: return 0;
   }
-  return plan_ws_bytes(make_plan(I, J, R, true), I, J);
+  // the larger of what the two ways of splitting need: which one runs also depends on the operands' alignment
+  size_t need = plan_ws_bytes(make_plan(I, J, R, true), I, J);
+  Plan p128;
+  if (plan_split128(I, J, R, p128)) need = std::max(need, plan_ws_bytes(p128, I, J));
+  return need;
 }
 
 namespace {
