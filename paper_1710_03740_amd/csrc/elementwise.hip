@@ -398,9 +398,13 @@ __global__ __launch_bounds__((WAVES * 64 > kThreads ? WAVES * 64 : kThreads)) vo
     if constexpr (VEC) {
       if (live && c0 < C) q[i] = stream ? __builtin_nontemporal_load(reinterpret_cast<const h8*>(z + c0)) : *reinterpret_cast<const h8*>(z + c0);
     } else {
+      // no branch around a load: every lane reads some element of the row (its own, or the row's last) and keeps it only
+      // if the element exists - behind branches the eight loads would go out one after the other, each waited for
 #pragma unroll
-      for (int e = 0; e < 8; ++e)
-        if (live && c0 + e < C) q[i][e] = z[c0 + e];
+      for (int e = 0; e < 8; ++e) {
+        const _Float16 v = z[min(c0 + e, C - 1)];
+        if (live && c0 + e < C) q[i][e] = v;
+      }
     }
     // row maximum on packed pairs (one instruction per two elements), widened once per chunk
     sm_h2 m2 = __builtin_elementwise_max(sm_h2{q[i][0], q[i][1]}, sm_h2{q[i][2], q[i][3]});

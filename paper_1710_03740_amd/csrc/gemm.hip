@@ -149,19 +149,26 @@ struct FilterOC {
 };
 
 // ---------------------------------------------------------------- chunk fetch
+// `safe`: an address that can always be read (the view's first element).  The element-wise form has no branch around
+// its loads: each reads an existing element (its own, the chunk's last, or `safe`) and the value is kept only if the
+// element exists.  Behind branches the loads went out one at a time, each waited for: a 256 x 1024 output over a
+// reduction of 10 took 20 us, all of it in two such chunks per operand.
 template <bool ALIGNED>
-__device__ __forceinline__ uint4v fetch(const uint16_t* p, int nv) {
+__device__ __forceinline__ uint4v fetch(const uint16_t* p, int nv, const uint16_t* safe) {
   uint4v v = {0u, 0u, 0u, 0u};
   if constexpr (ALIGNED) {
     if (nv == 8) v = *reinterpret_cast<const uint4v*>(p);
   } else {
-    if (nv > 0) {
-      uint16_t e[8];
+    const uint16_t* q = nv > 0 ? p : safe;
+    const int last = max(nv, 1) - 1;
+    uint16_t e[8];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) e[i] = (i < nv) ? p[i] : (uint16_t)0;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) v[i] = (uint32_t)e[2 * i] | ((uint32_t)e[2 * i + 1] << 16);
+    for (int i = 0; i < 8; ++i) {
+      const uint16_t x = q[min(i, last)];
+      e[i] = (i < nv) ? x : (uint16_t)0;
     }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = (uint32_t)e[2 * i] | ((uint32_t)e[2 * i + 1] << 16);
   }
   return v;
 }
@@ -185,7 +192,7 @@ struct TileLoader {
         const int row = row0 + i * (NT / 8);
         int nv;
         const uint16_t* p = v.chunk(o_base + row, r_base + kc * 8, nv);
-        reg[i] = fetch<ALIGNED>(p, nv);
+        reg[i] = fetch<ALIGNED>(p, nv, v.base);
       }
     } else {
       const int oc = t % (BO / 8), rg = t / (BO / 8);
@@ -193,7 +200,7 @@ struct TileLoader {
       for (int i = 0; i < 4; ++i) {
         int nv;
         const uint16_t* p = v.chunk(o_base + oc * 8, r_base + rg * 4 + i, nv);
-        reg[i] = fetch<ALIGNED>(p, nv);
+        reg[i] = fetch<ALIGNED>(p, nv, v.base);
       }
     }
   }
@@ -1889,8 +1896,10 @@ bool try_launch_dma(hipStream_t s, const AView& A, const BView& B, bool aligned,
 #endif
     if (four) {
       hipLaunchKernelGGL(k64, dim3(grid), dim3(256), 4 * 32768, s, DmaMat{A.base, A.ld}, DmaMat{B.base, B.ld}, pb, ep);
-    } else if (ep.mode != 0 && depth32_f32 == 0) {
-      // FP32 outputs (store, accumulate, split partials; 16 bytes per lane, checked above) on the same kernel
+    } else if (ep.mode != 0 && depth32_f32 == 0 && pl.ktiles_per_split >= 8) {
+      // FP32 outputs (store, accumulate, split partials; 16 bytes per lane, checked above) on the same kernel, unless
+      // the reduction is short: over 4 stages k_gemm_dma's two wavefronts per SIMD cover the fill and the write-out of
+      // each other (projection weight gradient 8192 x 1024 x 256, accumulated: 24.5 us there, 28.4 us here)
       hipLaunchKernelGGL(k64f, dim3(grid), dim3(256), 4 * 32768, s, DmaMat{A.base, A.ld}, DmaMat{B.base, B.ld}, pb, ep);
     } else {
       hipLaunchKernelGGL(k4, dim3(grid), dim3(512), 4 * 32768, s, DmaMat{A.base, A.ld}, DmaMat{B.base, B.ld}, pb, ep);
