@@ -244,19 +244,27 @@ struct Epilogue {
 
 // FP16 bit pattern of a value > 0 (Inf included, NaN not).
 __device__ __forceinline__ bool half_bits_positive(uint32_t b) { return (uint16_t)((b & 0xFFFFu) - 1u) < 0x7C00u; }
-// Pointwise stage of an FP16 store: 4 consecutive outputs of row i starting at column j (n of them inside the matrix).
-__device__ __forceinline__ uint2v apply_act4(uint2v hb, const Epilogue& ep, int64_t i, int64_t j, int n) {
+// The mask values (act == 2) of 4 consecutive outputs of row i starting at column j, n of them inside the matrix
+// (n = 0: none, the mask's first element is read instead), packed like the outputs.  No branch around the loads, so a
+// caller can fetch the masks of a whole tile first and wait once: fetched one group at a time between the stores, each
+// group cost a memory round trip (16 of them made a 256 x 1024 masked store take 17 us).
+// `whole`: the caller has checked (uniformly) that every group is 4 wide or absent and 8-byte aligned, so one load
+// fetches it; element by element each wavefront instruction touches 32 rows for 2 bytes apiece, and the 64 of them that
+// a 128 x 128 tile needs took 8 us.
+__device__ __forceinline__ uint2v load_mask4(const Epilogue& ep, int64_t i, int64_t j, int n, bool whole) {
+  const uint16_t* m = n > 0 ? ep.mask + i * ep.ldmask + j : ep.mask;
+  if (whole) return *reinterpret_cast<const uint2v*>(m);
+  const int last = max(n, 1) - 1;
+  const uint32_t e0 = m[0], e1 = m[min(1, last)], e2 = m[min(2, last)], e3 = m[min(3, last)];
+  return uint2v{e0 | (e1 << 16), e2 | (e3 << 16)};
+}
+// Pointwise stage of an FP16 store: 4 consecutive outputs (packed in hb); mk = their mask values when act == 2.
+__device__ __forceinline__ uint2v apply_act4(uint2v hb, const Epilogue& ep, uint2v mk) {
   if (ep.act == 0) return hb;
   uint32_t keep = 0;
-  if (ep.act == 1) {
+  const uint2v src = ep.act == 1 ? hb : mk;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) keep |= (uint32_t)half_bits_positive(hb[e >> 1] >> ((e & 1) * 16)) << e;
-  } else {
-    const uint16_t* m = ep.mask + i * ep.ldmask + j;
-#pragma unroll
-    for (int e = 0; e < 4; ++e)
-      if (e < n) keep |= (uint32_t)half_bits_positive(m[e]) << e;
-  }
+  for (int e = 0; e < 4; ++e) keep |= (uint32_t)half_bits_positive(src[e >> 1] >> ((e & 1) * 16)) << e;
   hb[0] &= ((keep & 1u) ? 0x0000FFFFu : 0u) | ((keep & 2u) ? 0xFFFF0000u : 0u);
   hb[1] &= ((keep & 4u) ? 0x0000FFFFu : 0u) | ((keep & 8u) ? 0xFFFF0000u : 0u);
   return hb;
@@ -353,6 +361,32 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void k_gemm(AView A, BV
   TileLoader<AView, A_ALIGNED, BM, NT> la;
   TileLoader<BView, B_ALIGNED, BN, NT> lb;
 
+  // Mask values (act == 2) of the whole tile: fetched in one go - ahead of the first operand loads where the registers are there
+  // for it (the 256-thread tile), so that both round trips pass together; else before the first store.
+  constexpr bool kMasksEarly = NT == 256;
+  uint2v mk[FM][FN][4];
+#pragma unroll
+  for (int a = 0; a < FM; ++a)
+#pragma unroll
+    for (int b = 0; b < FN; ++b)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) mk[a][b][g] = uint2v{0u, 0u};
+  auto fetch_masks = [&]() {
+    if (!(ep.mode == 0 && ep.act == 2)) return;
+    const bool whole = (pb.J % 4) == 0 && (ep.ldmask % 4) == 0 && (reinterpret_cast<uintptr_t>(ep.mask) & 7) == 0;
+#pragma unroll
+    for (int a = 0; a < FM; ++a) {
+      const int i = i0 + wm * WM + a * 32 + (lane & 31);
+#pragma unroll
+      for (int b = 0; b < FN; ++b)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int j = j0 + wn * WN + b * 32 + g * 8 + ((lane >> 5) << 2);
+          mk[a][b][g] = load_mask4(ep, i, j, (i < pb.I && j < pb.J) ? min(4, pb.J - j) : 0, whole);
+        }
+    }
+  };
+  if constexpr (kMasksEarly) fetch_masks();
   if (kt_begin < kt_end) {
     la.load(A, i0, kt_begin * BK, t);
     lb.load(B, j0, kt_begin * BK, t);
@@ -400,6 +434,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void k_gemm(AView A, BV
   // ---- epilogue.  acc[a][b][v]: row i = lane%32, col j = 8*(v/4) + 4*(lane/32) + v%4 of the 32x32 block.
   bool bad = false;
   const int64_t split_off = (ep.mode == 3) ? (int64_t)sp * pb.I * pb.J : 0;
+  if constexpr (!kMasksEarly) fetch_masks();
 #pragma unroll
   for (int a = 0; a < FM; ++a) {
     const int i = i0 + wm * WM + a * 32 + (lane & 31);
@@ -418,7 +453,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void k_gemm(AView A, BV
           half4 h;
 #pragma unroll
           for (int e = 0; e < 4; ++e) h[e] = (_Float16)x[e];
-          const uint2v hb = apply_act4(__builtin_bit_cast(uint2v, h), ep, i, j, nj);
+          const uint2v hb = apply_act4(__builtin_bit_cast(uint2v, h), ep, mk[a][b][g]);
           if (ep.flag) {
 #pragma unroll
             for (int e = 0; e < 4; ++e) bad |= (e < nj) & half_bits_special(hb[e >> 1] >> ((e & 1) * 16));
@@ -756,7 +791,7 @@ __global__ __launch_bounds__(512) void k_gemm_dma(DmaMat A, DmaMat B, Problem pb
         half4 h;
 #pragma unroll
         for (int e = 0; e < 4; ++e) h[e] = (_Float16)acc[a][b][e];
-        const uint2v hb = apply_act4(__builtin_bit_cast(uint2v, h), ep, i, j, 4);
+        const uint2v hb = apply_act4(__builtin_bit_cast(uint2v, h), ep, ep.act == 2 ? load_mask4(ep, i, j, 4, false) : uint2v{0u, 0u});
         if (ep.flag) bad |= half_bits_special(hb[0]) | half_bits_special(hb[0] >> 16) | half_bits_special(hb[1]) | half_bits_special(hb[1] >> 16);
         uint16_t* o = reinterpret_cast<uint16_t*>(ep.out) + (int64_t)i * ep.ld + j;
         if ((reinterpret_cast<uintptr_t>(o) & 7) == 0) {
