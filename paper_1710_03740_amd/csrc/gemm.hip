@@ -1788,6 +1788,69 @@ __global__ __launch_bounds__(256) void k_split_reduce(const float* __restrict__ 
   }
 }
 
+// The same reduction four adjacent columns per thread, for outputs whose rows hold a whole number of such groups at
+// 16-byte (FP32) / 8-byte (FP16, mask) aligned addresses - the host checks that: 16 bytes per lane from each partial,
+// one 8- or 16-byte store.  Each element's additions are those of reduce_one, in the same order.
+__global__ __launch_bounds__(256) void k_split_reduce4(const float* __restrict__ part, int splits, int I, int J, Epilogue ep) {
+  const int64_t total = (int64_t)I * J, total4 = total >> 2;
+  const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  bool bad = false;
+  if (q < total4) {
+    const float4v* p4 = reinterpret_cast<const float4v*>(part);
+    float4v s = p4[q];
+    int k = 1;
+    for (; k + 8 <= splits; k += 8) {
+      float4v v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = p4[(int64_t)(k + u) * total4 + q];
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) s[e] = __fadd_rn(s[e], v[u][e]);
+    }
+    for (; k < splits; ++k) {
+      const float4v v = p4[(int64_t)k * total4 + q];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) s[e] = __fadd_rn(s[e], v[e]);
+    }
+    const int64_t idx = q << 2, i = idx / J, j = idx - i * J;
+    if (ep.mode == 0) {
+      half4 h;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) h[e] = (_Float16)s[e];
+      const uint2v mk = ep.act == 2 ? *reinterpret_cast<const uint2v*>(ep.mask + i * ep.ldmask + j) : uint2v{0u, 0u};
+      const uint2v hb = apply_act4(__builtin_bit_cast(uint2v, h), ep, mk);
+      bad = half_bits_special(hb[0]) | half_bits_special(hb[0] >> 16) | half_bits_special(hb[1]) | half_bits_special(hb[1] >> 16);
+      *reinterpret_cast<uint2v*>(reinterpret_cast<uint16_t*>(ep.out) + i * ep.ld + j) = hb;
+    } else {
+      float4v* o = reinterpret_cast<float4v*>(reinterpret_cast<float*>(ep.out) + i * ep.ld + j);
+      if (ep.mode == 2) {
+        const float4v old = *o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) s[e] = __fadd_rn(old[e], s[e]);
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) bad |= (__float_as_uint(s[e]) & 0x7F800000u) == 0x7F800000u;
+      *o = s;
+    }
+  }
+  if (ep.flag != nullptr) {
+    const unsigned long long vote = __builtin_amdgcn_ballot_w64(bad);
+    if (vote != 0ull && (threadIdx.x & 63) == 0) atomicOr(ep.flag, 1u);
+  }
+}
+
+// Launches the reduction of `splits` partial outputs [split][I][J] at `ws` into the final form `ep`.
+void launch_split_reduce(hipStream_t s, const void* ws, int splits, int I, int J, const Epilogue& ep) {
+  const int64_t total = (int64_t)I * J;
+  const bool out_ok = ep.mode == 0 ? ((ep.ld % 4) == 0 && mpt_aligned(ep.out, 8) && (ep.act != 2 || ((ep.ldmask % 4) == 0 && mpt_aligned(ep.mask, 8))))
+                                   : ((ep.ld % 4) == 0 && mpt_aligned(ep.out, 16));
+  if ((J % 4) == 0 && mpt_aligned(ws, 16) && out_ok)
+    hipLaunchKernelGGL(k_split_reduce4, dim3((unsigned)((total / 4 + 255) / 256)), dim3(256), 0, s, reinterpret_cast<const float*>(ws), splits, I, J, ep);
+  else
+    hipLaunchKernelGGL(k_split_reduce, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, reinterpret_cast<const float*>(ws), splits, I, J, ep);
+}
+
 // ---------------------------------------------------------------- host-side planning
 struct Plan {
   bool big;             // 256x256 tiles (8 wavefronts) or 128x128 (4 wavefronts)
@@ -2003,9 +2066,7 @@ int run(hipStream_t s, const AView& A, const BView& B, bool a_aligned, bool b_al
   if (ws != nullptr && plan_split128(I, J, R, p128) && ws_bytes >= plan_ws_bytes(p128, I, J) &&
       try_launch_split128(s, A, B, aligned, p128, I, J, R, reinterpret_cast<float*>(ws), st)) {
     if (st != MPT_OK) return st;
-    const int64_t total = (int64_t)I * J;
-    hipLaunchKernelGGL(k_split_reduce, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
-                       reinterpret_cast<const float*>(ws), p128.splits, I, J, ep);
+    launch_split_reduce(s, ws, p128.splits, I, J, ep);
     MPT_LAUNCH_CHECK();
     return MPT_OK;
   }
@@ -2020,9 +2081,7 @@ int run(hipStream_t s, const AView& A, const BView& B, bool a_aligned, bool b_al
                                 : launch_tiles<AView, BView, false, false>(s, A, B, pl, I, J, R, first));
   if (st != MPT_OK) return st;
   if (pl.splits > 1) {
-    const int64_t total = (int64_t)I * J;
-    hipLaunchKernelGGL(k_split_reduce, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
-                       reinterpret_cast<const float*>(ws), pl.splits, I, J, ep);
+    launch_split_reduce(s, ws, pl.splits, I, J, ep);
     MPT_LAUNCH_CHECK();
   }
   return MPT_OK;
@@ -2290,9 +2349,7 @@ bool try_launch_conv_wgrad_dma(hipStream_t s, const uint16_t* x, const uint16_t*
     first.out = ws; first.ld = J; first.mode = 3; first.flag = nullptr;
     hipLaunchKernelGGL(k, dim3(grid), dim3(256), 4 * 32768, s, DmaMat{dy, Kf}, B, pb, first);
     if (hipGetLastError() != hipSuccess) { status = MPT_ERR_HIP; return true; }
-    const int64_t total = Kf * J;
-    hipLaunchKernelGGL(k_split_reduce, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, reinterpret_cast<const float*>(ws), pl.splits,
-                       (int)Kf, (int)J, ep);
+    launch_split_reduce(s, ws, pl.splits, (int)Kf, (int)J, ep);
   } else {
     auto k = k_gemm_dma4<DmaOperand4<false, 256>, DmaImgOC, 256, false>;
     static bool once = ((void)hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, 4 * 32768), true);
