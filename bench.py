@@ -273,7 +273,7 @@ def measure_configs(torch, mpt, np, dev, workloads):
         mag = torch.exp2(torch.empty(shape, device=dev).uniform_(lo, hi)) * scale
         return (mag * (torch.randint(0, 2, shape, device=dev) * 2 - 1)).half()
 
-    # ---- cfg 1: the whole 2-layer MLP step, device only (13 launches; latency bound)
+    # ---- cfg 1: the whole 2-layer MLP step, device only (12 launches; latency bound)
     c = workloads.mlp()
     x, lab = d16(c["x"]), torch.from_numpy(c["labels"]).to(dev)
     w1_32, w2_32 = torch.from_numpy(c["w1_32"].copy()).to(dev), torch.from_numpy(c["w2_32"].copy()).to(dev)
@@ -291,11 +291,10 @@ def measure_configs(torch, mpt, np, dev, workloads):
         mpt.mpt_softmax_xent_scaled(logits, lab, S, dlog, L, R)
         mpt.mpt_gemm_wgrad(h1, dlog, dw2, flag=flag, ws=ws1); mpt.mpt_gemm_dgrad_relu(dlog, w2, h1, dy1, ws1)
         mpt.mpt_gemm_wgrad(x, dy1, dw1, flag=flag, ws=ws1)
-        mpt.mpt_master_update(w1_32, None, dw1, w1, inv, lr, 0.0, flag)
-        mpt.mpt_master_update(w2_32, None, dw2, w2, inv, lr, 0.0, flag)
+        mpt.mpt_master_update_multi(((w1_32, None, dw1, w1), (w2_32, None, dw2, w2)), inv, lr, 0.0, flag)
     t = timeit(mlp_step, reps=50)
     fl = 3 * 2.0 * 256 * (1024 * 1024 + 1024 * 10)
-    mfma_row("cfg1 MLP 256x1024 -> 1024 -> 10", "whole step: 2 fwd (ReLU folded), loss, 2 wgrad (+Inf/NaN vote), dgrad (mask folded), 2 master updates; split reductions through one workspace", fl, t)
+    mfma_row("cfg1 MLP 256x1024 -> 1024 -> 10", "whole step: 2 fwd (ReLU folded), loss, 2 wgrad (+Inf/NaN vote), dgrad (mask folded), both master updates in one launch; split reductions through one workspace", fl, t)
     # the same step with no host work between its launches: captured once, replayed (first use of every kernel is the
     # eager timing above, outside the capture)
     torch.cuda.synchronize()
@@ -303,7 +302,7 @@ def measure_configs(torch, mpt, np, dev, workloads):
     with torch.cuda.graph(graph):
         mlp_step()
     t = timeit(graph.replay, reps=50)
-    mfma_row("cfg1 MLP 256x1024 -> 1024 -> 10", "whole step replayed from a HIP graph (the 13 launches back to back, no host work between them)", fl, t)
+    mfma_row("cfg1 MLP 256x1024 -> 1024 -> 10", "whole step replayed from a HIP graph (the 12 launches back to back, no host work between them)", fl, t)
     del graph, x, w1, w2, w1_32, w2_32
 
     # ---- cfg 3: projected-LSTM layer products at batch 256 (per timestep), and the time-batched weight gradient

@@ -218,6 +218,30 @@ int mpt_master_update(void* stream, size_t n, float* w32_dev, float* m32_dev,
                       float lr, float momentum, const uint32_t* flag_dev);
 
 /* ------------------------------------------------------------------------- *
+ * mpt_master_update for many parameter tensors in as few launches as possible
+ * (Sec. 3.1: every layer's weights have an FP32 master copy; the update is one
+ * pass over all of them).  items_host[k] names tensor k's device buffers and
+ * its element count; every tensor gets exactly the update mpt_master_update
+ * would give it (same operations, same bits), with the same inv_scale /
+ * scaler_dev, lr, momentum and skip flag.  m32_dev: given for all tensors or
+ * for none (ARG otherwise).  Tensors with n = 0 are skipped; count = 0 is a
+ * legal no-op.  The array is read during the call and may be freed after it.
+ * Nothing is launched unless every item is valid.
+ * Errors: NULL, ARG, ALIGN (as mpt_master_update, per tensor), SHAPE (n > 2^40).
+ * ------------------------------------------------------------------------- */
+typedef struct mpt_update_item {
+  float* w32_dev;        /* FP32 master weights, updated in place */
+  float* m32_dev;        /* FP32 momentum, updated in place; NULL = plain SGD */
+  const void* grad_dev;  /* FP16 or FP32 gradient (grad_is_fp32 of the call) */
+  uint16_t* w16_dev;     /* FP16 working copy, overwritten */
+  size_t n;              /* elements */
+} mpt_update_item;
+
+int mpt_master_update_multi(void* stream, int count, const mpt_update_item* items_host, int grad_is_fp32,
+                            float inv_scale, const mpt_scaler* scaler_dev,
+                            float lr, float momentum, const uint32_t* flag_dev);
+
+/* ------------------------------------------------------------------------- *
  * The same step in ONE pass over the gradient (Sec. 3.2: the overflow test and
  * the unscaled update read the same values): 20 B per element with momentum
  * and an FP16 gradient instead of 2 + 20 for mpt_unscale_check followed by

@@ -36,6 +36,10 @@ class mpt_opt_params(ctypes.Structure):
                 ("clip_factor_dev", c_vp)]
 
 
+class mpt_update_item(ctypes.Structure):
+    _fields_ = [("w32_dev", c_vp), ("m32_dev", c_vp), ("grad_dev", c_vp), ("w16_dev", c_vp), ("n", c_sz)]
+
+
 OPT_KINDS = {"momentum": 0, "nesterov": 1, "adagrad": 2, "adam": 3}
 
 _GEMM = [c_vp, c_i64, c_i64, c_i64, c_vp, c_i64, c_vp, c_i64, c_vp, c_i64, c_vp, c_sz]
@@ -61,6 +65,7 @@ SIGNATURES = {
     "mpt_master_update": (c_i, [c_vp, c_sz, c_vp, c_vp, c_vp, c_i, c_vp, c_f, c_vp, c_f, c_f, c_vp]),
     "mpt_probe_mfma": (c_i, [c_vp, c_i, c_i, c_vp]),
     "mpt_master_update_fused": (c_i, [c_vp, c_sz, c_vp, c_vp, c_vp, c_i, c_vp, c_vp, c_vp, c_f, c_vp, c_f, c_f, c_vp]),
+    "mpt_master_update_multi": (c_i, [c_vp, c_i, c_vp, c_i, c_f, c_vp, c_f, c_f, c_vp]),
     "mpt_add_fp16": (c_i, [c_vp, c_sz, c_vp, c_vp, c_vp]),
     "mpt_relu_fwd": (c_i, [c_vp, c_sz, c_vp, c_vp]),
     "mpt_relu_bwd": (c_i, [c_vp, c_sz, c_vp, c_vp, c_vp]),
@@ -344,6 +349,28 @@ def mpt_master_update(w32, m32, grad, w16, inv_scale, lr, momentum, flag=None, s
     _check("mpt_master_update", lib().mpt_master_update(_stream(), w32.numel(), _p(w32), _p(m32), _p(grad),
                                                         1 if grad.dtype == torch.float32 else 0, _p(w16),
                                                         inv_scale, _p(scaler_dev), lr, momentum, _p(flag)))
+
+
+def mpt_master_update_multi(tensors, inv_scale, lr, momentum, flag=None, scaler_dev=None):
+    """tensors: a sequence of (w32, m32 or None, grad, w16) device tensors, one entry per parameter tensor; the gradients
+    share one dtype and the momentum buffers are given for all entries or for none."""
+    tensors = list(tensors)
+    if not tensors:
+        return
+    gdt = tensors[0][2].dtype if tensors[0][2] is not None else None
+    items = (mpt_update_item * len(tensors))()
+    for k, (w32, m32, grad, w16) in enumerate(tensors):
+        n = _update_buffers(w32, [("m32", m32)], grad, w16, flag, scaler_dev)
+        if grad.dtype != gdt:
+            raise TypeError("tensors[%d]: gradient dtype %s differs from the first entry's %s" % (k, grad.dtype, gdt))
+        if (m32 is None) != (tensors[0][1] is None):
+            raise ValueError("tensors[%d]: momentum buffers for all entries or for none" % k)
+        _dev(w32, m32, grad, w16)
+        items[k].w32_dev, items[k].m32_dev, items[k].grad_dev, items[k].w16_dev, items[k].n = _p(w32), _p(m32), _p(grad), _p(w16), n
+    _dev(flag, scaler_dev)
+    _check("mpt_master_update_multi", lib().mpt_master_update_multi(_stream(), len(tensors), ctypes.cast(items, c_vp),
+                                                                    1 if gdt == torch.float32 else 0, inv_scale, _p(scaler_dev),
+                                                                    lr, momentum, _p(flag)))
 
 
 def mpt_master_update_fused(w32_in, m32_in, grad, w32_out, m32_out, w16_out, inv_scale, lr, momentum, flag, scaler_dev=None):

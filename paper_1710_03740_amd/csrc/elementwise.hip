@@ -207,6 +207,99 @@ __global__ __launch_bounds__(kThreads) void k_master_update_scalar(
   }
 }
 
+// Many parameter tensors in one launch (a network's layers each own a weight, a master copy and a momentum buffer;
+// a launch per tensor costs more than the update of a small one).  The tensors' pointers and sizes travel in the
+// kernel's arguments; a workgroup finds its tensor by walking the table of first workgroups (wavefront-uniform) and
+// then does what k_master_update / k_master_update_scalar do for that tensor: pairs where the tensor's buffers are
+// aligned for them, single elements else, one trip per thread.  Same operations, same results.
+constexpr int kMultiMax = 48;
+struct MultiItems {
+  float* w32[kMultiMax];
+  float* m32[kMultiMax];
+  const void* grad[kMultiMax];
+  uint16_t* w16[kMultiMax];
+  unsigned long long n[kMultiMax];
+  unsigned first_block[kMultiMax + 1];     // workgroups [first_block[k], first_block[k + 1]) belong to tensor k
+  unsigned pairs_mask_lo, pairs_mask_hi;   // bit k: tensor k moves in pairs
+  int count;
+};
+
+template <bool MOM, bool G32>
+__global__ __launch_bounds__(kThreads) void k_master_update_multi(MultiItems it, float inv_scale, const mpt_scaler* __restrict__ scaler,
+                                                                 float lr, float mu, const uint32_t* __restrict__ flag) {
+  int k = 0;
+  while (k + 1 < it.count && blockIdx.x >= it.first_block[k + 1]) ++k;
+  const size_t n = (size_t)it.n[k];
+  float* w32 = it.w32[k];
+  float* m32 = it.m32[k];
+  const void* grad = it.grad[k];
+  uint16_t* w16 = it.w16[k];
+  const bool pairs = ((k < 32 ? it.pairs_mask_lo >> k : it.pairs_mask_hi >> (k - 32)) & 1u) != 0u;
+  const size_t local = (size_t)(blockIdx.x - it.first_block[k]) * kThreads + threadIdx.x;
+  if (pairs) {
+    const size_t q = local;
+    const bool tail = (n & 1) && local == 0;                 // the odd last element goes with the tensor's first thread
+    if (q >= (n >> 1) && !tail) return;
+    float g[2] = {0.f, 0.f};
+    f2 w = {0, 0}, m = {0, 0};
+    f2* wp = reinterpret_cast<f2*>(w32) + q;
+    f2* mp = MOM ? reinterpret_cast<f2*>(m32) + q : nullptr;
+    const bool has_pair = q < (n >> 1);
+    if (has_pair) {
+      if constexpr (G32) {
+        const f2 a = reinterpret_cast<const f2*>(grad)[q];
+        g[0] = a[0]; g[1] = a[1];
+      } else {
+        const h2 a = reinterpret_cast<const h2*>(grad)[q];
+        g[0] = (float)a[0]; g[1] = (float)a[1];
+      }
+      w = *wp;
+      if constexpr (MOM) m = *mp;
+    }
+    if (flag != nullptr && *flag != 0u) return;             // overflow: the whole step is a no-op
+    const float inv = scaler != nullptr ? scaler->inv_scale : inv_scale;
+    if (has_pair) {
+      h2 h;
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        float mi = m[i];
+        w[i] = step1<MOM>(w[i], mi, g[i], inv, lr, mu);
+        m[i] = mi;
+        h[i] = (_Float16)w[i];
+      }
+      *wp = w;
+      if constexpr (MOM) *mp = m;
+      reinterpret_cast<h2*>(w16)[q] = h;
+    }
+    if (tail) {
+      const size_t i = n - 1;
+      float graw;
+      if constexpr (G32) graw = reinterpret_cast<const float*>(grad)[i];
+      else graw = (float)reinterpret_cast<const _Float16*>(grad)[i];
+      float mm = 0.f;
+      if constexpr (MOM) mm = m32[i];
+      const float wn = step1<MOM>(w32[i], mm, graw, inv, lr, mu);
+      w32[i] = wn;
+      if constexpr (MOM) m32[i] = mm;
+      reinterpret_cast<_Float16*>(w16)[i] = (_Float16)wn;
+    }
+  } else {
+    const size_t i = local;
+    if (i >= n) return;
+    if (flag != nullptr && *flag != 0u) return;
+    const float inv = scaler != nullptr ? scaler->inv_scale : inv_scale;
+    float graw;
+    if constexpr (G32) graw = reinterpret_cast<const float*>(grad)[i];
+    else graw = (float)reinterpret_cast<const _Float16*>(grad)[i];
+    float mm = 0.f;
+    if constexpr (MOM) mm = m32[i];
+    const float wn = step1<MOM>(w32[i], mm, graw, inv, lr, mu);
+    w32[i] = wn;
+    if constexpr (MOM) m32[i] = mm;
+    reinterpret_cast<_Float16*>(w16)[i] = (_Float16)wn;
+  }
+}
+
 // Inf/NaN scan (+ optional FP32 unscaled copy).  The exponent-field test runs on
 // the stored bits; each wavefront votes and at most one lane per wavefront
 // touches the flag.
@@ -674,6 +767,66 @@ extern "C" int mpt_master_update(void* stream, size_t n, float* w32, float* m32,
   }
   MPT_LAUNCH_CHECK();
   return MPT_OK;
+}
+
+extern "C" int mpt_master_update_multi(void* stream, int count, const mpt_update_item* items, int grad_is_fp32, float inv_scale,
+                                       const mpt_scaler* scaler, float lr, float momentum, const uint32_t* flag) {
+  if (count == 0) return MPT_OK;
+  if (count < 0) return MPT_ERR_ARG;
+  if (items == nullptr) return MPT_ERR_NULL;
+  if (!mpt_finite(lr) || !mpt_finite(momentum)) return MPT_ERR_ARG;
+  if (scaler == nullptr && (!mpt_finite(inv_scale) || !(inv_scale > 0.f))) return MPT_ERR_ARG;
+  if ((flag && !mpt_aligned(flag, 4)) || (scaler && !mpt_aligned(scaler, 4))) return MPT_ERR_ALIGN;
+  const size_t gsz = grad_is_fp32 ? 4 : 2;
+  int with_mom = 0, live = 0;
+  for (int k = 0; k < count; ++k) {          // everything is validated before anything is launched
+    const mpt_update_item& t = items[k];
+    if (t.n == 0) continue;
+    if (t.w32_dev == nullptr || t.grad_dev == nullptr || t.w16_dev == nullptr) return MPT_ERR_NULL;
+    if (!mpt_aligned(t.w32_dev, 4) || (t.m32_dev && !mpt_aligned(t.m32_dev, 4)) || !mpt_aligned(t.grad_dev, gsz) || !mpt_aligned(t.w16_dev, 2))
+      return MPT_ERR_ALIGN;
+    if (t.n > ((size_t)1 << 40)) return MPT_ERR_SHAPE;
+    ++live;
+    with_mom += t.m32_dev != nullptr;
+  }
+  if (live == 0) return MPT_OK;
+  if (with_mom != 0 && with_mom != live) return MPT_ERR_ARG;      // momentum buffers for all tensors or for none
+  const bool mom = with_mom != 0, g32 = grad_is_fp32 != 0;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  MultiItems it;
+  auto flush = [&](int filled) -> int {
+    if (filled == 0) return MPT_OK;
+    it.count = filled;
+    const unsigned grid = it.first_block[filled];
+#define MPT_MM(M, G) hipLaunchKernelGGL((k_master_update_multi<M, G>), dim3(grid), dim3(kThreads), 0, s, it, inv_scale, scaler, lr, momentum, flag)
+    if (mom) { if (g32) MPT_MM(true, true); else MPT_MM(true, false); }
+    else     { if (g32) MPT_MM(false, true); else MPT_MM(false, false); }
+#undef MPT_MM
+    MPT_LAUNCH_CHECK();
+    return MPT_OK;
+  };
+  int filled = 0;
+  it.first_block[0] = 0; it.pairs_mask_lo = it.pairs_mask_hi = 0;
+  for (int k = 0; k < count; ++k) {
+    const mpt_update_item& t = items[k];
+    if (t.n == 0) continue;
+    const bool pairs = mpt_aligned(t.w32_dev, 8) && (t.m32_dev == nullptr || mpt_aligned(t.m32_dev, 8)) &&
+                       mpt_aligned(t.grad_dev, g32 ? 8 : 4) && mpt_aligned(t.w16_dev, 4);
+    const size_t units = pairs ? (t.n + 1) / 2 : t.n;
+    const size_t blocks = (units + kThreads - 1) / kThreads;
+    if (filled == kMultiMax || (size_t)it.first_block[filled] + blocks > 0x7FFFFFFFu) {
+      const int st = flush(filled);
+      if (st != MPT_OK) return st;
+      filled = 0; it.first_block[0] = 0; it.pairs_mask_lo = it.pairs_mask_hi = 0;
+    }
+    if (blocks > 0x7FFFFFFFu) return MPT_ERR_SHAPE;
+    it.w32[filled] = t.w32_dev; it.m32[filled] = t.m32_dev; it.grad[filled] = t.grad_dev; it.w16[filled] = t.w16_dev;
+    it.n[filled] = (unsigned long long)t.n;
+    it.first_block[filled + 1] = it.first_block[filled] + (unsigned)blocks;
+    if (pairs) { if (filled < 32) it.pairs_mask_lo |= 1u << filled; else it.pairs_mask_hi |= 1u << (filled - 32); }
+    ++filled;
+  }
+  return flush(filled);
 }
 
 extern "C" int mpt_master_update_fused(void* stream, size_t n, const float* w_in, const float* m_in, const void* grad, int grad_is_fp32,

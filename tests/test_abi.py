@@ -129,6 +129,23 @@ def test_argument_errors_before_any_launch(L):
     assert L.mpt_master_update_fused(Z, 8, P, Z, P, 0, Q, Z, Q, 0.0, Z, 0.1, 0.9, P) == -5
     assert L.mpt_master_update_fused(Z, 8, P, Z, P, 0, ctypes.c_void_p(0x200002), Z, Q, 1.0, Z, 0.1, 0.9, P) == -3
     assert L.mpt_master_update_fused(Z, 0, Z, Z, Z, 0, Z, Z, Z, 1.0, Z, 0.1, 0.9, Z) == 0
+    class Item(ctypes.Structure):
+        _fields_ = [("w32", ctypes.c_void_p), ("m32", ctypes.c_void_p), ("grad", ctypes.c_void_p), ("w16", ctypes.c_void_p), ("n", ctypes.c_size_t)]
+    items = (Item * 2)(Item(P.value, None, P.value, P.value, 8), Item(Q.value, None, Q.value, Q.value, 8))
+    ip = ctypes.cast(items, ctypes.c_void_p)
+    assert L.mpt_master_update_multi(Z, 0, Z, 0, 1.0, Z, 0.1, 0.9, Z) == 0                   # no tensors: no-op
+    assert L.mpt_master_update_multi(Z, -1, ip, 0, 1.0, Z, 0.1, 0.9, Z) == -5
+    assert L.mpt_master_update_multi(Z, 2, Z, 0, 1.0, Z, 0.1, 0.9, Z) == -1
+    assert L.mpt_master_update_multi(Z, 2, ip, 0, 0.0, Z, 0.1, 0.9, Z) == -5
+    assert L.mpt_master_update_multi(Z, 2, ip, 0, 1.0, Z, float("inf"), 0.9, Z) == -5
+    items[1].w16 = None
+    assert L.mpt_master_update_multi(Z, 2, ip, 0, 1.0, Z, 0.1, 0.9, Z) == -1                 # the second tensor lacks a buffer: nothing is launched
+    items[1].w16 = Q.value; items[1].m32 = Q.value
+    assert L.mpt_master_update_multi(Z, 2, ip, 0, 1.0, Z, 0.1, 0.9, Z) == -5                 # momentum for one tensor only
+    items[1].m32 = None; items[1].grad = 0x200001
+    assert L.mpt_master_update_multi(Z, 2, ip, 0, 1.0, Z, 0.1, 0.9, Z) == -3
+    items[0].n = 0; items[1].n = 0; items[1].grad = None
+    assert L.mpt_master_update_multi(Z, 2, ip, 0, 1.0, Z, 0.1, 0.9, Z) == 0                  # empty tensors are skipped, whatever their pointers
     assert L.mpt_probe_mfma(Z, 10, 0, Z) == -1
     assert L.mpt_probe_mfma(Z, 0, 0, P) == -5
     assert L.mpt_loss_scale_update_dev(Z, Z, P) == -1

@@ -322,3 +322,44 @@ def test_flat_update_200_steps_full_size_sampled():
             assert np.array_equal(host(d_m[d_idx]).view(np.uint32), m.view(np.uint32)), t
             assert np.array_equal(fp16.bits(host16(d_h[d_idx])), fp16.bits(h)), t
     assert skipped == 8 and osc.scale == f.scale0 / 2 ** 8
+
+
+@pytest.mark.parametrize("fp32_grads,with_momentum", [(False, True), (False, False), (True, True)])
+def test_many_tensors_in_one_call(fp32_grads, with_momentum):
+    """mpt_master_update_multi over 60 parameter tensors (more than one launch's table holds) of sizes from 1 element to
+    300 000, some of them views at odd element offsets (no pair alignment): every tensor must come out exactly as the
+    oracle's update of that tensor alone, over two steps, and a raised flag must leave every bit of every tensor alone."""
+    rng = np.random.default_rng(11 + 2 * fp32_grads + with_momentum)
+    sizes = [1, 2, 3, 7, 255, 256, 257, 511, 513, 1000, 4097, 65536, 300000] + [int(x) for x in rng.integers(1, 5000, 47)]
+    offs = [int(x) for x in rng.integers(0, 2, len(sizes))]                      # 1: the view starts one element into its buffer
+    lr, mu, inv = 0.05, 0.9 if with_momentum else 0.0, float(F32(1.0 / 1024.0))
+    w, m, g, h, d = [], [], [], [], []
+    for n, o in zip(sizes, offs):
+        w.append((rng.standard_normal(n) * 0.1).astype(F32))
+        m.append((rng.standard_normal(n) * 0.01).astype(F32) if with_momentum else None)
+        gr = _rand_grads(rng, n, -12, 6)
+        g.append(gr.astype(F32) if fp32_grads else gr)
+        bw = torch.zeros(n + o, dtype=torch.float32, device="cuda"); bw[o:] = dev(w[-1])
+        bm = None
+        if with_momentum:
+            bm = torch.zeros(n + o, dtype=torch.float32, device="cuda"); bm[o:] = dev(m[-1])
+        bg = torch.zeros(n + o, dtype=torch.float32 if fp32_grads else torch.float16, device="cuda"); bg[o:] = dev(g[-1])
+        bh = torch.zeros(n + o, dtype=torch.float16, device="cuda")
+        d.append((bw[o:], bm[o:] if with_momentum else None, bg[o:], bh[o:]))
+    flag = _flag()
+    for step in range(2):
+        mpt.mpt_master_update_multi(d, inv, lr, mu, flag)
+        for k in range(len(sizes)):
+            w[k], mk, hk = update.master_update(w[k], m[k], g[k], inv, lr, mu, 0)
+            if with_momentum:
+                m[k] = mk
+            assert np.array_equal(host(d[k][0]).view(np.uint32), w[k].view(np.uint32)), (step, k, sizes[k])
+            if with_momentum:
+                assert np.array_equal(host(d[k][1]).view(np.uint32), m[k].view(np.uint32)), (step, k, sizes[k])
+            assert np.array_equal(fp16.bits(host16(d[k][3])), fp16.bits(hk)), (step, k, sizes[k])
+    flag.fill_(1)
+    mpt.mpt_master_update_multi(d, inv, lr, mu, flag)
+    for k in range(len(sizes)):
+        assert np.array_equal(host(d[k][0]).view(np.uint32), w[k].view(np.uint32)), ("skipped", k)
+        if with_momentum:
+            assert np.array_equal(host(d[k][1]).view(np.uint32), m[k].view(np.uint32)), ("skipped", k)
