@@ -359,14 +359,16 @@ def mpt_master_update_multi(tensors, inv_scale, lr, momentum, flag=None, scaler_
         return
     gdt = tensors[0][2].dtype if tensors[0][2] is not None else None
     items = (mpt_update_item * len(tensors))()
-    for k, (w32, m32, grad, w16) in enumerate(tensors):
-        n = _update_buffers(w32, [("m32", m32)], grad, w16, flag, scaler_dev)
+    counts = []
+    for k, (w32, m32, grad, w16) in enumerate(tensors):          # every entry is checked before the device check
+        counts.append(_update_buffers(w32, [("m32", m32)], grad, w16, flag, scaler_dev))
         if grad.dtype != gdt:
             raise TypeError("tensors[%d]: gradient dtype %s differs from the first entry's %s" % (k, grad.dtype, gdt))
         if (m32 is None) != (tensors[0][1] is None):
             raise ValueError("tensors[%d]: momentum buffers for all entries or for none" % k)
+    for k, (w32, m32, grad, w16) in enumerate(tensors):
         _dev(w32, m32, grad, w16)
-        items[k].w32_dev, items[k].m32_dev, items[k].grad_dev, items[k].w16_dev, items[k].n = _p(w32), _p(m32), _p(grad), _p(w16), n
+        items[k].w32_dev, items[k].m32_dev, items[k].grad_dev, items[k].w16_dev, items[k].n = _p(w32), _p(m32), _p(grad), _p(w16), counts[k]
     _dev(flag, scaler_dev)
     _check("mpt_master_update_multi", lib().mpt_master_update_multi(_stream(), len(tensors), ctypes.cast(items, c_vp),
                                                                     1 if gdt == torch.float32 else 0, inv_scale, _p(scaler_dev),

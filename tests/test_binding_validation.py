@@ -127,3 +127,13 @@ def test_glue_norm_and_lstm_shapes():
     reaches_device_check(mpt.mpt_lstm_cell_bwd, h(B, H), None, h(B, 4 * H), h(B, H), h(B, H), h(B, 4 * H), h(B, H))
     rejected("da: shape", mpt.mpt_lstm_cell_bwd, h(B, H), None, h(B, 4 * H), h(B, H), h(B, H), h(B, H), h(B, H))
     rejected("dc_next: shape", mpt.mpt_lstm_cell_bwd, h(B, H), h(B, 2 * H), h(B, 4 * H), h(B, H), h(B, H), h(B, 4 * H), h(B, H))
+
+
+def test_many_tensor_update_entries_are_checked_one_by_one():
+    good = (f(8), f(8), h(8), h(8))
+    reaches_device_check(mpt.mpt_master_update_multi, [good, (f(5), f(5), h(5), h(5))], 1.0, 0.1, 0.9)
+    mpt.mpt_master_update_multi([], 1.0, 0.1, 0.9)                                                   # nothing to do
+    rejected("grad: 4 elements", mpt.mpt_master_update_multi, [good, (f(5), f(5), h(4), h(5))], 1.0, 0.1, 0.9)       # a short gradient
+    rejected("momentum buffers", mpt.mpt_master_update_multi, [good, (f(5), None, h(5), h(5))], 1.0, 0.1, 0.9)
+    with pytest.raises(TypeError, match="gradient dtype"):
+        mpt.mpt_master_update_multi([good, (f(5), f(5), f(5), h(5))], 1.0, 0.1, 0.9)
