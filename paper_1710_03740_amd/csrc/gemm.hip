@@ -1908,11 +1908,14 @@ size_t plan_ws_bytes(const Plan& p, int64_t I, int64_t J) {
 // (256-row tiles would compute a padded half tile: 128 x 4096 x 4096 forward 27.5 -> 18.8 us) and whose time the memory
 // traffic decides: few tiles and an arithmetic intensity (every operand and the result once) below the ridge of
 // 2.5 PFLOP/s / 8 TB/s.  (For row counts that are multiples of 256 it measured within 2 % of the 256-row plans either
-// way - gate input gradient 55.8 against 55.5 us, projection 22.7 against 23.2 - and is not used.)  Depends on the shape
-// only, so that the workspace size can be asked for beforehand.
+// way - gate input gradient 55.8 against 55.5 us, projection 22.7 against 23.2 - and is used only as noted below.)
+// Depends on the shape only, so that the workspace size can be asked for beforehand.
 bool plan_split128(int64_t I, int64_t J, int64_t R, Plan& p) {
-  if ((I % 256) != 128 || (J % 256) || (R % 64)) return false;
+  if ((I % 128) || (J % 256) || (R % 64)) return false;
   const int64_t t128 = (I / 128) * (J / 256), kt = R / 64;
+  // rows a multiple of 256: only the smallest outputs over the longest reductions, where 256-row tiles would need 64
+  // splits (256 x 1024 over 32768: 40.5 -> 34.1 us; 256 x 2048 over 32768 is 3 us slower this way, over 8192 the same)
+  if ((I % 256) == 0 && !(t128 <= 8 && kt / 8 >= kCUs / t128)) return false;
   if (t128 >= kCUs * 3 / 4) return false;
   int64_t splits = kCUs / t128;
   if (splits > kt / 8) splits = kt / 8;                               // at least 8 stages of 64 per workgroup

@@ -470,6 +470,21 @@ def test_odd_multiple_of_128_rows_with_a_split_reduction():
     assert np.isinf(got).all() and int(flag.item()) == 1
 
 
+def test_smallest_outputs_over_the_longest_reductions():
+    """256 x 1024 outputs over a reduction of 32768 (the recurrent input gradient of the projected-LSTM layer at its own
+    size): 128 x 256 tiles, 32 splits.  Input-gradient and forward layouts."""
+    rng = np.random.default_rng(5)
+    M, N, K = 256, 32768, 1024
+    dY = (np.exp2(rng.uniform(-20, -3, (M, N))) * rng.choice([-1, 1], (M, N))).astype(np.float16)
+    W = (rng.standard_normal((K, N)) * 0.05).astype(np.float16)
+    dx, sa, s_ = gemm.gemm_dgrad(dY, W, full=True)
+    gemm_check(run_dgrad(dY, W, split=True), dx, sa, s_, "dgrad 256x1024 over 32768")
+    X = rng.standard_normal((M, N)).astype(np.float16)
+    Wf = (rng.standard_normal((N, K)) * 0.02).astype(np.float16)
+    y, sa, s_ = gemm.gemm_fwd(X, Wf, full=True)
+    gemm_check(run_fwd(X, Wf, split=True), y, sa, s_, "fwd 256x1024 over 32768")
+
+
 @pytest.mark.parametrize("M,N,K", [(256, 1024, 1024), (256, 10, 1024), (100, 72, 2048), (512, 384, 4096), (256, 1024, 8192), (384, 768, 8192)])
 def test_split_reduction_adds_every_partial_in_split_order(M, N, K):
     """Few output tiles and a long reduction: the launcher splits the reduction and a second pass adds the FP32 partials
