@@ -2064,11 +2064,14 @@ int run(hipStream_t s, const AView& A, const BView& B, bool a_aligned, bool b_al
   const Plan pl = make_plan(I, J, R, ws != nullptr);
   if (ws != nullptr && ws_bytes < plan_ws_bytes(pl, I, J)) return MPT_ERR_WORKSPACE;
   int st = MPT_OK;
-  // Few 256-row tiles but many 128 x 256 ones: the unsplit 128-row launch, unless a workspace is there and splitting the
-  // reduction over 256-row tiles occupies at least a quarter more CUs (time-batched products of a recurrent layer:
-  // 5120 x 1024 over 32768 has 160 tiles of 128 rows, but 80 x 3 of 256: 613 -> 318 us; over 8192: 99 -> 82 us).
+  // Few 256-row tiles but many 128 x 256 ones: the unsplit 128-row launch, unless a workspace is there, the reduction is
+  // long and splitting it over 256-row tiles occupies at least a quarter more CUs (time-batched products of a recurrent
+  // layer: 5120 x 1024 over 32768 has 160 tiles of 128 rows, but 80 x 3 of 256: 613 -> 318 us; over 8192: 99 -> 82 us).
+  // The split writes and reads back 67 MB of partials whatever the shape, about 20 us: below a reduction length of 8192
+  // that costs more than the idle CUs do (2048 x 2048 over 1024: 16 us unsplit, 33 us split; over 4096: 47 us either way;
+  // over 8192: 88 against 70 us).
   const int64_t t128 = (int64_t)(I / 128) * (J / 256);
-  const bool rather_split = ws != nullptr && pl.big && pl.splits > 1 && (int64_t)pl.tiles_i * pl.tiles_j * pl.splits * 4 >= t128 * 5;
+  const bool rather_split = ws != nullptr && pl.big && pl.splits > 1 && R >= 8192 && (int64_t)pl.tiles_i * pl.tiles_j * pl.splits * 4 >= t128 * 5;
   if (!rather_split && try_launch_dma128(s, A, B, aligned, I, J, R, ep, st)) return st;
   Plan p128;
   if (ws != nullptr && plan_split128(I, J, R, p128) && ws_bytes >= plan_ws_bytes(p128, I, J) &&
