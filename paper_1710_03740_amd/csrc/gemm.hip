@@ -2,15 +2,17 @@
 // (paper Sec. 3.3), for the three passes of a layer (Sec. 3.1 / Fig. 1) and for
 // the 3x3 convolution as an implicit GEMM.  gfx950 only.
 //
-// Three kernels compute C[i,j] = sum_r A(i,r) * B(r,j):
-//   k_gemm       the general one: any shape, alignment and operand view (plain matrices, gathered image windows,
-//                filter slices), FP16 / FP32 / accumulating stores, split partials;
-//   k_gemm_dma4  whole 256 x 256 (or 128 x 256) tiles of aligned operands - plain matrices, or the convolution's gathered
-//                image and filter - with an FP16 store (or, for the convolution's weight gradient, FP32 split partials):
-//                operands streamed global -> LDS, one wavefront per SIMD;
-//   k_gemm_dma   the same streaming with two wavefronts per SIMD, for FP32 outputs of plain matrices (store, accumulate,
-//                split partials) and odd output strides.
-// k_gemm_dma4 is the one the square 4096^3 workload runs on.
+// Four kernels compute C[i,j] = sum_r A(i,r) * B(r,j):
+//   k_gemm        the general one: any shape, alignment and operand view (plain matrices, gathered image windows,
+//                 filter slices), FP16 / FP32 / accumulating stores, split partials;
+//   k_gemm_dma64  whole 256 x 256 tiles of aligned operands - plain matrices, or the convolution's gathered image and
+//                 filter - streamed global -> LDS in stages of reduction depth 64, one wavefront per SIMD; FP16 store,
+//                 or (second instance) FP32 store / accumulate / split partials.  The square 4096^3 workload runs here;
+//   k_gemm_dma4   the same in stages of depth 32: 128 x 256 tiles (few-row outputs, split or not) and the convolution's
+//                 weight gradient with its per-tap gathered operand;
+//   k_gemm_dma    depth 32 with two wavefronts per SIMD: FP16 outputs with odd row strides, FP32 outputs over short
+//                 reductions.
+// k_split_reduce / k_split_reduce4 add split partials in split order.
 //
 // k_gemm works on a BM x BN tile per workgroup with v_mfma_f32_32x32x16_f16.  Operands differ only in how a
 // tile is fetched:
@@ -1094,7 +1096,7 @@ __device__ __forceinline__ void wait_frags9(half8& f, half8 (&g)[8]) {
 
 // F32OUT selects the epilogue at compile time (both in one kernel spill): false = FP16 store through LDS; true = FP32
 // store, accumulate or split partial straight from the accumulators, 16 bytes per lane (used for the convolution's
-// weight gradient, a long split reduction; on short ones k_gemm_dma's two wavefronts per SIMD are faster).
+// weight gradient and for split reductions over 128-row tiles).
 template <class AOp, class BOp, int BM, bool F32OUT = false>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_gemm_dma4(typename AOp::Src A, typename BOp::Src B, Problem pb, Epilogue ep) {
   constexpr bool A_RC = AOp::kRC, B_RC = BOp::kRC;
