@@ -193,3 +193,24 @@ def test_lstm_cell_argument_errors(L):
     b.argtypes = [ctypes.c_void_p, i64, i64] + [ctypes.c_void_p, i64] * 7
     assert b(Z, 4, 8, Z, 8, Z, 0, P, 32, P, 8, P, 8, P, 32, P, 8) == -1
     assert b(Z, 4, 8, P, 8, Z, 0, P, 32, P, 8, P, 8, P, 16, P, 8) == -2
+
+
+def test_workspace_size_is_a_whole_number_of_partial_outputs(L):
+    """mpt_gemm_workspace_bytes depends on the shape only and always asks for a whole number (0, or 2 to 64) of FP32
+    partial outputs [I][J], whichever way of splitting the library would pick; an invalid shape or pass asks for 0."""
+    L.mpt_gemm_workspace_bytes.restype = ctypes.c_size_t
+    L.mpt_gemm_workspace_bytes.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64]
+    shapes = [(1, 1, 1), (256, 10, 1024), (256, 1024, 1024), (256, 1024, 8192), (256, 32768, 2048), (256, 32768, 1024), (128, 4096, 4160),
+              (384, 768, 8192), (4096, 4096, 4096), (2048, 2048, 1024), (5120, 32768, 1024), (1000, 520, 776), (100, 72, 2048)]
+    for (M, N, K) in shapes:
+        for op, (I, J) in ((0, (M, N)), (1, (M, K)), (2, (K, N))):
+            b = L.mpt_gemm_workspace_bytes(op, M, N, K)
+            assert b % (I * J * 4) == 0, (op, M, N, K, b)
+            assert b // (I * J * 4) in [0] + list(range(2, 65)), (op, M, N, K, b)
+            assert b == L.mpt_gemm_workspace_bytes(op, M, N, K)
+    assert L.mpt_gemm_workspace_bytes(0, 4096, 4096, 4096) == 0                      # 256 tiles: nothing to split
+    # the larger of the plans' needs: 64 splits of 256-row tiles (taken when the operands are not aligned for the streamed
+    # kernel), although aligned operands run as 128-row tiles with 32 splits
+    assert L.mpt_gemm_workspace_bytes(1, 256, 32768, 1024) == 64 * 256 * 1024 * 4
+    assert L.mpt_gemm_workspace_bytes(3, 256, 256, 256) == 0
+    assert L.mpt_gemm_workspace_bytes(0, 0, 256, 256) == 0
