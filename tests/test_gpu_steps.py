@@ -152,8 +152,7 @@ def test_cfg1_mlp_step_replayed_from_a_hip_graph():
         mpt.mpt_softmax_xent_scaled(logits, lab, S, dlog, L, R)
         mpt.mpt_gemm_wgrad(h1, dlog, dw2, flag=flag, ws=ws); mpt.mpt_gemm_dgrad_relu(dlog, w2, h1, dy1, ws)
         mpt.mpt_gemm_wgrad(x, dy1, dw1, flag=flag, ws=ws)
-        mpt.mpt_master_update(w1_32, None, dw1, w1, inv, lr, 0.0, flag)
-        mpt.mpt_master_update(w2_32, None, dw2, w2, inv, lr, 0.0, flag)
+        mpt.mpt_master_update_multi(((w1_32, None, dw1, w1), (w2_32, None, dw2, w2)), inv, lr, 0.0, flag)   # both layers, one launch
 
     def reset():
         w1_32.copy_(dev(c["w1_32"].copy())); w2_32.copy_(dev(c["w2_32"].copy()))
