@@ -195,10 +195,11 @@ def test_wgrad_fp32_store_and_accumulate():
     assert int(flag.item()) == 1
 
 
-@pytest.mark.parametrize("K,N,B", [(512, 256, 128), (256, 768, 64), (1024, 512, 256), (4096, 2048, 64)])
+@pytest.mark.parametrize("K,N,B", [(512, 256, 128), (256, 768, 64), (1024, 512, 256), (4096, 2048, 64), (4096, 2048, 576)])
 def test_wgrad_fp32_whole_tiles(K, N, B):
     """FP32 store and accumulate with 16 bytes per lane: the general kernel on the small shapes, the streamed kernel's
-    FP32 epilogue on the last one (128 tiles of 256 x 256).  Integer data so that the sums are exact, then real data
+    FP32 epilogues on the last two (128 tiles of 256 x 256: one stage of the reduction on the two-wavefront-per-SIMD
+    kernel, nine on the depth-64 one).  Integer data so that the sums are exact, then real data
     against the oracle's allowance; the output is a column window of a wider buffer (row stride 8 floats longer than
     the matrix), and a planted Inf raises the flag."""
     rng = np.random.default_rng(K + N + B)
