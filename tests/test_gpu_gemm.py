@@ -299,6 +299,31 @@ def test_relu_folded_whole_tile_kernels():
         assert not got[mask <= 0].any()
 
 
+def test_relu_forms_through_a_split_reduction_of_whole_tiles():
+    """512 x 2048 outputs over a reduction of 8192: 16 tiles of 256 x 256, split 16 ways on the streamed kernel's FP32
+    partials; the ReLU and the backward mask are applied by the reduction, four columns per thread (mask rows 8-byte
+    aligned) or one (mask at an odd row stride)."""
+    M, N, K = 512, 2048, 8192
+    rng = np.random.default_rng(9)
+    X = rng.standard_normal((M, K)).astype(np.float16)
+    W = (rng.standard_normal((K, N)) * 0.02).astype(np.float16)
+    h, sa, s_ = gemm.gemm_fwd_relu(X, W, full=True)
+    H = torch.full((M, N), float("nan"), dtype=torch.float16, device="cuda")
+    mpt.mpt_gemm_fwd_relu(dev16(X), dev16(W), H, _ws(0, M, N, K))
+    gemm_check(host16(H), h, sa, s_, "fwd_relu, split")
+    dY = (np.exp2(rng.uniform(-20, -3, (M, K))) * rng.choice([-1, 1], (M, K))).astype(np.float16)   # reduce over K, output M x N
+    Wd = (rng.standard_normal((N, K)) * 0.05).astype(np.float16)
+    mask = np.maximum(rng.standard_normal((M, N)), 0).astype(np.float16)
+    dx, sa, s_ = gemm.gemm_dgrad_relu(dY, Wd, mask, full=True)
+    for pad in (0, 1):
+        mb = torch.zeros((M, N + pad), dtype=torch.float16, device="cuda"); mb[:, :N] = dev16(mask)
+        dX = torch.full((M, N), float("nan"), dtype=torch.float16, device="cuda")
+        mpt.mpt_gemm_dgrad_relu(dev16(dY), dev16(Wd), mb[:, :N], dX, _ws(1, M, K, N))
+        got = host16(dX)
+        gemm_check(got, dx, sa, s_, "dgrad_relu, split, mask pad %d" % pad)
+        assert not got[mask <= 0].any()
+
+
 def test_outputs_with_few_rows_and_many_columns():
     """384 x 16384 outputs (three 128-row tiles by 64 column tiles): the 128-row whole-tile kernel, in all three
     passes, with the folded ReLU forms and the overflow vote."""
